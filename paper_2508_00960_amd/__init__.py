@@ -1,0 +1,8 @@
+"""MI355X-native phantom-layer operators (forward, backward, training step).
+
+Thin binding over libphantom.so; see include/phantom.h for the contract.
+"""
+from .binding import (  # noqa: F401
+    ACTS, DTYPES, PhantomError, PhProblem, abi_version, ffn_step, layer_bwd, layer_fwd, last_error,
+    library_path, load, make_problem, workspace_bytes,
+)

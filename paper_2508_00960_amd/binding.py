@@ -1,0 +1,187 @@
+"""ctypes binding of libphantom.so: argument marshalling only.
+
+Every function has the name and argument order of its C entry point in
+include/phantom.h.  Tensor arguments are torch tensors on the GPU (their
+data_ptr() is passed), None (NULL), or plain integers (raw addresses, used by
+the host-only argument-validation tests).  Nothing is computed here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libphantom.so")
+
+ACTS = {"identity": 0, "relu": 1, "gelu": 2}
+DTYPES = {"f32": 0, "bf16": 1}
+
+PH_OK = 0
+
+
+class PhantomError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"libphantom status {status}: {message}")
+        self.status = status
+
+
+class PhProblem(ctypes.Structure):
+    _fields_ = [
+        ("n", ctypes.c_int64), ("p", ctypes.c_int64), ("k", ctypes.c_int64), ("batch", ctypes.c_int64),
+        ("layers", ctypes.c_int32), ("act", ctypes.c_int32), ("dtype", ctypes.c_int32), ("rank", ctypes.c_int32),
+    ]
+
+    @property
+    def s(self) -> int:
+        return self.n // self.p
+
+
+_PP = ctypes.POINTER(ctypes.c_void_p)
+
+
+class PhStepArgs(ctypes.Structure):
+    _fields_ = [
+        ("X0", ctypes.c_void_p), ("T", ctypes.c_void_p),
+        ("Lw", _PP), ("Cw", _PP), ("Dw", _PP), ("bias", _PP),
+        ("Lw_master", _PP), ("Cw_master", _PP), ("Dw_master", _PP), ("bias_master", _PP),
+        ("G", _PP), ("dg_own", _PP),
+        ("dLw", _PP), ("dCw", _PP), ("dDw", _PP), ("dbias", _PP),
+        ("Y_out", ctypes.c_void_p), ("loss", ctypes.c_void_p),
+        ("lr", ctypes.c_float), ("forward_only", ctypes.c_int32),
+    ]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Load libphantom.so.  It is never replaced by a fallback: a missing library is an error."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    import torch  # noqa: F401  (brings the HIP runtime the library links against into the process first)
+    if not os.path.exists(_LIB_PATH):
+        from .build import build_library
+        build_library(verbose=False)
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    prob = ctypes.POINTER(PhProblem)
+    lib.phantom_abi_version.restype = ctypes.c_int32
+    lib.phantom_last_error.restype = ctypes.c_char_p
+    lib.phantom_workspace_bytes.restype = ctypes.c_int
+    lib.phantom_workspace_bytes.argtypes = [prob, ctypes.POINTER(sz)]
+    lib.phantom_layer_fwd.restype = ctypes.c_int
+    lib.phantom_layer_fwd.argtypes = [prob] + [vp] * 9 + [vp, sz, vp]
+    lib.phantom_layer_bwd.restype = ctypes.c_int
+    lib.phantom_layer_bwd.argtypes = [prob] + [vp] * 14 + [vp, sz, vp]
+    lib.phantom_ffn_step.restype = ctypes.c_int
+    lib.phantom_ffn_step.argtypes = [prob, ctypes.POINTER(PhStepArgs), vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def abi_version() -> int:
+    return int(load().phantom_abi_version())
+
+
+def last_error() -> str:
+    return load().phantom_last_error().decode()
+
+
+def make_problem(n: int, p: int, k: int, batch: int, layers: int = 1, act: str = "relu", dtype: str = "f32",
+                 rank: int = 0) -> PhProblem:
+    return PhProblem(n, p, k, batch, layers, ACTS[act], DTYPES[dtype], rank)
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _nbytes(t) -> int:
+    if t is None:
+        return 0
+    if isinstance(t, tuple):
+        return t[1]
+    return t.numel() * t.element_size()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is not None:
+        return stream if isinstance(stream, int) else stream.cuda_stream
+    import torch
+    if torch.cuda.is_available():
+        return torch.cuda.current_stream().cuda_stream
+    return None
+
+
+def _check(status: int):
+    if status != PH_OK:
+        raise PhantomError(status, last_error())
+
+
+def _ws(workspace):
+    """workspace: a torch uint8 tensor, None, or (address, bytes)."""
+    if workspace is None:
+        return None, 0
+    if isinstance(workspace, tuple):
+        return workspace
+    return workspace.data_ptr(), workspace.numel() * workspace.element_size()
+
+
+def workspace_bytes(prob: PhProblem) -> int:
+    out = ctypes.c_size_t(0)
+    _check(load().phantom_workspace_bytes(ctypes.byref(prob), ctypes.byref(out)))
+    return int(out.value)
+
+
+def layer_fwd(prob, X, Lw, Cw, Dw, bias, G, Y, g_own, A_save, workspace=None, stream=None):
+    wp, wb = _ws(workspace)
+    _check(load().phantom_layer_fwd(ctypes.byref(prob), _ptr(X), _ptr(Lw), _ptr(Cw), _ptr(Dw), _ptr(bias), _ptr(G),
+                                    _ptr(Y), _ptr(g_own), _ptr(A_save), wp, wb, _stream(stream)))
+
+
+def layer_bwd(prob, dY, X, A_or_Y, Lw, Cw, Dw, G, dg_own, dX, dLw, dCw, dDw, dbias, dG_send, workspace=None,
+              stream=None):
+    wp, wb = _ws(workspace)
+    _check(load().phantom_layer_bwd(ctypes.byref(prob), _ptr(dY), _ptr(X), _ptr(A_or_Y), _ptr(Lw), _ptr(Cw), _ptr(Dw),
+                                    _ptr(G), _ptr(dg_own), _ptr(dX), _ptr(dLw), _ptr(dCw), _ptr(dDw), _ptr(dbias),
+                                    _ptr(dG_send), wp, wb, _stream(stream)))
+
+
+def _ptr_array(tensors: Optional[Sequence], layers: int):
+    if tensors is None:
+        return None, None
+    if len(tensors) != layers:
+        raise ValueError(f"expected {layers} per-layer tensors, got {len(tensors)}")
+    arr = (ctypes.c_void_p * layers)(*[_ptr(t) for t in tensors])
+    return ctypes.cast(arr, _PP), arr
+
+
+def ffn_step(prob, X0, T, Lw, Cw, Dw, bias, *, Lw_master=None, Cw_master=None, Dw_master=None, bias_master=None,
+             G=None, dg_own=None, dLw=None, dCw=None, dDw=None, dbias=None, Y_out=None, loss=None, lr=0.0,
+             forward_only=False, workspace=None, stream=None):
+    """phantom_ffn_step; per-layer arguments are sequences of prob.layers tensors (or None)."""
+    L = prob.layers
+    keep = []
+    args = PhStepArgs()
+    args.X0, args.T, args.Y_out, args.loss = _ptr(X0), _ptr(T), _ptr(Y_out), _ptr(loss)
+    for name, val in (("Lw", Lw), ("Cw", Cw), ("Dw", Dw), ("bias", bias), ("Lw_master", Lw_master),
+                      ("Cw_master", Cw_master), ("Dw_master", Dw_master), ("bias_master", bias_master),
+                      ("G", G), ("dg_own", dg_own), ("dLw", dLw), ("dCw", dCw), ("dDw", dDw), ("dbias", dbias)):
+        ptr, arr = _ptr_array(val, L)
+        keep.append(arr)
+        if ptr is not None:
+            setattr(args, name, ptr)
+    args.lr = float(lr)
+    args.forward_only = 1 if forward_only else 0
+    wp, wb = _ws(workspace)
+    _check(load().phantom_ffn_step(ctypes.byref(prob), ctypes.byref(args), wp, wb, _stream(stream)))

@@ -1,0 +1,146 @@
+// Memory-bound helpers of the phantom layer: local error, bias gradient,
+// in-memory reduce-scatter, MSE output error, SGD update.
+#pragma once
+#include "common.h"
+
+namespace phantom {
+
+// delta = dY * sigma'(S)   (Eq. (deltaL); the sigma' factor of Eq. (backprop)).
+// S is the pre-activation (any activation) or, for ReLU, the layer output.
+template <typename T>
+__global__ __launch_bounds__(256) void delta_kernel(const T *__restrict__ dY, const T *__restrict__ S,
+                                                   T *__restrict__ delta, int64_t count, int act)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) {
+        float d = to_f32(dY[i]);
+        if (act != ACT_IDENTITY) d *= act_deriv(act, to_f32(S[i]));
+        delta[i] = from_f32<T>(d);
+    }
+}
+
+// Column sums of delta [rows x cols] (Eq. (bpb): dLoss/db = sum over the batch of delta), two
+// deterministic passes: per-chunk partial sums, then their sum.
+constexpr int CS_COLS = 64;
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(const T *__restrict__ delta, float *__restrict__ partial,
+                                                            int rows, int cols, int rows_per_chunk)
+{
+    __shared__ float red[4][CS_COLS];
+    const int g = blockIdx.z, chunk = blockIdx.y;
+    const int col = blockIdx.x * CS_COLS + (threadIdx.x & (CS_COLS - 1));
+    const int lane_r = threadIdx.x / CS_COLS;
+    const T *d = delta + (int64_t)g * rows * cols;
+    const int r0 = chunk * rows_per_chunk;
+    const int r1 = min(rows, r0 + rows_per_chunk);
+    float acc = 0.f;
+    if (col < cols)
+        for (int r = r0 + lane_r; r < r1; r += 4) acc += to_f32(d[(int64_t)r * cols + col]);
+    red[lane_r][threadIdx.x & (CS_COLS - 1)] = acc;
+    __syncthreads();
+    if (lane_r == 0 && col < cols) {
+        float v = red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] + red[3][threadIdx.x];
+        partial[((int64_t)g * gridDim.y + chunk) * cols + col] = v;
+    }
+}
+
+__global__ __launch_bounds__(256) void colsum_final_kernel(const float *__restrict__ partial, float *__restrict__ out,
+                                                          int chunks, int cols, int groups)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= (int64_t)groups * cols) return;
+    const int g = (int)(i / cols), col = (int)(i % cols);
+    float acc = 0.f;
+    for (int c = 0; c < chunks; ++c) acc += partial[((int64_t)g * chunks + c) * cols + col];
+    out[i] = acc;
+}
+
+// In-memory Reduce-Scatter of Algorithm 1's backward: dg_own[i] = sum_{j != i} dG_send[j][slot of i on j].
+// dG_send [p, p-1, B*k], dg_own [p, B*k]; on holder j, source i sits in slot i (i < j) or i-1 (i > j).
+template <typename T>
+__global__ __launch_bounds__(256) void reduce_scatter_kernel(const T *__restrict__ dG_send, T *__restrict__ dg_own,
+                                                            int p, int64_t per_slot)
+{
+    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int i = blockIdx.y;
+    if (e >= per_slot) return;
+    float acc = 0.f;
+    for (int j = 0; j < p; ++j) {
+        if (j == i) continue;
+        const int slot = i < j ? i : i - 1;
+        acc += to_f32(dG_send[((int64_t)j * (p - 1) + slot) * per_slot + e]);
+    }
+    dg_own[(int64_t)i * per_slot + e] = from_f32<T>(acc);
+}
+
+// MSE output error (Section IV-B, "Local error at the output"): dY = (Y - T) / B and per-block partial
+// sums of (Y - T)^2; mse_final_kernel turns them into loss = 1/(2B) * sum.
+template <typename T>
+__global__ __launch_bounds__(256) void mse_kernel(const T *__restrict__ Y, const T *__restrict__ Tg,
+                                                 T *__restrict__ dY, int64_t count, float inv_b,
+                                                 float *__restrict__ partial)
+{
+    __shared__ float red[256];
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    float acc = 0.f;
+    for (; i < count; i += stride) {
+        float d = to_f32(Y[i]) - to_f32(Tg[i]);
+        acc += d * d;
+        dY[i] = from_f32<T>(d * inv_b);
+    }
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
+}
+
+__global__ __launch_bounds__(256) void mse_final_kernel(const float *__restrict__ partial, int n, float scale,
+                                                       float *__restrict__ loss)
+{
+    __shared__ float red[256];
+    float acc = 0.f;
+    for (int i = threadIdx.x; i < n; i += 256) acc += partial[i];
+    red[threadIdx.x] = acc;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *loss = red[0] * scale;
+}
+
+// SGD.  fp32 storage: w -= lr * g.  bf16 storage: master -= lr * g, w = bf16(master).
+__global__ __launch_bounds__(256) void sgd_f32_kernel(float *__restrict__ w, const float *__restrict__ g, float lr,
+                                                     int64_t count)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) w[i] = w[i] - lr * g[i];
+}
+
+__global__ __launch_bounds__(256) void sgd_bf16_kernel(float *__restrict__ master, bf16_t *__restrict__ w,
+                                                      const float *__restrict__ g, float lr, int64_t count)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) {
+        float m = master[i] - lr * g[i];
+        master[i] = m;
+        w[i] = from_f32<bf16_t>(m);
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void copy_kernel(const T *__restrict__ src, T *__restrict__ dst, int64_t count)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) dst[i] = src[i];
+}
+
+}  // namespace phantom

@@ -1,0 +1,494 @@
+// C ABI of libphantom.so: argument checks, workspace layout, and the sequence of
+// kernel launches that makes up each operator of the phantom layer.
+// Declarations and the meaning of every argument: include/phantom.h.
+#include "../../include/phantom.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "common.h"
+#include "elementwise.h"
+#include "gemm_generic.h"
+#include "views.h"
+
+using namespace phantom;
+
+namespace {
+
+thread_local std::string g_err;
+
+ph_status fail(ph_status st, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return st;
+}
+
+struct Geo {
+    int64_t n, p, k, B, s, q, Kc;
+    int groups;       // ranks held on this GPU: 1 or p
+    bool all;         // all-ranks mode
+    int act, dtype, rank, layers;
+    size_t esz;       // bytes per element of the storage type
+};
+
+ph_status make_geo(const ph_problem *pr, Geo &g)
+{
+    if (!pr) return fail(PH_ERR_INVALID_ARG, "problem is NULL");
+    if (pr->p < 1) return fail(PH_ERR_INVALID_ARG, "p = %lld must be >= 1", (long long)pr->p);
+    if (pr->n < 1 || pr->n % pr->p) return fail(PH_ERR_INVALID_ARG, "n = %lld must be a positive multiple of p = %lld",
+                                                (long long)pr->n, (long long)pr->p);
+    if (pr->batch < 1) return fail(PH_ERR_INVALID_ARG, "batch = %lld must be >= 1", (long long)pr->batch);
+    const int64_t s = pr->n / pr->p;
+    if (pr->p > 1 && (pr->k < 1 || pr->k > s))
+        return fail(PH_ERR_INVALID_ARG, "k = %lld must lie in [1, n/p = %lld]", (long long)pr->k, (long long)s);
+    if (pr->act < PH_ACT_IDENTITY || pr->act > PH_ACT_GELU) return fail(PH_ERR_INVALID_ARG, "unknown activation %d", pr->act);
+    if (pr->dtype != PH_F32 && pr->dtype != PH_BF16) return fail(PH_ERR_INVALID_ARG, "unknown dtype %d", pr->dtype);
+    if (pr->rank < -1 || pr->rank >= pr->p) return fail(PH_ERR_INVALID_ARG, "rank = %d must lie in [-1, p)", pr->rank);
+    if (pr->layers < 1) return fail(PH_ERR_INVALID_ARG, "layers = %d must be >= 1", pr->layers);
+    g.n = pr->n; g.p = pr->p; g.B = pr->batch; g.s = s; g.q = pr->p - 1;
+    g.k = g.q > 0 ? pr->k : 0;
+    g.Kc = s + g.q * g.k;
+    g.all = pr->rank < 0;
+    g.groups = g.all ? (int)pr->p : 1;
+    g.act = pr->act; g.dtype = pr->dtype; g.rank = pr->rank; g.layers = pr->layers;
+    g.esz = pr->dtype == PH_BF16 ? 2 : 4;
+    // index arithmetic inside the kernels uses 32-bit row/column numbers and a 3-D grid
+    if (g.B > (1 << 22) || g.s > (1 << 22) || g.Kc > (1 << 24) || g.p > 65535)
+        return fail(PH_ERR_UNSUPPORTED, "problem too large for 32-bit tile indices (batch, n/p <= 2^22, n/p+(p-1)k <= 2^24)");
+    return PH_OK;
+}
+
+ph_status need(const void *p, const char *name)
+{
+    if (!p) return fail(PH_ERR_INVALID_ARG, "%s is NULL", name);
+    if ((uintptr_t)p & 15) return fail(PH_ERR_INVALID_ARG, "%s is not 16-byte aligned", name);
+    return PH_OK;
+}
+ph_status optional(const void *p, const char *name)
+{
+    if (p && ((uintptr_t)p & 15)) return fail(PH_ERR_INVALID_ARG, "%s is not 16-byte aligned", name);
+    return PH_OK;
+}
+#define PH_TRY(expr) do { ph_status st__ = (expr); if (st__ != PH_OK) return st__; } while (0)
+
+ph_status check_launch(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(PH_ERR_LAUNCH, "%s: %s", what, hipGetErrorString(e));
+    return PH_OK;
+}
+
+// ---- workspace ---------------------------------------------------------------
+struct Arena {
+    char *base;
+    size_t used;
+    void *take(size_t bytes)
+    {
+        size_t at = (used + 255) & ~(size_t)255;
+        used = at + bytes;
+        return base ? base + at : nullptr;
+    }
+};
+
+constexpr int COLSUM_ROWS = 256;   // rows per partial sum of the bias gradient
+constexpr int MSE_BLOCKS = 1024;
+
+struct BwdWs {
+    void *delta;        // [groups, B, s] storage type
+    float *colsum;      // [groups, chunks, s]
+    int chunks;
+};
+
+BwdWs carve_bwd(Arena &a, const Geo &g)
+{
+    BwdWs w;
+    w.chunks = (int)((g.B + COLSUM_ROWS - 1) / COLSUM_ROWS);
+    w.delta = a.take((size_t)g.groups * g.B * g.s * g.esz);
+    w.colsum = (float *)a.take((size_t)g.groups * w.chunks * g.s * sizeof(float));
+    return w;
+}
+
+struct StepWs {
+    std::vector<void *> Y, A, G;
+    void *dYa, *dYb, *dG_send, *dg_own;
+    float *dLw, *dCw, *dDw, *dbias, *mse_partial;
+    BwdWs bwd;
+};
+
+StepWs carve_step(Arena &a, const Geo &g)
+{
+    StepWs w;
+    const size_t act_bytes = (size_t)g.groups * g.B * g.s * g.esz;
+    const size_t gath_bytes = (size_t)g.groups * g.B * g.k * g.esz;   // all-ranks: [p,B,k]; one-rank: [B,k]
+    for (int l = 0; l < g.layers; ++l) {
+        w.Y.push_back(a.take(act_bytes));
+        w.A.push_back(g.act == PH_ACT_GELU ? a.take(act_bytes) : nullptr);
+        w.G.push_back(g.q > 0 ? a.take(gath_bytes) : nullptr);
+    }
+    w.dYa = a.take(act_bytes);
+    w.dYb = a.take(act_bytes);
+    w.dG_send = g.q > 0 ? a.take((size_t)g.groups * g.q * g.B * g.k * g.esz) : nullptr;
+    w.dg_own = g.q > 0 ? a.take(gath_bytes) : nullptr;
+    w.dLw = (float *)a.take((size_t)g.groups * g.s * g.s * 4);
+    w.dCw = (float *)a.take((size_t)g.groups * g.k * g.s * 4 + 16);
+    w.dDw = (float *)a.take((size_t)g.groups * g.q * g.s * g.k * 4 + 16);
+    w.dbias = (float *)a.take((size_t)g.groups * g.s * 4);
+    w.mse_partial = (float *)a.take(MSE_BLOCKS * sizeof(float));
+    w.bwd = carve_bwd(a, g);
+    return w;
+}
+
+// ---- one product ---------------------------------------------------------------
+template <typename TIn, typename TOut>
+ph_status launch_gemm(const View &a, const View &b, const View &o, const Epilogue &ep,
+                      int64_t M, int64_t N, int64_t K, int groups, hipStream_t st, const char *what)
+{
+    if (M <= 0 || N <= 0 || groups <= 0) return PH_OK;
+    dim3 grid((unsigned)((N + GT - 1) / GT), (unsigned)((M + GT - 1) / GT), (unsigned)groups);
+    hipLaunchKernelGGL((gemm_generic_kernel<TIn, TOut>), grid, dim3(256), 0, st, a, b, o, ep, (int)M, (int)N, (int)K);
+    return check_launch(what);
+}
+
+Epilogue epi_store()
+{
+    Epilogue e{};
+    e.mode = EPI_STORE;
+    return e;
+}
+
+inline unsigned blocks_for(int64_t count, int per_block = 256, int cap = 8192)
+{
+    int64_t b = (count + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    if (b > cap) b = cap;
+    return (unsigned)b;
+}
+
+// ---- forward of one layer (Eq. (ylq)) ------------------------------------------------
+struct FwdArgs {
+    const void *X, *Lw, *Cw, *Dw, *bias, *G;
+    void *Y, *g_own, *A_save;
+};
+
+template <typename T>
+ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
+{
+    const int64_t B = g.B, s = g.s, k = g.k, q = g.q;
+    if (q > 0) {
+        // compression g = C y: [B, s] x [k, s]^T -> [B, k]
+        PH_TRY((launch_gemm<T, T>(view_plain(f.X, s, B * s), view_plain(f.Cw, s, k * s), view_plain(f.g_own, k, B * k),
+                                  epi_store(), B, k, s, g.groups, st, "compression")));
+    }
+    // local update + decompression + remote update + bias + activation: one product over the
+    // concatenated reduction index [y | g_1 .. g_{p-1}] . [L | D_1 .. D_{p-1}]^T
+    const void *gathered = g.all ? f.g_own : f.G;
+    View va = q > 0 ? view_rowseg(f.X, s, (int)s, B * s, gathered, (int)k, B * k, 0, g.all ? 0 : NO_SKIP, g.all ? 1 : 0)
+                    : view_plain(f.X, s, B * s);
+    View vb = q > 0 ? view_rowseg(f.Lw, s, (int)s, s * s, f.Dw, (int)k, s * k, q * s * k) : view_plain(f.Lw, s, s * s);
+    Epilogue ep{};
+    ep.mode = EPI_BIAS_ACT; ep.act = g.act; ep.bias = f.bias; ep.bias_g = s;
+    ep.aux = f.A_save; ep.aux_ld = s; ep.aux_g = B * s;
+    return launch_gemm<T, T>(va, vb, view_plain(f.Y, s, B * s), ep, B, s, g.Kc, g.groups, st, "layer update");
+}
+
+// ---- backward of one layer (Eq. (deltaL), (backprop), (bpb)-(bpD)) ---------------------------
+struct BwdArgs {
+    const void *dY, *X, *S, *Lw, *Cw, *Dw, *G;
+    void *dg_own;
+    void *dX;
+    float *dLw, *dCw, *dDw, *dbias;
+    void *dG_send;
+};
+
+template <typename T>
+ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t st)
+{
+    const int64_t B = g.B, s = g.s, k = g.k, q = g.q;
+    const int64_t act_count = (int64_t)g.groups * B * s;
+
+    // local error delta = dY * sigma'
+    hipLaunchKernelGGL((delta_kernel<T>), dim3(blocks_for(act_count)), dim3(256), 0, st,
+                       (const T *)b.dY, (const T *)b.S, (T *)w.delta, act_count, g.act);
+    PH_TRY(check_launch("local error"));
+
+    // bias gradient: column sums of delta
+    {
+        dim3 grid((unsigned)((s + CS_COLS - 1) / CS_COLS), (unsigned)w.chunks, (unsigned)g.groups);
+        hipLaunchKernelGGL((colsum_partial_kernel<T>), grid, dim3(256), 0, st, (const T *)w.delta, w.colsum,
+                           (int)B, (int)s, COLSUM_ROWS);
+        PH_TRY(check_launch("bias gradient (partial)"));
+        hipLaunchKernelGGL(colsum_final_kernel, dim3(blocks_for((int64_t)g.groups * s)), dim3(256), 0, st,
+                           (const float *)w.colsum, b.dbias, w.chunks, (int)s, g.groups);
+        PH_TRY(check_launch("bias gradient"));
+    }
+
+    if (q > 0) {
+        // error compression: dG_send[i] = delta . D_i   ([B, s] x [s, k] for every peer, one product over N = q*k)
+        View vb{};
+        vb.p0 = nullptr; vb.p1 = const_cast<void *>(b.Dw); vb.g0 = 0; vb.g1 = q * s * k;
+        vb.r = axis_seg(0, (int)k, 0, 1, s * k); vb.c = axis_plain(0, k);
+        vb.skip0 = NO_SKIP; vb.skip_g = 0;
+        View vo{};
+        vo.p0 = nullptr; vo.p1 = b.dG_send; vo.g0 = 0; vo.g1 = q * B * k;
+        vo.r = axis_plain(0, k); vo.c = axis_seg(0, (int)k, 0, 1, B * k);
+        vo.skip0 = NO_SKIP; vo.skip_g = 0;
+        PH_TRY((launch_gemm<T, T>(view_plain(w.delta, s, B * s), vb, vo, epi_store(), B, q * k, s, g.groups, st,
+                                  "error compression")));
+        if (g.all) {
+            const int64_t per_slot = B * k;
+            dim3 grid((unsigned)((per_slot + 255) / 256), (unsigned)g.p);
+            hipLaunchKernelGGL((reduce_scatter_kernel<T>), grid, dim3(256), 0, st, (const T *)b.dG_send, (T *)b.dg_own,
+                               (int)g.p, per_slot);
+            PH_TRY(check_launch("reduce-scatter"));
+        }
+    }
+
+    if (b.dX) {
+        // dX = delta . L + dg_own . C: reduction index = [delta | dg_own] against [L ; C]
+        View va = q > 0 ? view_rowseg(w.delta, s, (int)s, B * s, b.dg_own, (int)k, 0, B * k) : view_plain(w.delta, s, B * s);
+        View vb = q > 0 ? view_colstack(b.Lw, s, (int)s, s * s, b.Cw, s, (int)k, k * s) : view_plain_t(b.Lw, s, s * s);
+        PH_TRY((launch_gemm<T, T>(va, vb, view_plain(b.dX, s, B * s), epi_store(), B, s, s + k, g.groups, st,
+                                  "input gradient")));
+    }
+
+    // weight gradients: [dL | dD_1 .. dD_{p-1}] = delta^T . [X | G_1 .. G_{p-1}]
+    {
+        View va = view_plain_t(w.delta, s, B * s);
+        View vb = q > 0 ? view_rowseg_t(b.X, s, (int)s, B * s, b.G, (int)k, B * k, 0, g.all ? 0 : NO_SKIP, g.all ? 1 : 0)
+                        : view_plain_t(b.X, s, B * s);
+        View vo{};
+        vo.p0 = b.dLw; vo.p1 = b.dDw; vo.g0 = s * s; vo.g1 = q * s * k;
+        vo.r = axis_plain(s, k);
+        vo.c = q > 0 ? axis_seg((int)s, (int)k, 1, 1, s * k) : axis_plain(1, 0);
+        vo.skip0 = NO_SKIP; vo.skip_g = 0;
+        PH_TRY((launch_gemm<T, float>(va, vb, vo, epi_store(), s, g.Kc, B, g.groups, st, "weight gradients")));
+    }
+    if (q > 0) {
+        // dC = dg_own^T . X
+        PH_TRY((launch_gemm<T, float>(view_plain_t(b.dg_own, k, B * k), view_plain_t(b.X, s, B * s),
+                                      view_plain(b.dCw, s, k * s), epi_store(), k, s, B, g.groups, st,
+                                      "compressor gradient")));
+    }
+    return PH_OK;
+}
+
+ph_status check_fwd_args(const Geo &g, const FwdArgs &f)
+{
+    PH_TRY(need(f.X, "X")); PH_TRY(need(f.Lw, "Lw")); PH_TRY(need(f.bias, "bias")); PH_TRY(need(f.Y, "Y"));
+    PH_TRY(optional(f.A_save, "A_save"));
+    if (g.q > 0) {
+        PH_TRY(need(f.Cw, "Cw")); PH_TRY(need(f.Dw, "Dw")); PH_TRY(need(f.g_own, "g_own"));
+        if (!g.all) PH_TRY(need(f.G, "G"));
+    }
+    return PH_OK;
+}
+
+ph_status check_bwd_args(const Geo &g, const BwdArgs &b)
+{
+    PH_TRY(need(b.dY, "dY")); PH_TRY(need(b.X, "X")); PH_TRY(need(b.Lw, "Lw"));
+    if (g.act != PH_ACT_IDENTITY) PH_TRY(need(b.S, "A_or_Y"));
+    PH_TRY(optional(b.dX, "dX"));
+    PH_TRY(need(b.dLw, "dLw")); PH_TRY(need(b.dbias, "dbias"));
+    if (g.q > 0) {
+        PH_TRY(need(b.Cw, "Cw")); PH_TRY(need(b.Dw, "Dw")); PH_TRY(need(b.G, "G")); PH_TRY(need(b.dg_own, "dg_own"));
+        PH_TRY(need(b.dCw, "dCw")); PH_TRY(need(b.dDw, "dDw")); PH_TRY(need(b.dG_send, "dG_send"));
+    }
+    return PH_OK;
+}
+
+ph_status check_ws(void *ws, size_t have, size_t want)
+{
+    if (want == 0) return PH_OK;
+    if (!ws) return fail(PH_ERR_WORKSPACE, "workspace is NULL, %zu bytes needed", want);
+    if ((uintptr_t)ws & 255) return fail(PH_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+    if (have < want) return fail(PH_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", have, want);
+    return PH_OK;
+}
+
+template <typename T>
+ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStream_t st)
+{
+    const int L = g.layers;
+    const int64_t B = g.B, s = g.s, k = g.k, q = g.q;
+    const int64_t act_count = (int64_t)g.groups * B * s;
+
+    // forward through every layer; y_l stays in the storage type between layers
+    const void *in = a.X0;
+    std::vector<const void *> inputs(L);
+    for (int l = 0; l < L; ++l) {
+        inputs[l] = in;
+        FwdArgs f{in, a.Lw[l], q ? a.Cw[l] : nullptr, q ? a.Dw[l] : nullptr, a.bias[l],
+                  (q && !g.all) ? a.G[l] : nullptr, w.Y[l], w.G[l], w.A[l]};
+        PH_TRY(fwd_impl<T>(g, f, st));
+        in = w.Y[l];
+    }
+    if (a.Y_out) {
+        hipLaunchKernelGGL((copy_kernel<T>), dim3(blocks_for(act_count)), dim3(256), 0, st, (const T *)w.Y[L - 1],
+                           (T *)a.Y_out, act_count);
+        PH_TRY(check_launch("output copy"));
+    }
+    if (a.forward_only) return PH_OK;
+
+    // output error of the MSE loss
+    const unsigned mse_blocks = blocks_for(act_count, 256, MSE_BLOCKS);
+    hipLaunchKernelGGL((mse_kernel<T>), dim3(mse_blocks), dim3(256), 0, st, (const T *)w.Y[L - 1], (const T *)a.T,
+                       (T *)w.dYa, act_count, 1.0f / (float)B, w.mse_partial);
+    PH_TRY(check_launch("output error"));
+    hipLaunchKernelGGL(mse_final_kernel, dim3(1), dim3(256), 0, st, (const float *)w.mse_partial, (int)mse_blocks,
+                       0.5f / (float)B, a.loss);
+    PH_TRY(check_launch("loss"));
+
+    void *dY = w.dYa, *dX = w.dYb;
+    for (int l = L - 1; l >= 0; --l) {
+        BwdArgs b{};
+        b.dY = dY; b.X = inputs[l]; b.S = g.act == PH_ACT_GELU ? w.A[l] : w.Y[l];
+        b.Lw = a.Lw[l]; b.Cw = q ? a.Cw[l] : nullptr; b.Dw = q ? a.Dw[l] : nullptr;
+        b.G = q ? (g.all ? w.G[l] : a.G[l]) : nullptr;
+        b.dg_own = q ? (g.all ? w.dg_own : const_cast<void *>(a.dg_own[l])) : nullptr;
+        b.dX = l > 0 ? dX : nullptr;
+        b.dLw = a.dLw ? a.dLw[l] : w.dLw;
+        b.dCw = q ? (a.dCw ? a.dCw[l] : w.dCw) : nullptr;
+        b.dDw = q ? (a.dDw ? a.dDw[l] : w.dDw) : nullptr;
+        b.dbias = a.dbias ? a.dbias[l] : w.dbias;
+        b.dG_send = w.dG_send;
+        PH_TRY(bwd_impl<T>(g, b, w.bwd, st));
+
+        // SGD on this layer: nothing later in the backward pass reads its weights
+        struct Upd { void *w; float *master; const float *grad; int64_t count; };
+        Upd upd[4] = {
+            {a.Lw[l], a.Lw_master ? a.Lw_master[l] : nullptr, b.dLw, (int64_t)g.groups * s * s},
+            {a.bias[l], a.bias_master ? a.bias_master[l] : nullptr, b.dbias, (int64_t)g.groups * s},
+            {q ? a.Cw[l] : nullptr, (q && a.Cw_master) ? a.Cw_master[l] : nullptr, b.dCw, (int64_t)g.groups * k * s},
+            {q ? a.Dw[l] : nullptr, (q && a.Dw_master) ? a.Dw_master[l] : nullptr, b.dDw, (int64_t)g.groups * q * s * k},
+        };
+        for (const Upd &u : upd) {
+            if (!u.w || u.count == 0) continue;
+            if (g.dtype == PH_F32)
+                hipLaunchKernelGGL(sgd_f32_kernel, dim3(blocks_for(u.count)), dim3(256), 0, st, (float *)u.w, u.grad, a.lr,
+                                   u.count);
+            else
+                hipLaunchKernelGGL(sgd_bf16_kernel, dim3(blocks_for(u.count)), dim3(256), 0, st, u.master, (bf16_t *)u.w,
+                                   u.grad, a.lr, u.count);
+            PH_TRY(check_launch("SGD update"));
+        }
+        void *t = dY; dY = dX; dX = t;
+    }
+    return PH_OK;
+}
+
+ph_status check_ptr_array(const void *const *arr, int L, const char *name)
+{
+    if (!arr) return fail(PH_ERR_INVALID_ARG, "%s (host array of device pointers) is NULL", name);
+    for (int l = 0; l < L; ++l) {
+        char nm[64];
+        snprintf(nm, sizeof nm, "%s[%d]", name, l);
+        PH_TRY(need(arr[l], nm));
+    }
+    return PH_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t phantom_abi_version(void) { return 1; }
+
+const char *phantom_last_error(void) { return g_err.c_str(); }
+
+ph_status phantom_workspace_bytes(const ph_problem *prob, size_t *bytes)
+{
+    Geo g;
+    PH_TRY(make_geo(prob, g));
+    if (!bytes) return fail(PH_ERR_INVALID_ARG, "bytes is NULL");
+    Arena a{nullptr, 0};
+    carve_step(a, g);          // the step's layout contains the backward's; the forward needs none
+    *bytes = a.used + 256;
+    return PH_OK;
+}
+
+ph_status phantom_layer_fwd(const ph_problem *prob, const void *X, const void *Lw, const void *Cw, const void *Dw,
+                            const void *bias, const void *G, void *Y, void *g_own, void *A_save,
+                            void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    Geo g;
+    PH_TRY(make_geo(prob, g));
+    FwdArgs f{X, Lw, Cw, Dw, bias, G, Y, g_own, A_save};
+    PH_TRY(check_fwd_args(g, f));
+    hipStream_t st = (hipStream_t)hip_stream;
+    return g.dtype == PH_F32 ? fwd_impl<float>(g, f, st) : fwd_impl<bf16_t>(g, f, st);
+}
+
+ph_status phantom_layer_bwd(const ph_problem *prob, const void *dY, const void *X, const void *A_or_Y,
+                            const void *Lw, const void *Cw, const void *Dw, const void *G, void *dg_own,
+                            void *dX, float *dLw, float *dCw, float *dDw, float *dbias, void *dG_send,
+                            void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    Geo g;
+    PH_TRY(make_geo(prob, g));
+    BwdArgs b{dY, X, A_or_Y, Lw, Cw, Dw, G, dg_own, dX, dLw, dCw, dDw, dbias, dG_send};
+    PH_TRY(check_bwd_args(g, b));
+    Arena sizing{nullptr, 0};
+    carve_bwd(sizing, g);
+    PH_TRY(check_ws(workspace, workspace_bytes, sizing.used));
+    Arena a{(char *)workspace, 0};
+    BwdWs w = carve_bwd(a, g);
+    hipStream_t st = (hipStream_t)hip_stream;
+    return g.dtype == PH_F32 ? bwd_impl<float>(g, b, w, st) : bwd_impl<bf16_t>(g, b, w, st);
+}
+
+ph_status phantom_ffn_step(const ph_problem *prob, const ph_step_args *args, void *workspace, size_t workspace_bytes,
+                           void *hip_stream)
+{
+    Geo g;
+    PH_TRY(make_geo(prob, g));
+    if (!args) return fail(PH_ERR_INVALID_ARG, "args is NULL");
+    const int L = g.layers;
+    const bool train = !args->forward_only;
+    PH_TRY(need(args->X0, "X0"));
+    PH_TRY(check_ptr_array((const void *const *)args->Lw, L, "Lw"));
+    PH_TRY(check_ptr_array((const void *const *)args->bias, L, "bias"));
+    if (g.q > 0) {
+        PH_TRY(check_ptr_array((const void *const *)args->Cw, L, "Cw"));
+        PH_TRY(check_ptr_array((const void *const *)args->Dw, L, "Dw"));
+        if (!g.all) {
+            PH_TRY(check_ptr_array(args->G, L, "G"));
+            if (train) PH_TRY(check_ptr_array(args->dg_own, L, "dg_own"));
+        }
+    }
+    PH_TRY(optional(args->Y_out, "Y_out"));
+    if (train) {
+        PH_TRY(need(args->T, "T"));
+        if (!args->loss) return fail(PH_ERR_INVALID_ARG, "loss is NULL");
+        if (g.dtype == PH_BF16) {
+            PH_TRY(check_ptr_array((const void *const *)args->Lw_master, L, "Lw_master"));
+            PH_TRY(check_ptr_array((const void *const *)args->bias_master, L, "bias_master"));
+            if (g.q > 0) {
+                PH_TRY(check_ptr_array((const void *const *)args->Cw_master, L, "Cw_master"));
+                PH_TRY(check_ptr_array((const void *const *)args->Dw_master, L, "Dw_master"));
+            }
+        }
+        if (args->dLw) PH_TRY(check_ptr_array((const void *const *)args->dLw, L, "dLw"));
+        if (args->dbias) PH_TRY(check_ptr_array((const void *const *)args->dbias, L, "dbias"));
+        if (g.q > 0 && args->dCw) PH_TRY(check_ptr_array((const void *const *)args->dCw, L, "dCw"));
+        if (g.q > 0 && args->dDw) PH_TRY(check_ptr_array((const void *const *)args->dDw, L, "dDw"));
+    }
+    Arena sizing{nullptr, 0};
+    carve_step(sizing, g);
+    PH_TRY(check_ws(workspace, workspace_bytes, sizing.used));
+    Arena a{(char *)workspace, 0};
+    StepWs w = carve_step(a, g);
+    hipStream_t st = (hipStream_t)hip_stream;
+    return g.dtype == PH_F32 ? step_impl<float>(g, *args, w, st) : step_impl<bf16_t>(g, *args, w, st);
+}
+
+}  // extern "C"
