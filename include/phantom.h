@@ -119,13 +119,19 @@ ph_status phantom_layer_bwd(const ph_problem *prob,
                             void *dG_send,
                             void *workspace, size_t workspace_bytes, void *hip_stream);
 
+typedef enum {
+    PH_STEP_TRAIN = 0,      /* forward, loss, backward, SGD update */
+    PH_STEP_FORWARD = 1,    /* inference: forward only; T, loss, masters, G-gradients unused */
+    PH_STEP_NO_UPDATE = 2   /* forward, loss, backward; gradients are produced, weights are left alone */
+} ph_step_mode;
+
 /*
  * Arguments of phantom_ffn_step.  The arrays are HOST arrays of prob->layers
  * DEVICE pointers, read during the call.
  */
 typedef struct {
     const void *X0;            /* [B, s] network input (the rank's columns) */
-    const void *T;             /* [B, s] target; may be NULL when forward_only */
+    const void *T;             /* [B, s] target; may be NULL with PH_STEP_FORWARD */
     void *const *Lw;           /* compute weights in storage type, updated in place */
     void *const *Cw;
     void *const *Dw;
@@ -143,7 +149,7 @@ typedef struct {
     void *Y_out;               /* optional: network output [B, s], storage type */
     float *loss;               /* device scalar: 1/(2B) sum (y_L - t)^2 over batch, features and ranks held */
     float lr;                  /* SGD: w <- w - lr * dLoss/dw, all gradients taken before the update */
-    int32_t forward_only;      /* 1: inference; no loss, no backward, no update */
+    int32_t mode;              /* ph_step_mode */
 } ph_step_args;
 
 /*
@@ -151,8 +157,9 @@ typedef struct {
  * through every layer (Eq. (ylq)), MSE output error dLoss/dy_L = (y_L - t)/B
  * (Section IV-B, "Local error at the output", averaged over the batch),
  * backward through every layer (Eq. (backprop), (bpb)-(bpD)) and a plain SGD
- * update.  Equivalent to chaining phantom_layer_fwd / phantom_layer_bwd with
- * the tensors between layers kept in the storage type.
+ * update.  Between layers, y_l and delta_l = dLoss/dz_l are kept in the storage
+ * type; delta_l is formed as (L^T delta + C^T dg_own) * sigma_l' and rounded once,
+ * as Eq. (backprop) writes it (dLoss/dy_l itself is never stored).
  */
 ph_status phantom_ffn_step(const ph_problem *prob, const ph_step_args *args,
                            void *workspace, size_t workspace_bytes, void *hip_stream);

@@ -16,6 +16,7 @@ _LIB_PATH = os.path.join(_HERE, "libphantom.so")
 
 ACTS = {"identity": 0, "relu": 1, "gelu": 2}
 DTYPES = {"f32": 0, "bf16": 1}
+STEP_MODES = {"train": 0, "forward": 1, "no_update": 2}
 
 PH_OK = 0
 
@@ -48,7 +49,7 @@ class PhStepArgs(ctypes.Structure):
         ("G", _PP), ("dg_own", _PP),
         ("dLw", _PP), ("dCw", _PP), ("dDw", _PP), ("dbias", _PP),
         ("Y_out", ctypes.c_void_p), ("loss", ctypes.c_void_p),
-        ("lr", ctypes.c_float), ("forward_only", ctypes.c_int32),
+        ("lr", ctypes.c_float), ("mode", ctypes.c_int32),
     ]
 
 
@@ -168,7 +169,7 @@ def _ptr_array(tensors: Optional[Sequence], layers: int):
 
 def ffn_step(prob, X0, T, Lw, Cw, Dw, bias, *, Lw_master=None, Cw_master=None, Dw_master=None, bias_master=None,
              G=None, dg_own=None, dLw=None, dCw=None, dDw=None, dbias=None, Y_out=None, loss=None, lr=0.0,
-             forward_only=False, workspace=None, stream=None):
+             mode="train", workspace=None, stream=None):
     """phantom_ffn_step; per-layer arguments are sequences of prob.layers tensors (or None)."""
     L = prob.layers
     keep = []
@@ -182,6 +183,6 @@ def ffn_step(prob, X0, T, Lw, Cw, Dw, bias, *, Lw_master=None, Cw_master=None, D
         if ptr is not None:
             setattr(args, name, ptr)
     args.lr = float(lr)
-    args.forward_only = 1 if forward_only else 0
+    args.mode = STEP_MODES[mode]
     wp, wb = _ws(workspace)
     _check(load().phantom_ffn_step(ctypes.byref(prob), ctypes.byref(args), wp, wb, _stream(stream)))

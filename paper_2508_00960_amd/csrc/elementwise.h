@@ -74,12 +74,14 @@ __global__ __launch_bounds__(256) void reduce_scatter_kernel(const T *__restrict
     dg_own[(int64_t)i * per_slot + e] = from_f32<T>(acc);
 }
 
-// MSE output error (Section IV-B, "Local error at the output"): dY = (Y - T) / B and per-block partial
-// sums of (Y - T)^2; mse_final_kernel turns them into loss = 1/(2B) * sum.
+// MSE output error (Section IV-B, "Local error at the output", Eq. (deltaL)):
+// delta_L = ((Y - T) / B) * sigma'(S) with one rounding, and per-block partial sums of (Y - T)^2;
+// mse_final_kernel turns them into loss = 1/(2B) * sum.  S: pre-activation, or the output for ReLU.
 template <typename T>
-__global__ __launch_bounds__(256) void mse_kernel(const T *__restrict__ Y, const T *__restrict__ Tg,
-                                                 T *__restrict__ dY, int64_t count, float inv_b,
-                                                 float *__restrict__ partial)
+__global__ __launch_bounds__(256) void mse_delta_kernel(const T *__restrict__ Y, const T *__restrict__ Tg,
+                                                       const void *__restrict__ S, int s_f32, T *__restrict__ delta,
+                                                       int64_t count, float inv_b, int act,
+                                                       float *__restrict__ partial)
 {
     __shared__ float red[256];
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -88,7 +90,9 @@ __global__ __launch_bounds__(256) void mse_kernel(const T *__restrict__ Y, const
     for (; i < count; i += stride) {
         float d = to_f32(Y[i]) - to_f32(Tg[i]);
         acc += d * d;
-        dY[i] = from_f32<T>(d * inv_b);
+        float e = d * inv_b;
+        if (act != ACT_IDENTITY) e *= act_deriv(act, s_f32 ? ((const float *)S)[i] : to_f32(((const T *)S)[i]));
+        delta[i] = from_f32<T>(e);
     }
     red[threadIdx.x] = acc;
     __syncthreads();

@@ -20,6 +20,7 @@ struct Epilogue {
     void *aux;           // EPI_BIAS_ACT: optional pre-activation out; EPI_DACT: pre-activation (or ReLU output) in
     int64_t aux_ld;      //   plain row-major [M x N]
     int64_t aux_g;
+    int32_t aux_f32;     // aux holds float instead of the storage type
 };
 
 constexpr int GT = 64;   // tile edge
@@ -101,10 +102,14 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(View va, View vb, Vie
             float v = acc[i][j];
             if (ep.mode == EPI_BIAS_ACT) {
                 v += to_f32(((const TIn *)ep.bias + g * ep.bias_g)[n]);
-                if (ep.aux) ((TIn *)ep.aux + g * ep.aux_g)[(int64_t)m * ep.aux_ld + n] = from_f32<TIn>(v);
+                if (ep.aux) {
+                    const int64_t at = g * ep.aux_g + (int64_t)m * ep.aux_ld + n;
+                    if (ep.aux_f32) ((float *)ep.aux)[at] = v; else ((TIn *)ep.aux)[at] = from_f32<TIn>(v);
+                }
                 v = act_apply(ep.act, v);
             } else if (ep.mode == EPI_DACT) {
-                float a = to_f32(((const TIn *)ep.aux + g * ep.aux_g)[(int64_t)m * ep.aux_ld + n]);
+                const int64_t at = g * ep.aux_g + (int64_t)m * ep.aux_ld + n;
+                float a = ep.aux_f32 ? ((const float *)ep.aux)[at] : to_f32(((const TIn *)ep.aux)[at]);
                 v *= act_deriv(ep.act, a);
             }
             (reg ? o1 : o0)[off] = from_f32<TOut>(v);

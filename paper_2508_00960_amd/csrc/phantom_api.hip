@@ -131,7 +131,7 @@ StepWs carve_step(Arena &a, const Geo &g)
     const size_t gath_bytes = (size_t)g.groups * g.B * g.k * g.esz;   // all-ranks: [p,B,k]; one-rank: [B,k]
     for (int l = 0; l < g.layers; ++l) {
         w.Y.push_back(a.take(act_bytes));
-        w.A.push_back(g.act == PH_ACT_GELU ? a.take(act_bytes) : nullptr);
+        w.A.push_back(g.act == PH_ACT_GELU ? a.take((size_t)g.groups * g.B * g.s * sizeof(float)) : nullptr);
         w.G.push_back(g.q > 0 ? a.take(gath_bytes) : nullptr);
     }
     w.dYa = a.take(act_bytes);
@@ -177,6 +177,7 @@ inline unsigned blocks_for(int64_t count, int per_block = 256, int cap = 8192)
 struct FwdArgs {
     const void *X, *Lw, *Cw, *Dw, *bias, *G;
     void *Y, *g_own, *A_save;
+    bool a_f32;   // step only: A_save is float
 };
 
 template <typename T>
@@ -196,7 +197,7 @@ ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
     View vb = q > 0 ? view_rowseg(f.Lw, s, (int)s, s * s, f.Dw, (int)k, s * k, q * s * k) : view_plain(f.Lw, s, s * s);
     Epilogue ep{};
     ep.mode = EPI_BIAS_ACT; ep.act = g.act; ep.bias = f.bias; ep.bias_g = s;
-    ep.aux = f.A_save; ep.aux_ld = s; ep.aux_g = B * s;
+    ep.aux = f.A_save; ep.aux_ld = s; ep.aux_g = B * s; ep.aux_f32 = f.a_f32;
     return launch_gemm<T, T>(va, vb, view_plain(f.Y, s, B * s), ep, B, s, g.Kc, g.groups, st, "layer update");
 }
 
@@ -207,6 +208,10 @@ struct BwdArgs {
     void *dX;
     float *dLw, *dCw, *dDw, *dbias;
     void *dG_send;
+    const void *delta_ready;   // step only: delta already formed (dY, S unused)
+    bool dx_S_f32;             // step only: dx_S holds float
+    const void *dx_S;          // step only: multiply dX by sigma'(dx_S) on the way out, which makes it the
+                               //   previous layer's delta with a single rounding (Eq. (backprop))
 };
 
 template <typename T>
@@ -216,14 +221,18 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
     const int64_t act_count = (int64_t)g.groups * B * s;
 
     // local error delta = dY * sigma'
-    hipLaunchKernelGGL((delta_kernel<T>), dim3(blocks_for(act_count)), dim3(256), 0, st,
-                       (const T *)b.dY, (const T *)b.S, (T *)w.delta, act_count, g.act);
-    PH_TRY(check_launch("local error"));
+    const void *delta = b.delta_ready;
+    if (!delta) {
+        hipLaunchKernelGGL((delta_kernel<T>), dim3(blocks_for(act_count)), dim3(256), 0, st,
+                           (const T *)b.dY, (const T *)b.S, (T *)w.delta, act_count, g.act);
+        PH_TRY(check_launch("local error"));
+        delta = w.delta;
+    }
 
     // bias gradient: column sums of delta
     {
         dim3 grid((unsigned)((s + CS_COLS - 1) / CS_COLS), (unsigned)w.chunks, (unsigned)g.groups);
-        hipLaunchKernelGGL((colsum_partial_kernel<T>), grid, dim3(256), 0, st, (const T *)w.delta, w.colsum,
+        hipLaunchKernelGGL((colsum_partial_kernel<T>), grid, dim3(256), 0, st, (const T *)delta, w.colsum,
                            (int)B, (int)s, COLSUM_ROWS);
         PH_TRY(check_launch("bias gradient (partial)"));
         hipLaunchKernelGGL(colsum_final_kernel, dim3(blocks_for((int64_t)g.groups * s)), dim3(256), 0, st,
@@ -241,7 +250,7 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
         vo.p0 = nullptr; vo.p1 = b.dG_send; vo.g0 = 0; vo.g1 = q * B * k;
         vo.r = axis_plain(0, k); vo.c = axis_seg(0, (int)k, 0, 1, B * k);
         vo.skip0 = NO_SKIP; vo.skip_g = 0;
-        PH_TRY((launch_gemm<T, T>(view_plain(w.delta, s, B * s), vb, vo, epi_store(), B, q * k, s, g.groups, st,
+        PH_TRY((launch_gemm<T, T>(view_plain(delta, s, B * s), vb, vo, epi_store(), B, q * k, s, g.groups, st,
                                   "error compression")));
         if (g.all) {
             const int64_t per_slot = B * k;
@@ -254,15 +263,20 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
 
     if (b.dX) {
         // dX = delta . L + dg_own . C: reduction index = [delta | dg_own] against [L ; C]
-        View va = q > 0 ? view_rowseg(w.delta, s, (int)s, B * s, b.dg_own, (int)k, 0, B * k) : view_plain(w.delta, s, B * s);
+        View va = q > 0 ? view_rowseg(delta, s, (int)s, B * s, b.dg_own, (int)k, 0, B * k) : view_plain(delta, s, B * s);
         View vb = q > 0 ? view_colstack(b.Lw, s, (int)s, s * s, b.Cw, s, (int)k, k * s) : view_plain_t(b.Lw, s, s * s);
-        PH_TRY((launch_gemm<T, T>(va, vb, view_plain(b.dX, s, B * s), epi_store(), B, s, s + k, g.groups, st,
+        Epilogue ep = epi_store();
+        if (b.dx_S && g.act != PH_ACT_IDENTITY) {
+            ep.mode = EPI_DACT; ep.act = g.act; ep.aux = const_cast<void *>(b.dx_S); ep.aux_ld = s; ep.aux_g = B * s;
+            ep.aux_f32 = b.dx_S_f32;
+        }
+        PH_TRY((launch_gemm<T, T>(va, vb, view_plain(b.dX, s, B * s), ep, B, s, s + k, g.groups, st,
                                   "input gradient")));
     }
 
     // weight gradients: [dL | dD_1 .. dD_{p-1}] = delta^T . [X | G_1 .. G_{p-1}]
     {
-        View va = view_plain_t(w.delta, s, B * s);
+        View va = view_plain_t(delta, s, B * s);
         View vb = q > 0 ? view_rowseg_t(b.X, s, (int)s, B * s, b.G, (int)k, B * k, 0, g.all ? 0 : NO_SKIP, g.all ? 1 : 0)
                         : view_plain_t(b.X, s, B * s);
         View vo{};
@@ -327,7 +341,7 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
     for (int l = 0; l < L; ++l) {
         inputs[l] = in;
         FwdArgs f{in, a.Lw[l], q ? a.Cw[l] : nullptr, q ? a.Dw[l] : nullptr, a.bias[l],
-                  (q && !g.all) ? a.G[l] : nullptr, w.Y[l], w.G[l], w.A[l]};
+                  (q && !g.all) ? a.G[l] : nullptr, w.Y[l], w.G[l], w.A[l], true};
         PH_TRY(fwd_impl<T>(g, f, st));
         in = w.Y[l];
     }
@@ -336,21 +350,25 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
                            (T *)a.Y_out, act_count);
         PH_TRY(check_launch("output copy"));
     }
-    if (a.forward_only) return PH_OK;
+    if (a.mode == PH_STEP_FORWARD) return PH_OK;
 
-    // output error of the MSE loss
+    // output error of the MSE loss, already multiplied by sigma_L' (Eq. (deltaL))
     const unsigned mse_blocks = blocks_for(act_count, 256, MSE_BLOCKS);
-    hipLaunchKernelGGL((mse_kernel<T>), dim3(mse_blocks), dim3(256), 0, st, (const T *)w.Y[L - 1], (const T *)a.T,
-                       (T *)w.dYa, act_count, 1.0f / (float)B, w.mse_partial);
+    hipLaunchKernelGGL((mse_delta_kernel<T>), dim3(mse_blocks), dim3(256), 0, st, (const T *)w.Y[L - 1], (const T *)a.T,
+                       (const void *)(g.act == PH_ACT_GELU ? w.A[L - 1] : w.Y[L - 1]), (int)(g.act == PH_ACT_GELU),
+                       (T *)w.dYa, act_count,
+                       1.0f / (float)B, g.act, w.mse_partial);
     PH_TRY(check_launch("output error"));
     hipLaunchKernelGGL(mse_final_kernel, dim3(1), dim3(256), 0, st, (const float *)w.mse_partial, (int)mse_blocks,
                        0.5f / (float)B, a.loss);
     PH_TRY(check_launch("loss"));
 
-    void *dY = w.dYa, *dX = w.dYb;
+    void *dY = w.dYa, *dX = w.dYb;    // delta of the current layer / of the layer below
     for (int l = L - 1; l >= 0; --l) {
         BwdArgs b{};
-        b.dY = dY; b.X = inputs[l]; b.S = g.act == PH_ACT_GELU ? w.A[l] : w.Y[l];
+        b.delta_ready = dY; b.X = inputs[l];
+        b.dx_S = l > 0 ? (g.act == PH_ACT_GELU ? w.A[l - 1] : w.Y[l - 1]) : nullptr;
+        b.dx_S_f32 = g.act == PH_ACT_GELU;
         b.Lw = a.Lw[l]; b.Cw = q ? a.Cw[l] : nullptr; b.Dw = q ? a.Dw[l] : nullptr;
         b.G = q ? (g.all ? w.G[l] : a.G[l]) : nullptr;
         b.dg_own = q ? (g.all ? w.dg_own : const_cast<void *>(a.dg_own[l])) : nullptr;
@@ -362,6 +380,7 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
         b.dG_send = w.dG_send;
         PH_TRY(bwd_impl<T>(g, b, w.bwd, st));
 
+        if (a.mode == PH_STEP_NO_UPDATE) { void *t = dY; dY = dX; dX = t; continue; }
         // SGD on this layer: nothing later in the backward pass reads its weights
         struct Upd { void *w; float *master; const float *grad; int64_t count; };
         Upd upd[4] = {
@@ -422,7 +441,7 @@ ph_status phantom_layer_fwd(const ph_problem *prob, const void *X, const void *L
     (void)workspace; (void)workspace_bytes;
     Geo g;
     PH_TRY(make_geo(prob, g));
-    FwdArgs f{X, Lw, Cw, Dw, bias, G, Y, g_own, A_save};
+    FwdArgs f{X, Lw, Cw, Dw, bias, G, Y, g_own, A_save, false};
     PH_TRY(check_fwd_args(g, f));
     hipStream_t st = (hipStream_t)hip_stream;
     return g.dtype == PH_F32 ? fwd_impl<float>(g, f, st) : fwd_impl<bf16_t>(g, f, st);
@@ -435,7 +454,7 @@ ph_status phantom_layer_bwd(const ph_problem *prob, const void *dY, const void *
 {
     Geo g;
     PH_TRY(make_geo(prob, g));
-    BwdArgs b{dY, X, A_or_Y, Lw, Cw, Dw, G, dg_own, dX, dLw, dCw, dDw, dbias, dG_send};
+    BwdArgs b{dY, X, A_or_Y, Lw, Cw, Dw, G, dg_own, dX, dLw, dCw, dDw, dbias, dG_send, nullptr, false, nullptr};
     PH_TRY(check_bwd_args(g, b));
     Arena sizing{nullptr, 0};
     carve_bwd(sizing, g);
@@ -453,7 +472,9 @@ ph_status phantom_ffn_step(const ph_problem *prob, const ph_step_args *args, voi
     PH_TRY(make_geo(prob, g));
     if (!args) return fail(PH_ERR_INVALID_ARG, "args is NULL");
     const int L = g.layers;
-    const bool train = !args->forward_only;
+    if (args->mode < PH_STEP_TRAIN || args->mode > PH_STEP_NO_UPDATE) return fail(PH_ERR_INVALID_ARG, "unknown step mode %d", args->mode);
+    const bool train = args->mode != PH_STEP_FORWARD;
+    const bool update = args->mode == PH_STEP_TRAIN;
     PH_TRY(need(args->X0, "X0"));
     PH_TRY(check_ptr_array((const void *const *)args->Lw, L, "Lw"));
     PH_TRY(check_ptr_array((const void *const *)args->bias, L, "bias"));
@@ -469,7 +490,7 @@ ph_status phantom_ffn_step(const ph_problem *prob, const ph_step_args *args, voi
     if (train) {
         PH_TRY(need(args->T, "T"));
         if (!args->loss) return fail(PH_ERR_INVALID_ARG, "loss is NULL");
-        if (g.dtype == PH_BF16) {
+        if (g.dtype == PH_BF16 && update) {
             PH_TRY(check_ptr_array((const void *const *)args->Lw_master, L, "Lw_master"));
             PH_TRY(check_ptr_array((const void *const *)args->bias_master, L, "bias_master"));
             if (g.q > 0) {

@@ -84,7 +84,7 @@ def test_step_checks_per_layer_pointer_arrays():
     with pytest.raises(ph.PhantomError, match=r"Lw_master"):
         ph.ffn_step(prob, ok, ok, two, two, two, two, G=two, dg_own=two, loss=ok, lr=0.1, workspace=(0x2000, 1 << 40))
     with pytest.raises(ph.PhantomError, match=r"Dw\[1\] is NULL"):
-        ph.ffn_step(prob, ok, ok, two, two, [ok, None], two, G=two, forward_only=True, workspace=(0x2000, 1 << 40))
+        ph.ffn_step(prob, ok, ok, two, two, [ok, None], two, G=two, mode="forward", workspace=(0x2000, 1 << 40))
     with pytest.raises(ValueError):
         ph.ffn_step(prob, ok, ok, [ok], two, two, two)
 
