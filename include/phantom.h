@@ -167,6 +167,26 @@ ph_status phantom_ffn_step(const ph_problem *prob, const ph_step_args *args,
 /* Message of the calling thread's last error ("" if none).  Host string owned by the library. */
 const char *phantom_last_error(void);
 
+/*
+ * Per-kernel timing for benchmarks (measurement of the operators above, Section VI reports times
+ * per epoch only).  Between phantom_profile_begin and phantom_profile_end every kernel launch this
+ * library makes from the calling thread is bracketed by a pair of HIP events on its stream.
+ * phantom_profile_end waits for those events (the only call here that blocks), and returns one
+ * entry per distinct (kernel, shape): how often it ran and the summed time between its events.
+ * For products, M x N is the output and K the reduction length per group; for elementwise kernels
+ * N is the element count.  `entries` is a HOST array of `capacity` entries.
+ */
+typedef struct {
+    char name[40];
+    int64_t M, N, K;
+    int32_t groups;
+    int32_t calls;
+    double total_ms;
+} ph_profile_entry;
+
+ph_status phantom_profile_begin(int32_t max_launches);
+ph_status phantom_profile_end(ph_profile_entry *entries, int32_t capacity, int32_t *count);
+
 /* Library version, for the binding's sanity check. */
 int32_t phantom_abi_version(void);
 

@@ -53,6 +53,13 @@ class PhStepArgs(ctypes.Structure):
     ]
 
 
+class PhProfileEntry(ctypes.Structure):
+    _fields_ = [
+        ("name", ctypes.c_char * 40), ("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
+        ("groups", ctypes.c_int32), ("calls", ctypes.c_int32), ("total_ms", ctypes.c_double),
+    ]
+
+
 _lib = None
 
 
@@ -82,8 +89,25 @@ def load():
     lib.phantom_layer_bwd.argtypes = [prob] + [vp] * 14 + [vp, sz, vp]
     lib.phantom_ffn_step.restype = ctypes.c_int
     lib.phantom_ffn_step.argtypes = [prob, ctypes.POINTER(PhStepArgs), vp, sz, vp]
+    lib.phantom_profile_begin.restype = ctypes.c_int
+    lib.phantom_profile_begin.argtypes = [ctypes.c_int32]
+    lib.phantom_profile_end.restype = ctypes.c_int
+    lib.phantom_profile_end.argtypes = [ctypes.POINTER(PhProfileEntry), ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
     _lib = lib
     return lib
+
+
+def profile_begin(max_launches: int = 4096) -> None:
+    _check(load().phantom_profile_begin(int(max_launches)))
+
+
+def profile_end(capacity: int = 256):
+    """Returns a list of dicts: name, M, N, K, groups, calls, total_ms."""
+    entries = (PhProfileEntry * capacity)()
+    count = ctypes.c_int32(0)
+    _check(load().phantom_profile_end(entries, capacity, ctypes.byref(count)))
+    return [dict(name=e.name.decode(), M=e.M, N=e.N, K=e.K, groups=e.groups, calls=e.calls, total_ms=e.total_ms)
+            for e in entries[:count.value]]
 
 
 def abi_version() -> int:

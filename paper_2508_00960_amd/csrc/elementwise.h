@@ -139,6 +139,13 @@ __global__ __launch_bounds__(256) void sgd_bf16_kernel(float *__restrict__ maste
     }
 }
 
+__global__ __launch_bounds__(256) void fill_zero_kernel(float *__restrict__ dst, int64_t count)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < count; i += stride) dst[i] = 0.f;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void copy_kernel(const T *__restrict__ src, T *__restrict__ dst, int64_t count)
 {

@@ -7,12 +7,16 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstring>
+#include <algorithm>
 #include <string>
+#include <type_traits>
 #include <vector>
 
 #include "common.h"
 #include "elementwise.h"
 #include "gemm_generic.h"
+#include "gemm_mfma.h"
 #include "views.h"
 
 using namespace phantom;
@@ -38,6 +42,7 @@ struct Geo {
     bool all;         // all-ranks mode
     int act, dtype, rank, layers;
     size_t esz;       // bytes per element of the storage type
+    int vec;          // bf16: widest vector (8, 4, 2 elements) dividing n/p and k; 0: shape-agnostic kernels only
 };
 
 ph_status make_geo(const ph_problem *pr, Geo &g)
@@ -61,6 +66,11 @@ ph_status make_geo(const ph_problem *pr, Geo &g)
     g.groups = g.all ? (int)pr->p : 1;
     g.act = pr->act; g.dtype = pr->dtype; g.rank = pr->rank; g.layers = pr->layers;
     g.esz = pr->dtype == PH_BF16 ? 2 : 4;
+    g.vec = 0;
+    if (pr->dtype == PH_BF16) {
+        for (int v = 8; v >= 2 && !g.vec; v >>= 1)
+            if (s % v == 0 && (g.q == 0 || g.k % v == 0)) g.vec = v;
+    }
     // index arithmetic inside the kernels uses 32-bit row/column numbers and a 3-D grid
     if (g.B > (1 << 22) || g.s > (1 << 22) || g.Kc > (1 << 24) || g.p > 65535)
         return fail(PH_ERR_UNSUPPORTED, "problem too large for 32-bit tile indices (batch, n/p <= 2^22, n/p+(p-1)k <= 2^24)");
@@ -86,6 +96,37 @@ ph_status check_launch(const char *what)
     if (e != hipSuccess) return fail(PH_ERR_LAUNCH, "%s: %s", what, hipGetErrorString(e));
     return PH_OK;
 }
+
+// ---- optional per-launch timing (phantom_profile_begin / _end) ----------------------------
+struct ProfRec {
+    const char *name;
+    int64_t M, N, K;
+    int groups;
+};
+struct Profiler {
+    bool on = false;
+    std::vector<hipEvent_t> ev;      // 2 per record: start, stop
+    std::vector<ProfRec> recs;
+    size_t cap = 0;
+};
+thread_local Profiler g_prof;
+
+// Brackets one kernel launch with a pair of events on its stream while profiling is on.
+struct ProfScope {
+    hipStream_t st;
+    long idx = -1;
+    ProfScope(const char *name, int64_t M, int64_t N, int64_t K, int groups, hipStream_t s) : st(s)
+    {
+        if (!g_prof.on || g_prof.recs.size() >= g_prof.cap) return;
+        idx = (long)g_prof.recs.size();
+        g_prof.recs.push_back(ProfRec{name, M, N, K, groups});
+        (void)hipEventRecord(g_prof.ev[2 * idx], st);
+    }
+    ~ProfScope()
+    {
+        if (idx >= 0) (void)hipEventRecord(g_prof.ev[2 * idx + 1], st);
+    }
+};
 
 // ---- workspace ---------------------------------------------------------------
 struct Arena {
@@ -148,11 +189,106 @@ StepWs carve_step(Arena &a, const Geo &g)
 }
 
 // ---- one product ---------------------------------------------------------------
+inline unsigned blocks_for(int64_t count, int per_block = 256, int cap = 8192)
+{
+    int64_t b = (count + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    if (b > cap) b = cap;
+    return (unsigned)b;
+}
+
+// How one product is to be run: loader kinds of the two operands for the MFMA kernel, the vector
+// width the problem allows (0: use the shape-agnostic kernel), and whether the reduction may be
+// split over workgroups (float outputs only; the output is cleared first and added to atomically).
+struct GemmPlan {
+    int ka, kb;
+    int vec;
+    bool may_split;
+};
+
+template <int KA, int KB, int VEC, typename TOut, bool ATOMIC>
+ph_status launch_mfma_inst(const MfmaParams &P, hipStream_t st, const char *what)
+{
+    auto kern = gemm_mfma_kernel<KA, KB, VEC, VEC, TOut, ATOMIC>;
+    static thread_local bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, MFMA_LDS_BYTES);
+        if (e != hipSuccess) return fail(PH_ERR_LAUNCH, "%s: cannot reserve %d bytes of LDS: %s", what, MFMA_LDS_BYTES,
+                                         hipGetErrorString(e));
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)P.total_wg), dim3(256), MFMA_LDS_BYTES, st, P);
+    return check_launch(what);
+}
+
+template <int KA, int KB, typename TOut, bool ATOMIC>
+ph_status launch_mfma_vec(const MfmaParams &P, int vec, hipStream_t st, const char *what)
+{
+    switch (vec) {
+    case 8: return launch_mfma_inst<KA, KB, 8, TOut, ATOMIC>(P, st, what);
+    case 4: return launch_mfma_inst<KA, KB, 4, TOut, ATOMIC>(P, st, what);
+    default: return launch_mfma_inst<KA, KB, 2, TOut, ATOMIC>(P, st, what);
+    }
+}
+
+// bf16 operands on the matrix cores
+template <typename TOut>
+ph_status launch_mfma(const GemmPlan &plan, const View &a, const View &b, const View &o, const Epilogue &ep,
+                      int64_t M, int64_t N, int64_t K, int groups, hipStream_t st, const char *what)
+{
+    MfmaParams P{};
+    P.a = a; P.b = b; P.o = o; P.ep = ep;
+    P.M = (int)M; P.N = (int)N; P.K = (int)K;
+    P.tiles_m = (int)((M + MT - 1) / MT);
+    P.tiles_n = (int)((N + MT - 1) / MT);
+    const int64_t tiles = (int64_t)P.tiles_m * P.tiles_n * groups;
+    const int ksteps = (int)((K + KT - 1) / KT);
+    int ksplit = 1;
+    if (plan.may_split && std::is_same<TOut, float>::value && ep.mode == EPI_STORE) {
+        // aim at two workgroups per compute unit, keep at least 4 reduction steps per workgroup
+        const int64_t want = (2 * 256 + tiles - 1) / tiles;
+        ksplit = (int)std::max<int64_t>(1, std::min<int64_t>(want, ksteps / 4));
+    }
+    const int steps_per = (ksteps + ksplit - 1) / ksplit;
+    ksplit = (ksteps + steps_per - 1) / steps_per;
+    P.ksplit = ksplit;
+    P.k_per_split = steps_per * KT;
+    const int64_t total = tiles * ksplit;
+    if (total > 0x7fffffff) return fail(PH_ERR_UNSUPPORTED, "%s: too many tiles", what);
+    P.total_wg = (int)total;
+    if (ksplit > 1) {
+        if constexpr (std::is_same<TOut, float>::value) {
+            // clear what the split pieces add into (both regions of the output view)
+            for (int region = 0; region < 2; ++region) {
+                float *base = (float *)(region ? o.p1 : o.p0);
+                const int64_t per_group = region ? o.g1 : o.g0;
+                if (!base || per_group <= 0) continue;
+                const int64_t count = per_group * groups;
+                ProfScope prof("clear split-K output", 0, count, 0, 1, st);
+                hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks_for(count, 1024)), dim3(256), 0, st, base, count);
+                PH_TRY(check_launch("clear split-K output"));
+            }
+            ProfScope prof(what, M, N, K, groups, st);
+            if (plan.ka == LD_KM && plan.kb == LD_KM) return launch_mfma_vec<LD_KM, LD_KM, float, true>(P, plan.vec, st, what);
+        }
+        return fail(PH_ERR_UNSUPPORTED, "%s: split reduction not available for this operand layout", what);
+    }
+    ProfScope prof(what, M, N, K, groups, st);
+    if (plan.ka == LD_KC && plan.kb == LD_KC) return launch_mfma_vec<LD_KC, LD_KC, TOut, false>(P, plan.vec, st, what);
+    if (plan.ka == LD_KC && plan.kb == LD_KM) return launch_mfma_vec<LD_KC, LD_KM, TOut, false>(P, plan.vec, st, what);
+    if (plan.ka == LD_KM && plan.kb == LD_KM) return launch_mfma_vec<LD_KM, LD_KM, TOut, false>(P, plan.vec, st, what);
+    return fail(PH_ERR_UNSUPPORTED, "%s: operand layout pair not built", what);
+}
+
 template <typename TIn, typename TOut>
-ph_status launch_gemm(const View &a, const View &b, const View &o, const Epilogue &ep,
+ph_status launch_gemm(const GemmPlan &plan, const View &a, const View &b, const View &o, const Epilogue &ep,
                       int64_t M, int64_t N, int64_t K, int groups, hipStream_t st, const char *what)
 {
     if (M <= 0 || N <= 0 || groups <= 0) return PH_OK;
+    if constexpr (std::is_same<TIn, bf16_t>::value) {
+        if (plan.vec > 0) return launch_mfma<TOut>(plan, a, b, o, ep, M, N, K, groups, st, what);
+    }
+    ProfScope prof(what, M, N, K, groups, st);
     dim3 grid((unsigned)((N + GT - 1) / GT), (unsigned)((M + GT - 1) / GT), (unsigned)groups);
     hipLaunchKernelGGL((gemm_generic_kernel<TIn, TOut>), grid, dim3(256), 0, st, a, b, o, ep, (int)M, (int)N, (int)K);
     return check_launch(what);
@@ -163,14 +299,6 @@ Epilogue epi_store()
     Epilogue e{};
     e.mode = EPI_STORE;
     return e;
-}
-
-inline unsigned blocks_for(int64_t count, int per_block = 256, int cap = 8192)
-{
-    int64_t b = (count + per_block - 1) / per_block;
-    if (b < 1) b = 1;
-    if (b > cap) b = cap;
-    return (unsigned)b;
 }
 
 // ---- forward of one layer (Eq. (ylq)) ------------------------------------------------
@@ -186,7 +314,8 @@ ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
     const int64_t B = g.B, s = g.s, k = g.k, q = g.q;
     if (q > 0) {
         // compression g = C y: [B, s] x [k, s]^T -> [B, k]
-        PH_TRY((launch_gemm<T, T>(view_plain(f.X, s, B * s), view_plain(f.Cw, s, k * s), view_plain(f.g_own, k, B * k),
+        PH_TRY((launch_gemm<T, T>(GemmPlan{LD_KC, LD_KC, g.vec, false}, view_plain(f.X, s, B * s),
+                                  view_plain(f.Cw, s, k * s), view_plain(f.g_own, k, B * k),
                                   epi_store(), B, k, s, g.groups, st, "compression")));
     }
     // local update + decompression + remote update + bias + activation: one product over the
@@ -198,7 +327,8 @@ ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
     Epilogue ep{};
     ep.mode = EPI_BIAS_ACT; ep.act = g.act; ep.bias = f.bias; ep.bias_g = s;
     ep.aux = f.A_save; ep.aux_ld = s; ep.aux_g = B * s; ep.aux_f32 = f.a_f32;
-    return launch_gemm<T, T>(va, vb, view_plain(f.Y, s, B * s), ep, B, s, g.Kc, g.groups, st, "layer update");
+    return launch_gemm<T, T>(GemmPlan{LD_KC, LD_KC, g.vec, false}, va, vb, view_plain(f.Y, s, B * s), ep, B, s, g.Kc,
+                             g.groups, st, "layer update");
 }
 
 // ---- backward of one layer (Eq. (deltaL), (backprop), (bpb)-(bpD)) ---------------------------
@@ -223,6 +353,7 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
     // local error delta = dY * sigma'
     const void *delta = b.delta_ready;
     if (!delta) {
+        ProfScope prof("local error", 0, act_count, 0, 1, st);
         hipLaunchKernelGGL((delta_kernel<T>), dim3(blocks_for(act_count)), dim3(256), 0, st,
                            (const T *)b.dY, (const T *)b.S, (T *)w.delta, act_count, g.act);
         PH_TRY(check_launch("local error"));
@@ -232,6 +363,7 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
     // bias gradient: column sums of delta
     {
         dim3 grid((unsigned)((s + CS_COLS - 1) / CS_COLS), (unsigned)w.chunks, (unsigned)g.groups);
+        ProfScope prof("bias gradient", 0, act_count, 0, 1, st);
         hipLaunchKernelGGL((colsum_partial_kernel<T>), grid, dim3(256), 0, st, (const T *)delta, w.colsum,
                            (int)B, (int)s, COLSUM_ROWS);
         PH_TRY(check_launch("bias gradient (partial)"));
@@ -250,11 +382,12 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
         vo.p0 = nullptr; vo.p1 = b.dG_send; vo.g0 = 0; vo.g1 = q * B * k;
         vo.r = axis_plain(0, k); vo.c = axis_seg(0, (int)k, 0, 1, B * k);
         vo.skip0 = NO_SKIP; vo.skip_g = 0;
-        PH_TRY((launch_gemm<T, T>(view_plain(delta, s, B * s), vb, vo, epi_store(), B, q * k, s, g.groups, st,
-                                  "error compression")));
+        PH_TRY((launch_gemm<T, T>(GemmPlan{LD_KC, LD_KM, g.vec, false}, view_plain(delta, s, B * s), vb, vo, epi_store(),
+                                  B, q * k, s, g.groups, st, "error compression")));
         if (g.all) {
             const int64_t per_slot = B * k;
             dim3 grid((unsigned)((per_slot + 255) / 256), (unsigned)g.p);
+            ProfScope prof("reduce-scatter", 0, per_slot * g.p * (g.p - 1), 0, 1, st);
             hipLaunchKernelGGL((reduce_scatter_kernel<T>), grid, dim3(256), 0, st, (const T *)b.dG_send, (T *)b.dg_own,
                                (int)g.p, per_slot);
             PH_TRY(check_launch("reduce-scatter"));
@@ -270,8 +403,8 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
             ep.mode = EPI_DACT; ep.act = g.act; ep.aux = const_cast<void *>(b.dx_S); ep.aux_ld = s; ep.aux_g = B * s;
             ep.aux_f32 = b.dx_S_f32;
         }
-        PH_TRY((launch_gemm<T, T>(va, vb, view_plain(b.dX, s, B * s), ep, B, s, s + k, g.groups, st,
-                                  "input gradient")));
+        PH_TRY((launch_gemm<T, T>(GemmPlan{LD_KC, LD_KM, g.vec, false}, va, vb, view_plain(b.dX, s, B * s), ep, B, s,
+                                  s + k, g.groups, st, "input gradient")));
     }
 
     // weight gradients: [dL | dD_1 .. dD_{p-1}] = delta^T . [X | G_1 .. G_{p-1}]
@@ -284,13 +417,14 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
         vo.r = axis_plain(s, k);
         vo.c = q > 0 ? axis_seg((int)s, (int)k, 1, 1, s * k) : axis_plain(1, 0);
         vo.skip0 = NO_SKIP; vo.skip_g = 0;
-        PH_TRY((launch_gemm<T, float>(va, vb, vo, epi_store(), s, g.Kc, B, g.groups, st, "weight gradients")));
+        PH_TRY((launch_gemm<T, float>(GemmPlan{LD_KM, LD_KM, g.vec, true}, va, vb, vo, epi_store(), s, g.Kc, B, g.groups,
+                                      st, "weight gradients")));
     }
     if (q > 0) {
         // dC = dg_own^T . X
-        PH_TRY((launch_gemm<T, float>(view_plain_t(b.dg_own, k, B * k), view_plain_t(b.X, s, B * s),
-                                      view_plain(b.dCw, s, k * s), epi_store(), k, s, B, g.groups, st,
-                                      "compressor gradient")));
+        PH_TRY((launch_gemm<T, float>(GemmPlan{LD_KM, LD_KM, g.vec, true}, view_plain_t(b.dg_own, k, B * k),
+                                      view_plain_t(b.X, s, B * s), view_plain(b.dCw, s, k * s), epi_store(), k, s, B,
+                                      g.groups, st, "compressor gradient")));
     }
     return PH_OK;
 }
@@ -354,6 +488,8 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
 
     // output error of the MSE loss, already multiplied by sigma_L' (Eq. (deltaL))
     const unsigned mse_blocks = blocks_for(act_count, 256, MSE_BLOCKS);
+    {
+    ProfScope prof("output error", 0, act_count, 0, 1, st);
     hipLaunchKernelGGL((mse_delta_kernel<T>), dim3(mse_blocks), dim3(256), 0, st, (const T *)w.Y[L - 1], (const T *)a.T,
                        (const void *)(g.act == PH_ACT_GELU ? w.A[L - 1] : w.Y[L - 1]), (int)(g.act == PH_ACT_GELU),
                        (T *)w.dYa, act_count,
@@ -362,6 +498,7 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
     hipLaunchKernelGGL(mse_final_kernel, dim3(1), dim3(256), 0, st, (const float *)w.mse_partial, (int)mse_blocks,
                        0.5f / (float)B, a.loss);
     PH_TRY(check_launch("loss"));
+    }
 
     void *dY = w.dYa, *dX = w.dYb;    // delta of the current layer / of the layer below
     for (int l = L - 1; l >= 0; --l) {
@@ -391,6 +528,7 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
         };
         for (const Upd &u : upd) {
             if (!u.w || u.count == 0) continue;
+            ProfScope prof("SGD update", 0, u.count, 0, 1, st);
             if (g.dtype == PH_F32)
                 hipLaunchKernelGGL(sgd_f32_kernel, dim3(blocks_for(u.count)), dim3(256), 0, st, (float *)u.w, u.grad, a.lr,
                                    u.count);
@@ -420,6 +558,53 @@ ph_status check_ptr_array(const void *const *arr, int L, const char *name)
 extern "C" {
 
 int32_t phantom_abi_version(void) { return 1; }
+
+ph_status phantom_profile_begin(int32_t max_launches)
+{
+    if (max_launches < 1) return fail(PH_ERR_INVALID_ARG, "max_launches = %d must be >= 1", max_launches);
+    if (g_prof.on) return fail(PH_ERR_INVALID_ARG, "profiling is already on");
+    while (g_prof.ev.size() < (size_t)max_launches * 2) {
+        hipEvent_t e;
+        hipError_t err = hipEventCreate(&e);
+        if (err != hipSuccess) return fail(PH_ERR_LAUNCH, "hipEventCreate: %s", hipGetErrorString(err));
+        g_prof.ev.push_back(e);
+    }
+    g_prof.recs.clear();
+    g_prof.cap = (size_t)max_launches;
+    g_prof.on = true;
+    return PH_OK;
+}
+
+ph_status phantom_profile_end(ph_profile_entry *entries, int32_t capacity, int32_t *count)
+{
+    if (!g_prof.on) return fail(PH_ERR_INVALID_ARG, "profiling is not on");
+    g_prof.on = false;
+    if (!count || (capacity > 0 && !entries)) return fail(PH_ERR_INVALID_ARG, "entries / count is NULL");
+    int32_t used = 0;
+    for (size_t i = 0; i < g_prof.recs.size(); ++i) {
+        const ProfRec &r = g_prof.recs[i];
+        hipError_t err = hipEventSynchronize(g_prof.ev[2 * i + 1]);
+        float ms = 0.f;
+        if (err == hipSuccess) err = hipEventElapsedTime(&ms, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]);
+        if (err != hipSuccess) return fail(PH_ERR_LAUNCH, "profile event %zu: %s", i, hipGetErrorString(err));
+        int32_t at = -1;
+        for (int32_t j = 0; j < used && at < 0; ++j)
+            if (!strncmp(entries[j].name, r.name, sizeof entries[j].name - 1) && entries[j].M == r.M &&
+                entries[j].N == r.N && entries[j].K == r.K && entries[j].groups == r.groups)
+                at = j;
+        if (at < 0) {
+            if (used >= capacity) continue;
+            at = used++;
+            memset(&entries[at], 0, sizeof entries[at]);
+            strncpy(entries[at].name, r.name, sizeof entries[at].name - 1);
+            entries[at].M = r.M; entries[at].N = r.N; entries[at].K = r.K; entries[at].groups = r.groups;
+        }
+        entries[at].calls += 1;
+        entries[at].total_ms += ms;
+    }
+    *count = used;
+    return PH_OK;
+}
 
 const char *phantom_last_error(void) { return g_err.c_str(); }
 

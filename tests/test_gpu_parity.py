@@ -38,6 +38,10 @@ ONE_RANK_CASES = [
     (2048, 16, 64, 300, "gelu", "bf16", 7),
     (96, 1, 0, 50, "gelu", "bf16", 0),
     (512, 2, 256, 160, "relu", "bf16", 1),        # k = n/p
+    (1024, 4, 4, 300, "relu", "bf16", 1),         # k = 4: 8-byte vectors
+    (1032, 4, 6, 260, "gelu", "bf16", 2),         # shard 258, k = 6: 4-byte vectors
+    (2048, 8, 32, 1100, "relu", "bf16", 0),       # several tiles in every dimension, split reduction
+    (1536, 4, 16, 520, "identity", "bf16", 3),    # shard 384 = 3 tiles
 ]
 
 
