@@ -1,0 +1,269 @@
+#!/usr/bin/env python3
+"""Benchmark of the phantom-layer hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2]
+
+A "step" is one pass of the whole hot path over one batch of synthetic input that already sits in
+HBM: for the default workload (BASELINE configuration 2: n=4096, p=8, shard 512, k=32, batch 1024,
+4 layers, ReLU, MSE, bf16 storage / fp32 accumulate, all 8 emulated ranks on the GPU) that is the
+forward through every layer, the loss, and the backward through every layer, via phantom_ffn_step.
+Prints ONE JSON line: whole-step throughput (TFLOP/s from the algorithmic FLOP count
+6*B*s*(s+p*k) per layer and rank, and samples/s), the roofline of the dominant kernel measured
+with HIP events around each of its launches, the CPU oracle timed on a bounded sample, and the
+equal-width dense network through the same kernels.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA, published
+HBM_PEAK_GBS = 8000.0         # MI355X HBM3E, published
+
+WORKLOADS = {
+    # name: (n, p, k, batch, layers, act, dtype, rank, mode, lr)
+    "c1": (256, 4, 8, 32, 2, "relu", "f32", -1, "train", 1e-2),
+    "c2": (4096, 8, 32, 1024, 4, "relu", "bf16", -1, "no_update", 0.0),
+    "c3": (32768, 64, 16, 2048, 1, "relu", "bf16", 0, "no_update", 0.0),
+    "c4": (16384, 16, 64, 4096, 8, "gelu", "bf16", 0, "train", 1e-3),
+    "c5k4": (8192, 8, 4, 8192, 6, "relu", "bf16", 0, "forward", 0.0),
+    "c5k16": (8192, 8, 16, 8192, 6, "relu", "bf16", 0, "forward", 0.0),
+    "c5k64": (8192, 8, 64, 8192, 6, "relu", "bf16", 0, "forward", 0.0),
+    "c5k256": (8192, 8, 256, 8192, 6, "relu", "bf16", 0, "forward", 0.0),
+}
+
+
+def flops_per_step(n, p, k, B, L, mode, groups):
+    s = n // p
+    per = B * s * (s + (p * k if p > 1 else 0))      # multiply-adds of one forward, one rank, one layer
+    passes = 1 if mode == "forward" else 3           # backward costs twice the forward (Section IV-B)
+    return 2.0 * per * passes * L * groups
+
+
+def bytes_per_step(n, p, k, B, L, mode, groups, e):
+    """Algorithmic bytes: every input and weight read once, every output written once, storage type."""
+    s, q = n // p, p - 1
+    W = s * s + (p * s * k if p > 1 else 0) + s
+    fwd = e * (2 * B * s + q * k * B + (B * k if q else 0) + W)
+    bwd = e * (4 * B * s + 2 * q * k * B + (B * k if q else 0) + 2 * W)
+    return float((fwd if mode == "forward" else fwd + bwd) * L * groups)
+
+
+class Bench:
+    """Device-resident tensors of one workload and a closure that runs one step through the C ABI."""
+
+    def __init__(self, name, seeded=True, seed=0):
+        import numpy as np
+        import torch
+        import paper_2508_00960_amd as ph
+        import phantom_inputs as pin
+        from helpers import empty, empty_f32, to_gpu, to_gpu_f32, workspace
+
+        n, p, k, B, L, act, dt, rank, mode, lr = WORKLOADS[name] if isinstance(name, str) else name
+        self.cfg = dict(n=n, p=p, k=k, batch=B, layers=L, act=act, dtype=dt, rank=rank, mode=mode, lr=lr)
+        self.ph, self.torch = ph, torch
+        self.prob = pin.Problem(n=n, p=p, k=k, batch=B, layers=L, act=act, dtype=dt, rank=rank)
+        self.pc = ph.make_problem(n, p, k, B, L, act, dt, rank)
+        self.groups = p if rank < 0 else 1
+        self.mode, self.lr = mode, lr
+        self.ws = workspace(ph.workspace_bytes(self.pc))
+        s, q = n // p, p - 1
+        has = q > 0
+        tdt = torch.float32 if dt == "f32" else torch.bfloat16
+        lead = (p,) if rank < 0 else ()
+        names = ["Lw", "bias"] + (["Cw", "Dw"] if has else [])
+        if seeded:
+            data = pin.all_rank_step_inputs(self.prob, seed) if rank < 0 else pin.one_rank_step_inputs(self.prob, seed)
+            self.host = data
+            self.W = {nm: [to_gpu(P[nm], dt) for P in data["layers"]] for nm in names}
+            self.G = [to_gpu(P["G"], dt) for P in data["layers"]] if (has and rank >= 0) else None
+            self.dg = [to_gpu(P["dg_own"], dt) for P in data["layers"]] if (has and rank >= 0) else None
+            self.X0, self.T = to_gpu(data["X0"], dt), to_gpu(data["T"], dt)
+        else:
+            # same shapes and distributions, drawn on the GPU (used for the side measurements only)
+            gen = torch.Generator(device="cuda").manual_seed(seed)
+            def uni(shape, bound):
+                return ((torch.rand(shape, device="cuda", generator=gen) * 2 - 1) * bound).to(tdt)
+            def nrm(shape, scale=1.0):
+                return (torch.randn(shape, device="cuda", generator=gen) * scale).to(tdt)
+            shapes = {"Lw": (lead + (s, s), s ** -0.5), "bias": (lead + (s,), s ** -0.5)}
+            if has:
+                shapes["Cw"] = (lead + (k, s), s ** -0.5)
+                shapes["Dw"] = (lead + (q, s, k), k ** -0.5)
+            self.W = {nm: [uni(*shapes[nm]) for _ in range(L)] for nm in names}
+            self.G = [nrm((q, B, k)) for _ in range(L)] if (has and rank >= 0) else None
+            self.dg = [nrm((B, k), 1.0 / B) for _ in range(L)] if (has and rank >= 0) else None
+            self.X0, self.T = nrm(lead + (B, s)), nrm(lead + (B, s))
+        self.M = None
+        if dt == "bf16" and mode == "train":
+            self.M = {nm: [w.float() for w in self.W[nm]] for nm in names}
+        self.loss = empty_f32((4,))
+        self.flops = flops_per_step(n, p, k, B, L, mode, self.groups)
+        self.bytes = bytes_per_step(n, p, k, B, L, mode, self.groups, 4 if dt == "f32" else 2)
+
+    def step(self):
+        W, M = self.W, self.M or {}
+        self.ph.ffn_step(self.pc, self.X0, self.T, W["Lw"], W.get("Cw"), W.get("Dw"), W["bias"],
+                         Lw_master=M.get("Lw"), Cw_master=M.get("Cw"), Dw_master=M.get("Dw"),
+                         bias_master=M.get("bias"), G=self.G, dg_own=self.dg, loss=self.loss, lr=self.lr,
+                         mode=self.mode, workspace=self.ws)
+
+    def time_steps(self, steps, warmup, graph=True):
+        """(ms per step, launch mode).  Warm-up untimed, then exactly `steps` steps between device syncs."""
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        run, how = self.step, "eager"
+        if graph:
+            try:
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    self.step()
+                torch.cuda.current_stream().wait_stream(side)
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    self.step()
+                g.replay()
+                torch.cuda.synchronize()
+                run, how = g.replay, "hip_graph"
+            except Exception as exc:   # capture is an optimisation of the launch path, not of the kernels
+                print(f"[bench] graph capture failed, timing eager launches: {exc}", file=sys.stderr)
+                torch.cuda.synchronize()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            run()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps, how
+
+    def profile(self, steps):
+        """Per-kernel times from HIP events around every launch (eager launches)."""
+        self.torch.cuda.synchronize()
+        self.ph.profile_begin(steps * 64 * self.prob.layers + 64)
+        for _ in range(steps):
+            self.step()
+        return self.ph.profile_end()
+
+
+def kernel_table(entries, steps, esize):
+    """Adds per-launch averages, FLOP and algorithmic bytes to the raw profile entries."""
+    out = []
+    for e in entries:
+        avg_us = e["total_ms"] * 1e3 / e["calls"]
+        row = dict(name=e["name"], M=e["M"], N=e["N"], K=e["K"], groups=e["groups"],
+                   launches_per_step=e["calls"] / steps, avg_us=round(avg_us, 3))
+        if e["K"] > 0:
+            flops = 2.0 * e["M"] * e["N"] * e["K"] * e["groups"]
+            out_e = 4 if e["name"] in ("weight gradients", "compressor gradient") else esize
+            byts = (esize * (e["M"] + e["N"]) * e["K"] + out_e * e["M"] * e["N"]) * e["groups"]
+            row.update(tflops=round(flops / avg_us * 1e-6, 2), gbs=round(byts / avg_us * 1e-3, 1),
+                       flops=flops, bytes=byts)
+        out.append(row)
+    return out
+
+
+def cpu_baseline(bench, sample_batch):
+    """The fp64 oracle as it stands on the host cores, on a batch subset of the same workload."""
+    import phantom_inputs as pin
+    from oracle import oracle
+    c = bench.cfg
+    prob = pin.Problem(n=c["n"], p=c["p"], k=c["k"], batch=sample_batch, layers=c["layers"], act=c["act"],
+                       dtype=c["dtype"], rank=c["rank"])
+    all_ranks = c["rank"] < 0
+    data = pin.all_rank_step_inputs(prob, 0) if all_ranks else pin.one_rank_step_inputs(prob, 0)
+    t0 = time.perf_counter()
+    if c["mode"] == "forward":
+        oracle.ffn_forward(c["act"], data["X0"], data["layers"], c["dtype"], all_ranks)
+    else:
+        oracle.ffn_step(c["act"], data["X0"], data["T"], data["layers"], c["lr"], c["dtype"], all_ranks)
+    dt = time.perf_counter() - t0
+    fl = flops_per_step(c["n"], c["p"], c["k"], sample_batch, c["layers"], c["mode"], bench.groups)
+    return {"value": fl / dt * 1e-12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "seconds": round(dt, 2), "samples_per_s": sample_batch / dt,
+            "sample": f"same workload with batch {sample_batch} of {c['batch']} (all ranks, all layers, fp64)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--cpu-sample-batch", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the other ranks of phantom parallelism are emulated "
+              "as buffers on it); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    b = Bench(args.workload)
+    c = b.cfg
+    ms, how = b.time_steps(args.steps, args.warmup, graph=not args.no_graph)
+    ms_eager, _ = b.time_steps(max(10, args.steps // 4), 2, graph=False) if how == "hip_graph" else (ms, how)
+    tflops = b.flops / ms * 1e-9
+    esize = 4 if c["dtype"] == "f32" else 2
+
+    prof_steps = max(5, min(args.steps, 50))
+    table = kernel_table(b.profile(prof_steps), prof_steps, esize)
+    products = [r for r in table if "flops" in r]
+    dom = max(products, key=lambda r: r["avg_us"] * r["launches_per_step"])
+    ridge = MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
+    if dom["flops"] / dom["bytes"] >= ridge * 0.5 or c["dtype"] == "f32":
+        roof = {"bound": "mfma", "achieved": dom["tflops"], "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": dom["tflops"] / MFMA_PEAK_TFLOPS}
+    else:
+        roof = {"bound": "hbm", "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": dom["gbs"] / HBM_PEAK_GBS}
+    roof.update(traffic=None, kernel=f"{dom['name']} M={dom['M']} N={dom['N']} K={dom['K']} x{dom['groups']}",
+                avg_us=dom["avg_us"], launches_per_step=dom["launches_per_step"],
+                flop_per_launch=dom["flops"], algorithmic_bytes_per_launch=dom["bytes"])
+
+    out = {
+        "metric": "phantom-layer fwd+bwd TFLOP/s and samples/s per GPU; % of bf16 MFMA peak",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if c["dtype"] == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: phantom FFN n={c['n']} p={c['p']} (shard {c['n'] // c['p']}) "
+                               f"k={c['k']} batch={c['batch']} layers={c['layers']} {c['act']} "
+                               f"{'all ranks emulated on the GPU' if c['rank'] < 0 else 'rank %d with seeded peer buffers' % c['rank']}, "
+                               f"step = {c['mode']}",
+                   "launch": how, "n": c["n"], "p": c["p"], "k": c["k"], "global_batch": c["batch"],
+                   "layers": c["layers"], "activation": c["act"]},
+        "samples_per_s": c["batch"] / ms * 1e3,
+        "ms_per_step_eager": ms_eager,
+        "pct_mfma_peak": 100.0 * tflops / MFMA_PEAK_TFLOPS,
+        "pct_hbm_peak": 100.0 * (b.bytes / ms * 1e-6) / HBM_PEAK_GBS,
+        "algorithmic_flop_per_step": b.flops, "algorithmic_bytes_per_step": b.bytes,
+        "roofline": roof,
+        "kernels": [{k_: v for k_, v in r.items() if k_ not in ("flops", "bytes")} for r in table],
+    }
+
+    if not args.no_dense:
+        # equal-width dense (tensor-parallel-equivalent) network through the same kernels: p = 1
+        d = Bench((c["n"], 1, 0, c["batch"], c["layers"], c["act"], c["dtype"], 0, c["mode"], c["lr"]), seeded=False)
+        dms, dhow = d.time_steps(max(10, args.steps // 4), 5, graph=not args.no_graph)
+        out["dense_equal_width"] = {"ms_per_step": dms, "tflops": d.flops / dms * 1e-9, "launch": dhow,
+                                    "flop_per_step": d.flops, "phantom_speedup": dms / ms}
+        del d
+    if not args.no_cpu_baseline:
+        sample = args.cpu_sample_batch or max(1, min(c["batch"], int(4.0e10 / (b.flops / c["batch"]))))
+        out["cpu_baseline"] = cpu_baseline(b, sample)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
