@@ -217,7 +217,7 @@ ph_status launch_mfma_inst(const MfmaParams &P, hipStream_t st, const char *what
                                          hipGetErrorString(e));
         configured = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)P.total_wg), dim3(256), MFMA_LDS_BYTES, st, P);
+    hipLaunchKernelGGL(kern, dim3((unsigned)P.total_wg), dim3(MFMA_THREADS), MFMA_LDS_BYTES, st, P);
     return check_launch(what);
 }
 
@@ -245,9 +245,14 @@ ph_status launch_mfma(const GemmPlan &plan, const View &a, const View &b, const 
     const int ksteps = (int)((K + KT - 1) / KT);
     int ksplit = 1;
     if (plan.may_split && std::is_same<TOut, float>::value && ep.mode == EPI_STORE) {
-        // aim at two workgroups per compute unit, keep at least 4 reduction steps per workgroup
-        const int64_t want = (2 * 256 + tiles - 1) / tiles;
-        ksplit = (int)std::max<int64_t>(1, std::min<int64_t>(want, ksteps / 4));
+        // Splitting pays only when the tiles cover a small part of the 256 compute units: the atomic
+        // adds of a split cost about as much as the product itself (measured: 512 x 736 x 1024 x 8
+        // takes 34 us unsplit, 64 us in 3 pieces).  Then aim at one workgroup per compute unit and
+        // keep at least 8 reduction steps per piece.
+        if (tiles < 96) {
+            const int64_t want = (256 + tiles - 1) / tiles;
+            ksplit = (int)std::max<int64_t>(1, std::min<int64_t>(want, ksteps / 8));
+        }
     }
     const int steps_per = (ksteps + ksplit - 1) / ksplit;
     ksplit = (ksteps + steps_per - 1) / steps_per;
