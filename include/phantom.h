@@ -182,6 +182,7 @@ typedef struct {
     int32_t groups;
     int32_t calls;
     double total_ms;
+    int64_t M2, N2, K2;   /* a launch that carries two products side by side: the second one's shape, else 0 */
 } ph_profile_entry;
 
 ph_status phantom_profile_begin(int32_t max_launches);

@@ -20,40 +20,54 @@ __global__ __launch_bounds__(256) void delta_kernel(const T *__restrict__ dY, co
     }
 }
 
-// Column sums of delta [rows x cols] (Eq. (bpb): dLoss/db = sum over the batch of delta), two
-// deterministic passes: per-chunk partial sums, then their sum.
-constexpr int CS_COLS = 64;
+// Column sums of delta [rows x cols] (Eq. (bpb): dLoss/db = sum over the batch of delta).  One workgroup
+// owns CSUM_COLS columns of one group and rows [chunk*rows_per_chunk, ...): 16-byte loads, row lanes x
+// column lanes, one LDS reduction at the end.  With one chunk the result is stored (deterministic);
+// with several chunks (few columns, many rows) each adds its part atomically into the cleared output.
+constexpr int CSUM_COLS = 128;
 template <typename T>
-__global__ __launch_bounds__(256) void colsum_partial_kernel(const T *__restrict__ delta, float *__restrict__ partial,
-                                                            int rows, int cols, int rows_per_chunk)
+__global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ delta, float *__restrict__ out, int rows, int cols,
+                                                    int rows_per_chunk)
 {
-    __shared__ float red[4][CS_COLS];
-    const int g = blockIdx.z, chunk = blockIdx.y;
-    const int col = blockIdx.x * CS_COLS + (threadIdx.x & (CS_COLS - 1));
-    const int lane_r = threadIdx.x / CS_COLS;
+    constexpr int VEC = 16 / (int)sizeof(T);            // elements per 16-byte load
+    constexpr int CL = CSUM_COLS / VEC;                 // column lanes
+    constexpr int RL = 256 / CL;                        // row lanes
+    __shared__ float red[RL][CSUM_COLS + 1];
+    const int g = blockIdx.y;
+    const int cl = threadIdx.x % CL, rl = threadIdx.x / CL;
+    const int col = blockIdx.x * CSUM_COLS + cl * VEC;
     const T *d = delta + (int64_t)g * rows * cols;
-    const int r0 = chunk * rows_per_chunk;
-    const int r1 = min(rows, r0 + rows_per_chunk);
-    float acc = 0.f;
-    if (col < cols)
-        for (int r = r0 + lane_r; r < r1; r += 4) acc += to_f32(d[(int64_t)r * cols + col]);
-    red[lane_r][threadIdx.x & (CS_COLS - 1)] = acc;
-    __syncthreads();
-    if (lane_r == 0 && col < cols) {
-        float v = red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] + red[3][threadIdx.x];
-        partial[((int64_t)g * gridDim.y + chunk) * cols + col] = v;
+    const int r_begin = blockIdx.z * rows_per_chunk;
+    const int r_end = min(rows, r_begin + rows_per_chunk);
+    float acc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+    if (col + VEC <= cols && (cols % VEC) == 0) {
+        for (int r = r_begin + rl; r < r_end; r += RL) {
+            const uint4 raw = *(const uint4 *)(d + (int64_t)r * cols + col);
+            const T *e = (const T *)&raw;
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[v] += to_f32(e[v]);
+        }
+    } else {
+        for (int r = r_begin + rl; r < r_end; r += RL)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v)
+                if (col + v < cols) acc[v] += to_f32(d[(int64_t)r * cols + col + v]);
     }
-}
-
-__global__ __launch_bounds__(256) void colsum_final_kernel(const float *__restrict__ partial, float *__restrict__ out,
-                                                          int chunks, int cols, int groups)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= (int64_t)groups * cols) return;
-    const int g = (int)(i / cols), col = (int)(i % cols);
-    float acc = 0.f;
-    for (int c = 0; c < chunks; ++c) acc += partial[((int64_t)g * chunks + c) * cols + col];
-    out[i] = acc;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) red[rl][cl * VEC + v] = acc[v];
+    __syncthreads();
+    if (threadIdx.x < CSUM_COLS) {
+        const int c = blockIdx.x * CSUM_COLS + threadIdx.x;
+        float sum = 0.f;
+#pragma unroll
+        for (int r = 0; r < RL; ++r) sum += red[r][threadIdx.x];
+        if (c < cols) {
+            if (gridDim.z == 1) out[(int64_t)g * cols + c] = sum;
+            else unsafeAtomicAdd(out + (int64_t)g * cols + c, sum);
+        }
+    }
 }
 
 // In-memory Reduce-Scatter of Algorithm 1's backward: dg_own[i] = sum_{j != i} dG_send[j][slot of i on j].

@@ -309,17 +309,30 @@ __device__ __forceinline__ void epilogue_rows(const MfmaParams &P, int g, const 
 // wavefronts whose loads, LDS traffic and MFMAs interleave, without reading any operand twice.  At
 // the end the teams swap half of their accumulators through LDS: team 0 finishes and writes the
 // upper 32 rows of every wavefront quadrant, team 1 the lower 32.
+// One launch may carry two independent products of the same operand layout and output type (the
+// layer update with the compression, the error compression with the input gradient, the weight
+// gradients with the compressor gradient): their workgroups run side by side instead of one thin
+// launch waiting for the other.
+struct MfmaBatch {
+    MfmaParams p[2];
+    int count;
+    int total_wg;
+};
+
 template <int KA, int KB, int VA, int VB, typename TOut, bool ATOMIC>
-__global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaParams P)
+__global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
 
     // XCD-aware id: hardware deals workgroup ids round-robin over 8 XCDs
     int wg = blockIdx.x;
     {
-        const int per = P.total_wg >> 3;
+        const int per = batch.total_wg >> 3;
         if (wg < per * 8) wg = (wg & 7) * per + (wg >> 3);
     }
+    const bool second = wg >= batch.p[0].total_wg;
+    if (second) wg -= batch.p[0].total_wg;
+    const MfmaParams &P = batch.p[second ? 1 : 0];
     const int tiles = P.tiles_m * P.tiles_n;
     const int g = wg / (tiles * P.ksplit);
     int rem = wg - g * tiles * P.ksplit;

@@ -102,6 +102,7 @@ struct ProfRec {
     const char *name;
     int64_t M, N, K;
     int groups;
+    int64_t M2, N2, K2;   // second product of a paired launch (0 if none)
 };
 struct Profiler {
     bool on = false;
@@ -115,11 +116,12 @@ thread_local Profiler g_prof;
 struct ProfScope {
     hipStream_t st;
     long idx = -1;
-    ProfScope(const char *name, int64_t M, int64_t N, int64_t K, int groups, hipStream_t s) : st(s)
+    ProfScope(const char *name, int64_t M, int64_t N, int64_t K, int groups, hipStream_t s, int64_t M2 = 0,
+              int64_t N2 = 0, int64_t K2 = 0) : st(s)
     {
         if (!g_prof.on || g_prof.recs.size() >= g_prof.cap) return;
         idx = (long)g_prof.recs.size();
-        g_prof.recs.push_back(ProfRec{name, M, N, K, groups});
+        g_prof.recs.push_back(ProfRec{name, M, N, K, groups, M2, N2, K2});
         (void)hipEventRecord(g_prof.ev[2 * idx], st);
     }
     ~ProfScope()
@@ -140,21 +142,16 @@ struct Arena {
     }
 };
 
-constexpr int COLSUM_ROWS = 256;   // rows per partial sum of the bias gradient
 constexpr int MSE_BLOCKS = 1024;
 
 struct BwdWs {
     void *delta;        // [groups, B, s] storage type
-    float *colsum;      // [groups, chunks, s]
-    int chunks;
 };
 
 BwdWs carve_bwd(Arena &a, const Geo &g)
 {
     BwdWs w;
-    w.chunks = (int)((g.B + COLSUM_ROWS - 1) / COLSUM_ROWS);
     w.delta = a.take((size_t)g.groups * g.B * g.s * g.esz);
-    w.colsum = (float *)a.take((size_t)g.groups * w.chunks * g.s * sizeof(float));
     return w;
 }
 
@@ -197,7 +194,7 @@ inline unsigned blocks_for(int64_t count, int per_block = 256, int cap = 8192)
     return (unsigned)b;
 }
 
-// How one product is to be run: loader kinds of the two operands for the MFMA kernel, the vector
+// How a product is to be run: loader kinds of the two operands for the MFMA kernel, the vector
 // width the problem allows (0: use the shape-agnostic kernel), and whether the reduction may be
 // split over workgroups (float outputs only; the output is cleared first and added to atomically).
 struct GemmPlan {
@@ -206,8 +203,14 @@ struct GemmPlan {
     bool may_split;
 };
 
+struct Product {
+    View a, b, o;
+    Epilogue ep;
+    int64_t M, N, K;
+};
+
 template <int KA, int KB, int VEC, typename TOut, bool ATOMIC>
-ph_status launch_mfma_inst(const MfmaParams &P, hipStream_t st, const char *what)
+ph_status launch_mfma_inst(const MfmaBatch &batch, hipStream_t st, const char *what)
 {
     auto kern = gemm_mfma_kernel<KA, KB, VEC, VEC, TOut, ATOMIC>;
     static thread_local bool configured = false;
@@ -217,86 +220,120 @@ ph_status launch_mfma_inst(const MfmaParams &P, hipStream_t st, const char *what
                                          hipGetErrorString(e));
         configured = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)P.total_wg), dim3(MFMA_THREADS), MFMA_LDS_BYTES, st, P);
+    hipLaunchKernelGGL(kern, dim3((unsigned)batch.total_wg), dim3(MFMA_THREADS), MFMA_LDS_BYTES, st, batch);
     return check_launch(what);
 }
 
 template <int KA, int KB, typename TOut, bool ATOMIC>
-ph_status launch_mfma_vec(const MfmaParams &P, int vec, hipStream_t st, const char *what)
+ph_status launch_mfma_vec(const MfmaBatch &batch, int vec, hipStream_t st, const char *what)
 {
     switch (vec) {
-    case 8: return launch_mfma_inst<KA, KB, 8, TOut, ATOMIC>(P, st, what);
-    case 4: return launch_mfma_inst<KA, KB, 4, TOut, ATOMIC>(P, st, what);
-    default: return launch_mfma_inst<KA, KB, 2, TOut, ATOMIC>(P, st, what);
+    case 8: return launch_mfma_inst<KA, KB, 8, TOut, ATOMIC>(batch, st, what);
+    case 4: return launch_mfma_inst<KA, KB, 4, TOut, ATOMIC>(batch, st, what);
+    default: return launch_mfma_inst<KA, KB, 2, TOut, ATOMIC>(batch, st, what);
     }
 }
 
-// bf16 operands on the matrix cores
-template <typename TOut>
-ph_status launch_mfma(const GemmPlan &plan, const View &a, const View &b, const View &o, const Epilogue &ep,
-                      int64_t M, int64_t N, int64_t K, int groups, hipStream_t st, const char *what)
+MfmaParams mfma_params(const Product &pr, int groups, int ksplit)
 {
     MfmaParams P{};
-    P.a = a; P.b = b; P.o = o; P.ep = ep;
-    P.M = (int)M; P.N = (int)N; P.K = (int)K;
-    P.tiles_m = (int)((M + MT - 1) / MT);
-    P.tiles_n = (int)((N + MT - 1) / MT);
-    const int64_t tiles = (int64_t)P.tiles_m * P.tiles_n * groups;
-    const int ksteps = (int)((K + KT - 1) / KT);
+    P.a = pr.a; P.b = pr.b; P.o = pr.o; P.ep = pr.ep;
+    P.M = (int)pr.M; P.N = (int)pr.N; P.K = (int)pr.K;
+    P.tiles_m = (int)((pr.M + MT - 1) / MT);
+    P.tiles_n = (int)((pr.N + MT - 1) / MT);
+    const int ksteps = (int)((pr.K + KT - 1) / KT);
+    const int steps_per = (ksteps + ksplit - 1) / ksplit;
+    P.ksplit = (ksteps + steps_per - 1) / steps_per;
+    P.k_per_split = steps_per * KT;
+    P.total_wg = P.tiles_m * P.tiles_n * groups * P.ksplit;
+    return P;
+}
+
+// bf16 operands on the matrix cores: one product, or two of the same layout side by side in one launch
+template <typename TOut>
+ph_status launch_mfma(const GemmPlan &plan, const Product *prods, int count, int groups, hipStream_t st, const char *what)
+{
     int ksplit = 1;
-    if (plan.may_split && std::is_same<TOut, float>::value && ep.mode == EPI_STORE) {
+    const Product &first = prods[0];
+    const int64_t tiles = ((first.M + MT - 1) / MT) * ((first.N + MT - 1) / MT) * groups;
+    if (tiles * 8 > 0x7fffffff) return fail(PH_ERR_UNSUPPORTED, "%s: too many tiles", what);
+    if (count == 1 && plan.may_split && std::is_same<TOut, float>::value && first.ep.mode == EPI_STORE) {
         // Splitting pays only when the tiles cover a small part of the 256 compute units: the atomic
         // adds of a split cost about as much as the product itself (measured: 512 x 736 x 1024 x 8
         // takes 34 us unsplit, 64 us in 3 pieces).  Then aim at one workgroup per compute unit and
         // keep at least 8 reduction steps per piece.
-        if (tiles < 96) {
-            const int64_t want = (256 + tiles - 1) / tiles;
-            ksplit = (int)std::max<int64_t>(1, std::min<int64_t>(want, ksteps / 8));
-        }
+        const int ksteps = (int)((first.K + KT - 1) / KT);
+        if (tiles < 96) ksplit = (int)std::max<int64_t>(1, std::min<int64_t>((256 + tiles - 1) / tiles, ksteps / 8));
     }
-    const int steps_per = (ksteps + ksplit - 1) / ksplit;
-    ksplit = (ksteps + steps_per - 1) / steps_per;
-    P.ksplit = ksplit;
-    P.k_per_split = steps_per * KT;
-    const int64_t total = tiles * ksplit;
-    if (total > 0x7fffffff) return fail(PH_ERR_UNSUPPORTED, "%s: too many tiles", what);
-    P.total_wg = (int)total;
-    if (ksplit > 1) {
+    MfmaBatch batch{};
+    batch.count = count;
+    batch.p[0] = mfma_params(first, groups, ksplit);
+    batch.total_wg = batch.p[0].total_wg;
+    if (count == 2) {
+        batch.p[1] = mfma_params(prods[1], groups, 1);
+        batch.total_wg += batch.p[1].total_wg;
+    }
+    const Product &second = prods[count - 1];
+    if (batch.p[0].ksplit > 1) {
         if constexpr (std::is_same<TOut, float>::value) {
             // clear what the split pieces add into (both regions of the output view)
             for (int region = 0; region < 2; ++region) {
-                float *base = (float *)(region ? o.p1 : o.p0);
-                const int64_t per_group = region ? o.g1 : o.g0;
+                float *base = (float *)(region ? first.o.p1 : first.o.p0);
+                const int64_t per_group = region ? first.o.g1 : first.o.g0;
                 if (!base || per_group <= 0) continue;
-                const int64_t count = per_group * groups;
-                ProfScope prof("clear split-K output", 0, count, 0, 1, st);
-                hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks_for(count, 1024)), dim3(256), 0, st, base, count);
+                const int64_t n = per_group * groups;
+                ProfScope prof("clear split-K output", 0, n, 0, 1, st);
+                hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks_for(n, 1024)), dim3(256), 0, st, base, n);
                 PH_TRY(check_launch("clear split-K output"));
             }
-            ProfScope prof(what, M, N, K, groups, st);
-            if (plan.ka == LD_KM && plan.kb == LD_KM) return launch_mfma_vec<LD_KM, LD_KM, float, true>(P, plan.vec, st, what);
+            ProfScope prof(what, first.M, first.N, first.K, groups, st);
+            if (plan.ka == LD_KM && plan.kb == LD_KM) return launch_mfma_vec<LD_KM, LD_KM, float, true>(batch, plan.vec, st, what);
         }
         return fail(PH_ERR_UNSUPPORTED, "%s: split reduction not available for this operand layout", what);
     }
-    ProfScope prof(what, M, N, K, groups, st);
-    if (plan.ka == LD_KC && plan.kb == LD_KC) return launch_mfma_vec<LD_KC, LD_KC, TOut, false>(P, plan.vec, st, what);
-    if (plan.ka == LD_KC && plan.kb == LD_KM) return launch_mfma_vec<LD_KC, LD_KM, TOut, false>(P, plan.vec, st, what);
-    if (plan.ka == LD_KM && plan.kb == LD_KM) return launch_mfma_vec<LD_KM, LD_KM, TOut, false>(P, plan.vec, st, what);
+    ProfScope prof(what, first.M, first.N, first.K, groups, st, count == 2 ? second.M : 0, count == 2 ? second.N : 0,
+                   count == 2 ? second.K : 0);
+    if (plan.ka == LD_KC && plan.kb == LD_KC) return launch_mfma_vec<LD_KC, LD_KC, TOut, false>(batch, plan.vec, st, what);
+    if (plan.ka == LD_KC && plan.kb == LD_KM) return launch_mfma_vec<LD_KC, LD_KM, TOut, false>(batch, plan.vec, st, what);
+    if (plan.ka == LD_KM && plan.kb == LD_KM) return launch_mfma_vec<LD_KM, LD_KM, TOut, false>(batch, plan.vec, st, what);
     return fail(PH_ERR_UNSUPPORTED, "%s: operand layout pair not built", what);
+}
+
+// Runs one product, or two independent ones of the same kind (names: `what` for the pair on the
+// matrix cores, `what` / `what2` when they run as separate launches of the shape-agnostic kernel).
+template <typename TIn, typename TOut>
+ph_status launch_products(const GemmPlan &plan, const Product *prods_in, int count_in, int groups, hipStream_t st,
+                          const char *what, const char *what_first = nullptr, const char *what_second = nullptr)
+{
+    Product prods[2];
+    const char *names[2];
+    int count = 0;
+    for (int i = 0; i < count_in; ++i)
+        if (prods_in[i].M > 0 && prods_in[i].N > 0) {
+            names[count] = i == 0 ? (what_first ? what_first : what) : (what_second ? what_second : what);
+            prods[count++] = prods_in[i];
+        }
+    if (count == 0 || groups <= 0) return PH_OK;
+    if constexpr (std::is_same<TIn, bf16_t>::value) {
+        if (plan.vec > 0) return launch_mfma<TOut>(plan, prods, count, groups, st, count == 2 ? what : names[0]);
+    }
+    for (int i = 0; i < count; ++i) {
+        const Product &pr = prods[i];
+        ProfScope prof(names[i], pr.M, pr.N, pr.K, groups, st);
+        dim3 grid((unsigned)((pr.N + GT - 1) / GT), (unsigned)((pr.M + GT - 1) / GT), (unsigned)groups);
+        hipLaunchKernelGGL((gemm_generic_kernel<TIn, TOut>), grid, dim3(256), 0, st, pr.a, pr.b, pr.o, pr.ep, (int)pr.M,
+                           (int)pr.N, (int)pr.K);
+        PH_TRY(check_launch(names[i]));
+    }
+    return PH_OK;
 }
 
 template <typename TIn, typename TOut>
 ph_status launch_gemm(const GemmPlan &plan, const View &a, const View &b, const View &o, const Epilogue &ep,
                       int64_t M, int64_t N, int64_t K, int groups, hipStream_t st, const char *what)
 {
-    if (M <= 0 || N <= 0 || groups <= 0) return PH_OK;
-    if constexpr (std::is_same<TIn, bf16_t>::value) {
-        if (plan.vec > 0) return launch_mfma<TOut>(plan, a, b, o, ep, M, N, K, groups, st, what);
-    }
-    ProfScope prof(what, M, N, K, groups, st);
-    dim3 grid((unsigned)((N + GT - 1) / GT), (unsigned)((M + GT - 1) / GT), (unsigned)groups);
-    hipLaunchKernelGGL((gemm_generic_kernel<TIn, TOut>), grid, dim3(256), 0, st, a, b, o, ep, (int)M, (int)N, (int)K);
-    return check_launch(what);
+    Product pr{a, b, o, ep, M, N, K};
+    return launch_products<TIn, TOut>(plan, &pr, 1, groups, st, what);
 }
 
 Epilogue epi_store()
@@ -317,23 +354,29 @@ template <typename T>
 ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
 {
     const int64_t B = g.B, s = g.s, k = g.k, q = g.q;
-    if (q > 0) {
-        // compression g = C y: [B, s] x [k, s]^T -> [B, k]
-        PH_TRY((launch_gemm<T, T>(GemmPlan{LD_KC, LD_KC, g.vec, false}, view_plain(f.X, s, B * s),
-                                  view_plain(f.Cw, s, k * s), view_plain(f.g_own, k, B * k),
-                                  epi_store(), B, k, s, g.groups, st, "compression")));
-    }
+    const GemmPlan plan{LD_KC, LD_KC, g.vec, false};
+    // compression g = C y: [B, s] x [k, s]^T -> [B, k]
+    Product compress{view_plain(f.X, s, B * s), view_plain(f.Cw, s, k * s), view_plain(f.g_own, k, B * k), epi_store(),
+                     q > 0 ? B : 0, k, s};
     // local update + decompression + remote update + bias + activation: one product over the
     // concatenated reduction index [y | g_1 .. g_{p-1}] . [L | D_1 .. D_{p-1}]^T
     const void *gathered = g.all ? f.g_own : f.G;
-    View va = q > 0 ? view_rowseg(f.X, s, (int)s, B * s, gathered, (int)k, B * k, 0, g.all ? 0 : NO_SKIP, g.all ? 1 : 0)
-                    : view_plain(f.X, s, B * s);
-    View vb = q > 0 ? view_rowseg(f.Lw, s, (int)s, s * s, f.Dw, (int)k, s * k, q * s * k) : view_plain(f.Lw, s, s * s);
-    Epilogue ep{};
-    ep.mode = EPI_BIAS_ACT; ep.act = g.act; ep.bias = f.bias; ep.bias_g = s;
-    ep.aux = f.A_save; ep.aux_ld = s; ep.aux_g = B * s; ep.aux_f32 = f.a_f32;
-    return launch_gemm<T, T>(GemmPlan{LD_KC, LD_KC, g.vec, false}, va, vb, view_plain(f.Y, s, B * s), ep, B, s, g.Kc,
-                             g.groups, st, "layer update");
+    Product update{};
+    update.a = q > 0 ? view_rowseg(f.X, s, (int)s, B * s, gathered, (int)k, B * k, 0, g.all ? 0 : NO_SKIP, g.all ? 1 : 0)
+                     : view_plain(f.X, s, B * s);
+    update.b = q > 0 ? view_rowseg(f.Lw, s, (int)s, s * s, f.Dw, (int)k, s * k, q * s * k) : view_plain(f.Lw, s, s * s);
+    update.o = view_plain(f.Y, s, B * s);
+    update.ep.mode = EPI_BIAS_ACT; update.ep.act = g.act; update.ep.bias = f.bias; update.ep.bias_g = s;
+    update.ep.aux = f.A_save; update.ep.aux_ld = s; update.ep.aux_g = B * s; update.ep.aux_f32 = f.a_f32;
+    update.M = B; update.N = s; update.K = g.Kc;
+    if (g.all) {
+        // every rank reads the other ranks' g: the compression of all ranks has to finish first
+        PH_TRY((launch_products<T, T>(plan, &compress, 1, g.groups, st, "compression")));
+        return launch_products<T, T>(plan, &update, 1, g.groups, st, "layer update");
+    }
+    // one rank: the peers' g are inputs, so the rank's own compression runs beside the update
+    Product both[2] = {update, compress};
+    return launch_products<T, T>(plan, both, 2, g.groups, st, "layer update + compression", "layer update", "compression");
 }
 
 // ---- backward of one layer (Eq. (deltaL), (backprop), (bpb)-(bpD)) ---------------------------
@@ -367,29 +410,54 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
 
     // bias gradient: column sums of delta
     {
-        dim3 grid((unsigned)((s + CS_COLS - 1) / CS_COLS), (unsigned)w.chunks, (unsigned)g.groups);
+        const int strips = (int)((s + CSUM_COLS - 1) / CSUM_COLS);
+        // enough workgroups to pull the whole tensor at memory speed: split the rows when the strips are few
+        int chunks = (int)std::max<int64_t>(1, std::min<int64_t>(256 / ((int64_t)strips * g.groups), B / 128));
+        if (g.dtype == PH_F32) chunks = 1;      // the fp32 path keeps a fixed summation order
+        const int rows_per_chunk = (int)((B + chunks - 1) / chunks);
+        chunks = (int)((B + rows_per_chunk - 1) / rows_per_chunk);
+        if (chunks > 1) {
+            ProfScope prof("clear bias gradient", 0, (int64_t)g.groups * s, 0, 1, st);
+            hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks_for((int64_t)g.groups * s)), dim3(256), 0, st, b.dbias,
+                               (int64_t)g.groups * s);
+            PH_TRY(check_launch("clear bias gradient"));
+        }
+        dim3 grid((unsigned)strips, (unsigned)g.groups, (unsigned)chunks);
         ProfScope prof("bias gradient", 0, act_count, 0, 1, st);
-        hipLaunchKernelGGL((colsum_partial_kernel<T>), grid, dim3(256), 0, st, (const T *)delta, w.colsum,
-                           (int)B, (int)s, COLSUM_ROWS);
-        PH_TRY(check_launch("bias gradient (partial)"));
-        hipLaunchKernelGGL(colsum_final_kernel, dim3(blocks_for((int64_t)g.groups * s)), dim3(256), 0, st,
-                           (const float *)w.colsum, b.dbias, w.chunks, (int)s, g.groups);
+        hipLaunchKernelGGL((colsum_kernel<T>), grid, dim3(256), 0, st, (const T *)delta, b.dbias, (int)B, (int)s,
+                           rows_per_chunk);
         PH_TRY(check_launch("bias gradient"));
     }
 
-    if (q > 0) {
-        // error compression: dG_send[i] = delta . D_i   ([B, s] x [s, k] for every peer, one product over N = q*k)
-        View vb{};
-        vb.p0 = nullptr; vb.p1 = const_cast<void *>(b.Dw); vb.g0 = 0; vb.g1 = q * s * k;
-        vb.r = axis_seg(0, (int)k, 0, 1, s * k); vb.c = axis_plain(0, k);
-        vb.skip0 = NO_SKIP; vb.skip_g = 0;
-        View vo{};
-        vo.p0 = nullptr; vo.p1 = b.dG_send; vo.g0 = 0; vo.g1 = q * B * k;
-        vo.r = axis_plain(0, k); vo.c = axis_seg(0, (int)k, 0, 1, B * k);
-        vo.skip0 = NO_SKIP; vo.skip_g = 0;
-        PH_TRY((launch_gemm<T, T>(GemmPlan{LD_KC, LD_KM, g.vec, false}, view_plain(delta, s, B * s), vb, vo, epi_store(),
-                                  B, q * k, s, g.groups, st, "error compression")));
-        if (g.all) {
+    // error compression: dG_send[i] = delta . D_i   ([B, s] x [s, k] for every peer, one product over N = q*k)
+    Product send{};
+    send.a = view_plain(delta, s, B * s);
+    send.b.p0 = nullptr; send.b.p1 = const_cast<void *>(b.Dw); send.b.g0 = 0; send.b.g1 = q * s * k;
+    send.b.r = axis_seg(0, (int)k, 0, 1, s * k); send.b.c = axis_plain(0, k);
+    send.b.skip0 = NO_SKIP; send.b.skip_g = 0;
+    send.o.p0 = nullptr; send.o.p1 = b.dG_send; send.o.g0 = 0; send.o.g1 = q * B * k;
+    send.o.r = axis_plain(0, k); send.o.c = axis_seg(0, (int)k, 0, 1, B * k);
+    send.o.skip0 = NO_SKIP; send.o.skip_g = 0;
+    send.ep = epi_store();
+    send.M = q > 0 ? B : 0; send.N = q * k; send.K = s;
+
+    // dX = delta . L + dg_own . C: reduction index = [delta | dg_own] against [L ; C]
+    Product dx{};
+    dx.a = q > 0 ? view_rowseg(delta, s, (int)s, B * s, b.dg_own, (int)k, 0, B * k) : view_plain(delta, s, B * s);
+    dx.b = q > 0 ? view_colstack(b.Lw, s, (int)s, s * s, b.Cw, s, (int)k, k * s) : view_plain_t(b.Lw, s, s * s);
+    dx.o = view_plain(b.dX, s, B * s);
+    dx.ep = epi_store();
+    if (b.dx_S && g.act != PH_ACT_IDENTITY) {
+        dx.ep.mode = EPI_DACT; dx.ep.act = g.act; dx.ep.aux = const_cast<void *>(b.dx_S); dx.ep.aux_ld = s;
+        dx.ep.aux_g = B * s; dx.ep.aux_f32 = b.dx_S_f32;
+    }
+    dx.M = b.dX ? B : 0; dx.N = s; dx.K = s + k;
+
+    const GemmPlan plan_x{LD_KC, LD_KM, g.vec, false};
+    if (g.all) {
+        // the input gradient needs dg_own, which is the sum of what all ranks send: three launches
+        PH_TRY((launch_products<T, T>(plan_x, &send, 1, g.groups, st, "error compression")));
+        if (q > 0) {
             const int64_t per_slot = B * k;
             dim3 grid((unsigned)((per_slot + 255) / 256), (unsigned)g.p);
             ProfScope prof("reduce-scatter", 0, per_slot * g.p * (g.p - 1), 0, 1, st);
@@ -397,41 +465,30 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
                                (int)g.p, per_slot);
             PH_TRY(check_launch("reduce-scatter"));
         }
+        PH_TRY((launch_products<T, T>(plan_x, &dx, 1, g.groups, st, "input gradient")));
+    } else {
+        Product both[2] = {dx, send};
+        PH_TRY((launch_products<T, T>(plan_x, both, 2, g.groups, st, "input gradient + error compression",
+                                      "input gradient", "error compression")));
     }
 
-    if (b.dX) {
-        // dX = delta . L + dg_own . C: reduction index = [delta | dg_own] against [L ; C]
-        View va = q > 0 ? view_rowseg(delta, s, (int)s, B * s, b.dg_own, (int)k, 0, B * k) : view_plain(delta, s, B * s);
-        View vb = q > 0 ? view_colstack(b.Lw, s, (int)s, s * s, b.Cw, s, (int)k, k * s) : view_plain_t(b.Lw, s, s * s);
-        Epilogue ep = epi_store();
-        if (b.dx_S && g.act != PH_ACT_IDENTITY) {
-            ep.mode = EPI_DACT; ep.act = g.act; ep.aux = const_cast<void *>(b.dx_S); ep.aux_ld = s; ep.aux_g = B * s;
-            ep.aux_f32 = b.dx_S_f32;
-        }
-        PH_TRY((launch_gemm<T, T>(GemmPlan{LD_KC, LD_KM, g.vec, false}, va, vb, view_plain(b.dX, s, B * s), ep, B, s,
-                                  s + k, g.groups, st, "input gradient")));
-    }
-
-    // weight gradients: [dL | dD_1 .. dD_{p-1}] = delta^T . [X | G_1 .. G_{p-1}]
-    {
-        View va = view_plain_t(delta, s, B * s);
-        View vb = q > 0 ? view_rowseg_t(b.X, s, (int)s, B * s, b.G, (int)k, B * k, 0, g.all ? 0 : NO_SKIP, g.all ? 1 : 0)
-                        : view_plain_t(b.X, s, B * s);
-        View vo{};
-        vo.p0 = b.dLw; vo.p1 = b.dDw; vo.g0 = s * s; vo.g1 = q * s * k;
-        vo.r = axis_plain(s, k);
-        vo.c = q > 0 ? axis_seg((int)s, (int)k, 1, 1, s * k) : axis_plain(1, 0);
-        vo.skip0 = NO_SKIP; vo.skip_g = 0;
-        PH_TRY((launch_gemm<T, float>(GemmPlan{LD_KM, LD_KM, g.vec, true}, va, vb, vo, epi_store(), s, g.Kc, B, g.groups,
-                                      st, "weight gradients")));
-    }
-    if (q > 0) {
-        // dC = dg_own^T . X
-        PH_TRY((launch_gemm<T, float>(GemmPlan{LD_KM, LD_KM, g.vec, true}, view_plain_t(b.dg_own, k, B * k),
-                                      view_plain_t(b.X, s, B * s), view_plain(b.dCw, s, k * s), epi_store(), k, s, B,
-                                      g.groups, st, "compressor gradient")));
-    }
-    return PH_OK;
+    // weight gradients: [dL | dD_1 .. dD_{p-1}] = delta^T . [X | G_1 .. G_{p-1}], and dC = dg_own^T . X beside it
+    Product dw{};
+    dw.a = view_plain_t(delta, s, B * s);
+    dw.b = q > 0 ? view_rowseg_t(b.X, s, (int)s, B * s, b.G, (int)k, B * k, 0, g.all ? 0 : NO_SKIP, g.all ? 1 : 0)
+                 : view_plain_t(b.X, s, B * s);
+    dw.o.p0 = b.dLw; dw.o.p1 = b.dDw; dw.o.g0 = s * s; dw.o.g1 = q * s * k;
+    dw.o.r = axis_plain(s, k);
+    dw.o.c = q > 0 ? axis_seg((int)s, (int)k, 1, 1, s * k) : axis_plain(1, 0);
+    dw.o.skip0 = NO_SKIP; dw.o.skip_g = 0;
+    dw.ep = epi_store();
+    dw.M = s; dw.N = g.Kc; dw.K = B;
+    Product dc{view_plain_t(b.dg_own, k, B * k), view_plain_t(b.X, s, B * s), view_plain(b.dCw, s, k * s), epi_store(),
+               q > 0 ? k : 0, s, B};
+    Product grads[2] = {dw, dc};
+    // a lone weight-gradient product with few tiles may split its reduction; a pair never does
+    return launch_products<T, float>(GemmPlan{LD_KM, LD_KM, g.vec, q == 0}, grads, q > 0 ? 2 : 1, g.groups, st,
+                                     "weight + compressor gradients", "weight gradients", "compressor gradient");
 }
 
 ph_status check_fwd_args(const Geo &g, const FwdArgs &f)
@@ -595,7 +652,8 @@ ph_status phantom_profile_end(ph_profile_entry *entries, int32_t capacity, int32
         int32_t at = -1;
         for (int32_t j = 0; j < used && at < 0; ++j)
             if (!strncmp(entries[j].name, r.name, sizeof entries[j].name - 1) && entries[j].M == r.M &&
-                entries[j].N == r.N && entries[j].K == r.K && entries[j].groups == r.groups)
+                entries[j].N == r.N && entries[j].K == r.K && entries[j].groups == r.groups && entries[j].M2 == r.M2 &&
+                entries[j].N2 == r.N2 && entries[j].K2 == r.K2)
                 at = j;
         if (at < 0) {
             if (used >= capacity) continue;
@@ -603,6 +661,7 @@ ph_status phantom_profile_end(ph_profile_entry *entries, int32_t capacity, int32
             memset(&entries[at], 0, sizeof entries[at]);
             strncpy(entries[at].name, r.name, sizeof entries[at].name - 1);
             entries[at].M = r.M; entries[at].N = r.N; entries[at].K = r.K; entries[at].groups = r.groups;
+            entries[at].M2 = r.M2; entries[at].N2 = r.N2; entries[at].K2 = r.K2;
         }
         entries[at].calls += 1;
         entries[at].total_ms += ms;
