@@ -7,6 +7,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <algorithm>
 #include <string>
@@ -315,7 +316,24 @@ ph_status launch_products(const GemmPlan &plan, const Product *prods_in, int cou
         }
     if (count == 0 || groups <= 0) return PH_OK;
     if constexpr (std::is_same<TIn, bf16_t>::value) {
-        if (plan.vec > 0) return launch_mfma<TOut>(plan, prods, count, groups, st, count == 2 ? what : names[0]);
+        if (plan.vec > 0) {
+            // Two products share a launch only when that does not add a round of workgroups: a tile
+            // occupies a whole compute unit, so 256 + 32 tiles take two rounds where 256, then 32, take
+            // one round and a short one.  PHANTOM_PAIR=0 / 1 forces the choice (for measurements).
+            bool pair = count == 2;
+            if (pair) {
+                const int64_t t0 = ((prods[0].M + MT - 1) / MT) * ((prods[0].N + MT - 1) / MT) * groups;
+                const int64_t t1 = ((prods[1].M + MT - 1) / MT) * ((prods[1].N + MT - 1) / MT) * groups;
+                const int64_t cus = 256;
+                pair = (t0 + t1 + cus - 1) / cus <= (t0 + cus - 1) / cus + (t1 + cus - 1) / cus - 1 || t0 + t1 <= cus;
+                static const char *force = getenv("PHANTOM_PAIR");
+                if (force) pair = force[0] == '1';
+            }
+            if (pair || count == 1) return launch_mfma<TOut>(plan, prods, count, groups, st, count == 2 ? what : names[0]);
+            GemmPlan single = plan;
+            PH_TRY(launch_mfma<TOut>(single, &prods[0], 1, groups, st, names[0]));
+            return launch_mfma<TOut>(single, &prods[1], 1, groups, st, names[1]);
+        }
     }
     for (int i = 0; i < count; ++i) {
         const Product &pr = prods[i];
@@ -487,7 +505,7 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
                q > 0 ? k : 0, s, B};
     Product grads[2] = {dw, dc};
     // a lone weight-gradient product with few tiles may split its reduction; a pair never does
-    return launch_products<T, float>(GemmPlan{LD_KM, LD_KM, g.vec, q == 0}, grads, q > 0 ? 2 : 1, g.groups, st,
+    return launch_products<T, float>(GemmPlan{LD_KM, LD_KM, g.vec, true}, grads, q > 0 ? 2 : 1, g.groups, st,
                                      "weight + compressor gradients", "weight gradients", "compressor gradient");
 }
 
