@@ -160,9 +160,13 @@ def kernel_table(entries, steps, esize):
         row = dict(name=e["name"], M=e["M"], N=e["N"], K=e["K"], groups=e["groups"],
                    launches_per_step=e["calls"] / steps, avg_us=round(avg_us, 3))
         if e["K"] > 0:
-            flops = 2.0 * e["M"] * e["N"] * e["K"] * e["groups"]
-            out_e = 4 if e["name"] in ("weight gradients", "compressor gradient") else esize
-            byts = (esize * (e["M"] + e["N"]) * e["K"] + out_e * e["M"] * e["N"]) * e["groups"]
+            out_e = 4 if "gradients" in e["name"] or e["name"] == "compressor gradient" else esize
+            flops, byts = 0.0, 0.0
+            for M, N, K in ((e["M"], e["N"], e["K"]), (e.get("M2", 0), e.get("N2", 0), e.get("K2", 0))):
+                flops += 2.0 * M * N * K * e["groups"]
+                byts += (esize * (M + N) * K + out_e * M * N) * e["groups"]
+            if e.get("K2", 0):
+                row.update(M2=e["M2"], N2=e["N2"], K2=e["K2"])
             row.update(tflops=round(flops / avg_us * 1e-6, 2), gbs=round(byts / avg_us * 1e-3, 1),
                        flops=flops, bytes=byts)
         out.append(row)
