@@ -152,10 +152,23 @@ class Bench:
         return self.ph.profile_end()
 
 
+EMPTY_LAUNCH = "(empty launch)"
+
+
 def kernel_table(entries, steps, esize):
-    """Adds per-launch averages, FLOP and algorithmic bytes to the raw profile entries."""
+    """Adds per-launch averages, FLOP and algorithmic bytes to the raw profile entries.
+
+    avg_us is the time between the HIP events around a launch, as measured: it includes about 2 us of
+    launch latency that rocprofv3's kernel duration does not, so every rate derived from it is on the
+    low side.  What the same pair of events reads around a kernel that does nothing is reported
+    beside it (`empty_launch_us`), not subtracted.
+    """
     out = []
+    empty = [e for e in entries if e["name"] == EMPTY_LAUNCH]
+    overhead = empty[0]["total_ms"] * 1e3 / empty[0]["calls"] if empty else 0.0
     for e in entries:
+        if e["name"] == EMPTY_LAUNCH:
+            continue
         avg_us = e["total_ms"] * 1e3 / e["calls"]
         row = dict(name=e["name"], M=e["M"], N=e["N"], K=e["K"], groups=e["groups"],
                    launches_per_step=e["calls"] / steps, avg_us=round(avg_us, 3))
@@ -170,7 +183,25 @@ def kernel_table(entries, steps, esize):
             row.update(tflops=round(flops / avg_us * 1e-6, 2), gbs=round(byts / avg_us * 1e-3, 1),
                        flops=flops, bytes=byts)
         out.append(row)
-    return out
+    return out, overhead
+
+
+def measured_traffic(workload, row):
+    """HBM bytes per launch of one kernel, from the committed rocprofv3 counter summary (None if not measured).
+
+    The summary holds one line per (workload, kernel, shape): FETCH_SIZE and WRITE_SIZE per dispatch,
+    already scaled by what the same counters read for a copy of known size in the same run.
+    """
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    key = [workload, row["name"].replace(" ", "_"), str(row["M"]), str(row["N"]), str(row["K"]), str(row["groups"])]
+    with open(path) as f:
+        for line in f:
+            w = line.split()
+            if len(w) >= 8 and not line.startswith("#") and w[:6] == key:
+                return float(w[6]) + float(w[7])
+    return None
 
 
 def cpu_baseline(bench, sample_batch):
@@ -204,6 +235,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--cpu-sample-batch", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 256 MiB device copy: the dispatch of known size that scales rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the other ranks of phantom parallelism are emulated "
@@ -214,6 +248,13 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
+    if args.calibrate_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     b = Bench(args.workload)
     c = b.cfg
     ms, how = b.time_steps(args.steps, args.warmup, graph=not args.no_graph)
@@ -222,17 +263,17 @@ def main():
     esize = 4 if c["dtype"] == "f32" else 2
 
     prof_steps = max(5, min(args.steps, 50))
-    table = kernel_table(b.profile(prof_steps), prof_steps, esize)
+    table, event_overhead_us = kernel_table(b.profile(prof_steps), prof_steps, esize)
     products = [r for r in table if "flops" in r]
     dom = max(products, key=lambda r: r["avg_us"] * r["launches_per_step"])
     ridge = MFMA_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
-    if dom["flops"] / dom["bytes"] >= ridge * 0.5 or c["dtype"] == "f32":
+    if dom["flops"] / dom["bytes"] >= ridge or c["dtype"] == "f32":
         roof = {"bound": "mfma", "achieved": dom["tflops"], "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": dom["tflops"] / MFMA_PEAK_TFLOPS}
     else:
         roof = {"bound": "hbm", "achieved": dom["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": dom["gbs"] / HBM_PEAK_GBS}
-    roof.update(traffic=None, kernel=f"{dom['name']} M={dom['M']} N={dom['N']} K={dom['K']} x{dom['groups']}",
+    roof.update(traffic=measured_traffic(args.workload, dom), kernel=f"{dom['name']} M={dom['M']} N={dom['N']} K={dom['K']} x{dom['groups']}",
                 avg_us=dom["avg_us"], launches_per_step=dom["launches_per_step"],
                 flop_per_launch=dom["flops"], algorithmic_bytes_per_launch=dom["bytes"])
 
@@ -253,6 +294,7 @@ def main():
         "pct_hbm_peak": 100.0 * (b.bytes / ms * 1e-6) / HBM_PEAK_GBS,
         "algorithmic_flop_per_step": b.flops, "algorithmic_bytes_per_step": b.bytes,
         "roofline": roof,
+        "empty_launch_us": round(event_overhead_us, 3),
         "kernels": [{k_: v for k_, v in r.items() if k_ not in ("flops", "bytes")} for r in table],
     }
 

@@ -175,6 +175,9 @@ const char *phantom_last_error(void);
  * entry per distinct (kernel, shape): how often it ran and the summed time between its events.
  * For products, M x N is the output and K the reduction length per group; for elementwise kernels
  * N is the element count.  `entries` is a HOST array of `capacity` entries.
+ * The time between two events around a launch includes launch and time-stamp latency (a few
+ * microseconds); to let the caller subtract it, the first profiled launch is preceded by 32
+ * launches of a kernel that does nothing, reported as the entry named "(empty launch)".
  */
 typedef struct {
     char name[40];

@@ -510,10 +510,10 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
 }
 
 #ifdef PHANTOM_TIMELINE   // cycle stamps for the development micro-benchmark, never built into the library
-#define PH_STAMP(slot) do { __builtin_amdgcn_sched_barrier(0); if (blockIdx.x == 0 && lane == 0 && wave == 0 && t < 16) \
-        ((long long *)P.ep.aux)[(team * 16 + t) * 8 + (slot)] = clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
+#define PH_PHASE(slot) do { __builtin_amdgcn_sched_barrier(0); if ((blockIdx.x == 0 || blockIdx.x == gridDim.x - 1) && threadIdx.x == 0) \
+        ((long long *)batch.p[0].ep.aux)[(blockIdx.x ? 8 : 0) + (slot)] = clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
 #else
-#define PH_STAMP(slot) do { } while (0)
+#define PH_PHASE(slot) do { } while (0)
 #endif
 
 // 512 threads = two teams of 4 wavefronts.  Both teams work on the SAME 128 x 128 tile of C; team q
@@ -535,6 +535,7 @@ template <int KA, int KB, int VA, int VB, typename TOut, bool ATOMIC>
 __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    PH_PHASE(0);
 
     // XCD-aware id: hardware deals workgroup ids round-robin over 8 XCDs
     int wg = blockIdx.x;
@@ -585,6 +586,7 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    PH_PHASE(1);
 
     __bf16 *smem = (__bf16 *)smem_raw + team * 4 * TILE_ELEMS;
     __bf16 *s0a = smem, *s0b = smem + TILE_ELEMS, *s1a = smem + 2 * TILE_ELEMS, *s1b = smem + 3 * TILE_ELEMS;
@@ -601,6 +603,7 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
     PH_STORE(0, 0, kfirst);
     PH_FETCH(0, kfirst + 2 * KS);
     __syncthreads();
+    PH_PHASE(2);
 
     // step t multiplies LDS stage t%2; on entry the operands of step t+1 sit in register set (t+1)%2 and
     // are moved to the other LDS stage, whose readers finished before the barrier that ended step t-1
@@ -633,6 +636,7 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
 #undef PH_STEP
     if (t < steps) mfma_tile<KA, KB>(acc, s0a, s0b, wm, wn, lane);
     __syncthreads();
+    PH_PHASE(3);
 #undef PH_FETCH
 #undef PH_STORE
 
@@ -665,7 +669,9 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
         }
     }
     __syncthreads();
+    PH_PHASE(4);
     epilogue_from_lds<VA, TOut, ATOMIC>(P, g, ctile, m0, n0);
+    PH_PHASE(5);
 }
 
 }  // namespace phantom
