@@ -119,14 +119,14 @@ __device__ __forceinline__ StageState stage_init(const View &v, int g, int r0, i
     s.c_decides = v.c.decides;
     s.c_split = v.c.decides ? v.c.split : 0x7fffffff;
     s.c_seg = v.c.seg; s.c_skip = skip;
-    s.c_magic = (unsigned)((0x100000000ull + (unsigned)v.c.seg - 1) / (unsigned)v.c.seg);
+    s.c_magic = v.c.magic;                           // the MFMA path never sees seg == 1 (VEC >= 2 divides seg)
     s.c_mult0 = (int)v.c.mult0; s.c_mult1 = (int)v.c.mult1; s.c_seg_stride = (int)v.c.seg_stride;
     s.r_region = -1;
     s.col_seg = 0; s.col_in_seg = s.col;
     if (KIND == LD_KC) {
         s.regular = !v.c.decides || (v.c.split % KT == 0 && (KT % v.c.seg == 0 || v.c.seg % KT == 0));
         if (s.regular && v.c.decides && v.c.seg < KT) {
-            s.col_seg = s.col / v.c.seg;
+            s.col_seg = (int)__umulhi((unsigned)s.col, v.c.magic);
             s.col_in_seg = s.col - s.col_seg * v.c.seg;
         }
 #pragma unroll
@@ -309,7 +309,7 @@ __device__ __forceinline__ void mfma_tile(f32x16 (&acc)[2][2], const __bf16 *ta,
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv[j], av[i], acc[i][j], 0, 0, 0);   // B first: see acc_to_lds
     }
 }
 
@@ -339,7 +339,7 @@ __device__ __forceinline__ void fused_quarter(f32x16 (&acc)[2][2], const __bf16 
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv[j], av[i], acc[i][j], 0, 0, 0);   // B first: see acc_to_lds
     stage_store<KA, VA, CAREFUL, Q * PA, (Q + 1) * PA>(sa, ra, na, c_store);
     stage_store<KB, VB, CAREFUL, Q * PB, (Q + 1) * PB>(sb, rb, nb, c_store);
     stage_fetch<KA, VA, CAREFUL, Q * PA, (Q + 1) * PA>(sa, a_off0, a_off1, ra, c_fetch);
@@ -380,7 +380,7 @@ __device__ __forceinline__ void fast_step(f32x16 (&acc)[2][2], bf16x8 (&fr)[2][4
 {
     constexpr int NA = StageCfg<KA, VA>::NV, NB = StageCfg<KB, VB>::NV;
     const FastStep fa = fast_step_addr<KA, VA>(sa, c_fetch), fb = fast_step_addr<KB, VB>(sb, c_fetch);
-#define PH_MFMA(buf, i, j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[buf][i], fr[buf][2 + j], acc[i][j], 0, 0, 0)
+#define PH_MFMA(buf, i, j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[buf][2 + j], fr[buf][i], acc[i][j], 0, 0, 0)
 #define PH_STORE_A(q) stage_store<KA, VA, false, part_lo(NA, q), part_lo(NA, q + 1)>(sa, ra, na, 0)
 #define PH_STORE_B(q) stage_store<KB, VB, false, part_lo(NB, q), part_lo(NB, q + 1)>(sb, rb, nb, 0)
 #define PH_FETCH_A(q) fast_fetch<KA, VA, part_lo(NA, q), part_lo(NA, q + 1)>(fa, a_off0, a_off1, ra)
@@ -425,24 +425,33 @@ __device__ __forceinline__ void fast_step(f32x16 (&acc)[2][2], bf16x8 (&fr)[2][4
 // the 8 MB of a 4096 x 1024 bf16 output, a third of the kernel).  Instead the finished fp32 tile
 // goes to LDS and all 512 threads walk it row by row, VEC consecutive columns per thread: bias,
 // activation (or its derivative) and every global access are then 16-byte vectors on full lines.
-constexpr int CT_PITCH = MT + 4;                       // floats per row of the fp32 tile in LDS
-constexpr int CT_OFFSET_BYTES = 2 * 256 * 32 * 4;      // behind the two 32 KB accumulator-exchange areas
-static_assert(CT_OFFSET_BYTES + MT * CT_PITCH * 4 <= MFMA_LDS_BYTES, "fp32 tile fits behind the exchange area");
+constexpr int CT_PITCH = MT + 4;                       // floats per row of an fp32 tile in LDS (132 = 4 mod 64: the 16-byte
+                                                       // writes of 16 lanes in 16 different rows fall on 64 different banks)
+constexpr int CT_ELEMS = MT * CT_PITCH;                // one tile per team
+static_assert(2 * CT_ELEMS * 4 <= MFMA_LDS_BYTES, "both teams' fp32 tiles fit in the staging space");
 
-// this lane's 32 x 64 block of finished accumulators (two 32 x 32 MFMA tiles side by side) -> LDS tile.
-// A lane holds column (lane & 31) of each MFMA tile and rows 8*(e/4) + 4*(lane>>5) + e%4.
-__device__ __forceinline__ void tile_to_lds(float *ctile, const f32x16 (&acc)[2], int row0, int col0, int lane)
+// A wavefront's 64 x 64 block of accumulators -> its team's fp32 tile in LDS.
+// The MFMAs are issued with the B operand first, i.e. they compute the transpose of each 32 x 32 block:
+// a lane then holds, of block (i, j), row (lane & 31) and the columns 8*(e/4) + 4*(lane>>5) + e%4, so
+// every group of four accumulators is 16 contiguous bytes of a row-major tile (one ds_write_b128;
+// in the untransposed layout the same data would take four 4-byte writes).
+__device__ __forceinline__ void acc_to_lds(float *ctile, const f32x16 (&acc)[2][2], int wm, int wn, int lane)
 {
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int e = 0; e < 16; ++e)
-            ctile[(row0 + (e >> 2) * 8 + (lane >> 5) * 4 + (e & 3)) * CT_PITCH + col0 + j * 32 + (lane & 31)] = acc[j][e];
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                f32x4 v = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                *(f32x4 *)(ctile + (wm + 32 * i + (lane & 31)) * CT_PITCH + wn + 32 * j + 8 * q + 4 * (lane >> 5)) = v;
+            }
 }
 
 template <typename T, int VEC> struct PackOf { typedef T type __attribute__((ext_vector_type(VEC))); };
 
-// rows [m0, m0+128) x columns [n0, n0+128) of the output from the fp32 tile in LDS
+// rows [m0, m0+128) x columns [n0, n0+128) of the output = sum of the two teams' fp32 tiles in LDS
 template <int VEC, typename TOut, bool ATOMIC>
 __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, const float *ctile, int m0, int n0)
 {
@@ -461,8 +470,12 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
         const int m = m0 + row, n = n0 + col;
         if (m >= P.M || n >= P.N) continue;
         float x[VEC];
+        {
+            const FlV c0 = *(const FlV *)(ctile + row * CT_PITCH + col);
+            const FlV c1 = *(const FlV *)(ctile + CT_ELEMS + row * CT_PITCH + col);
 #pragma unroll
-        for (int u = 0; u < VEC; ++u) x[u] = ctile[row * CT_PITCH + col + u];
+            for (int u = 0; u < VEC; ++u) x[u] = c0[u] + c1[u];
+        }
         const int64_t aux_at = g * ep.aux_g + (int64_t)m * ep.aux_ld + n;
         if (ep.mode == EPI_BIAS_ACT) {
             const BfV b = *(const BfV *)((const __bf16 *)ep.bias + g * ep.bias_g + n);
@@ -519,8 +532,7 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
 // 512 threads = two teams of 4 wavefronts.  Both teams work on the SAME 128 x 128 tile of C; team q
 // takes the reduction steps q, q+2, q+4, ... with its own pair of LDS stages, so every SIMD holds two
 // wavefronts whose loads, LDS traffic and MFMAs interleave, without reading any operand twice.  At
-// the end the teams swap half of their accumulators through LDS: team 0 finishes and writes the
-// upper 32 rows of every wavefront quadrant, team 1 the lower 32.
+// the end each team writes its partial fp32 tile to LDS and the epilogue adds the two.
 // One launch may carry two independent products of the same operand layout and output type (the
 // layer update with the compression, the error compression with the input gradient, the weight
 // gradients with the compressor gradient): their workgroups run side by side instead of one thin
@@ -531,7 +543,7 @@ struct MfmaBatch {
     int total_wg;
 };
 
-template <int KA, int KB, int VA, int VB, typename TOut, bool ATOMIC>
+template <int KA, int KB, int VA, int VB, typename TOut, bool ATOMIC, bool PAIR>
 __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -543,9 +555,11 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
         const int per = batch.total_wg >> 3;
         if (wg < per * 8) wg = (wg & 7) * per + (wg >> 3);
     }
-    const bool second = wg >= batch.p[0].total_wg;
+    // PAIR is a template parameter because choosing between the two parameter blocks at run time
+    // makes every later read of a parameter a dependent memory access (measured: 1.8 us per launch)
+    const bool second = PAIR && wg >= batch.p[0].total_wg;
     if (second) wg -= batch.p[0].total_wg;
-    const MfmaParams &P = batch.p[second ? 1 : 0];
+    const MfmaParams &P = PAIR ? batch.p[second ? 1 : 0] : batch.p[0];
     const int tiles = P.tiles_m * P.tiles_n;
     const int g = wg / (tiles * P.ksplit);
     int rem = wg - g * tiles * P.ksplit;
@@ -562,6 +576,7 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
     const int m0 = tm * MT, n0 = tn * MT;
     const int k_begin = ks * P.k_per_split;
     const int k_end = min(P.K, k_begin + P.k_per_split);
+    PH_PHASE(6);
 
     const int team = threadIdx.x >> 8;
     const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
@@ -572,6 +587,7 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
     int a_off0[SA::NV], a_off1[SA::NV], b_off0[SB::NV], b_off1[SB::NV];
     const StageState sa = stage_init<KA, VA>(P.a, g, m0, P.M, k_end, tid, a_off0, a_off1);
     const StageState sb = stage_init<KB, VB>(P.b, g, n0, P.N, k_end, tid, b_off0, b_off1);
+    PH_PHASE(7);
     typename SA::V ra0[SA::NV], ra1[SA::NV];
     typename SB::V rb0[SB::NV], rb1[SB::NV];
 #define PH_FETCH(set, c0) do { stage_fetch<KA, VA, true>(sa, a_off0, a_off1, ra##set, (c0)); \
@@ -640,34 +656,10 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
 #undef PH_FETCH
 #undef PH_STORE
 
-    // the two teams hold partial sums of the same tile: swap halves through LDS (2 x 32 KB of floats)
-    float *xch = (float *)smem_raw;
-    {
-        float *mine = xch + (team ? 0 : 256 * 32) + tid;      // team 1 gives its upper rows, team 0 its lower rows
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e)
-                mine[(j * 16 + e) * 256] = team ? acc[0][j][e] : acc[1][j][e];
-    }
-    __syncthreads();
-    float *ctile = (float *)(smem_raw + CT_OFFSET_BYTES);
-    {
-        const float *theirs = xch + (team ? 256 * 32 : 0) + tid;
-        if (team == 0) {
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[0][j][e] += theirs[(j * 16 + e) * 256];
-            tile_to_lds(ctile, acc[0], wm, wn, lane);
-        } else {
-#pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[1][j][e] += theirs[(j * 16 + e) * 256];
-            tile_to_lds(ctile, acc[1], wm + 32, wn, lane);
-        }
-    }
+    // the two teams hold partial sums of the same tile: each writes its own fp32 tile over the
+    // staging space (free after the barrier above), the epilogue adds the two while reading
+    float *ctile = (float *)smem_raw;
+    acc_to_lds(ctile + team * CT_ELEMS, acc, wm, wn, lane);
     __syncthreads();
     PH_PHASE(4);
     epilogue_from_lds<VA, TOut, ATOMIC>(P, g, ctile, m0, n0);

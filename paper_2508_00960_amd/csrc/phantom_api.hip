@@ -227,10 +227,10 @@ struct Product {
     int64_t M, N, K;
 };
 
-template <int KA, int KB, int VEC, typename TOut, bool ATOMIC>
-ph_status launch_mfma_inst(const MfmaBatch &batch, hipStream_t st, const char *what)
+template <int KA, int KB, int VEC, typename TOut, bool ATOMIC, bool PAIR>
+ph_status launch_mfma_pair(const MfmaBatch &batch, hipStream_t st, const char *what)
 {
-    auto kern = gemm_mfma_kernel<KA, KB, VEC, VEC, TOut, ATOMIC>;
+    auto kern = gemm_mfma_kernel<KA, KB, VEC, VEC, TOut, ATOMIC, PAIR>;
     static thread_local bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, MFMA_LDS_BYTES);
@@ -240,6 +240,13 @@ ph_status launch_mfma_inst(const MfmaBatch &batch, hipStream_t st, const char *w
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)batch.total_wg), dim3(MFMA_THREADS), MFMA_LDS_BYTES, st, batch);
     return check_launch(what);
+}
+
+template <int KA, int KB, int VEC, typename TOut, bool ATOMIC>
+ph_status launch_mfma_inst(const MfmaBatch &batch, hipStream_t st, const char *what)
+{
+    if (batch.count == 2) return launch_mfma_pair<KA, KB, VEC, TOut, ATOMIC, true>(batch, st, what);
+    return launch_mfma_pair<KA, KB, VEC, TOut, ATOMIC, false>(batch, st, what);
 }
 
 template <int KA, int KB, typename TOut, bool ATOMIC>

@@ -21,7 +21,7 @@ struct Axis {
     int32_t decides;     // 1: this index selects the region
     int32_t split;       // decides: indices < split are region 0
     int32_t seg;         // decides: segment length in region 1 (>= 1)
-    int32_t pad_;
+    uint32_t magic;      // ceil(2^32 / seg): idx / seg == __umulhi(idx, magic) while idx * seg < 2^32 (seg >= 2)
     int64_t mult0;       // region 0 offset = idx * mult0
     int64_t mult1;       // region 1 offset = idx * mult1 (not deciding) or slot*seg_stride + w*mult1 (deciding)
     int64_t seg_stride;
@@ -76,13 +76,14 @@ __device__ __forceinline__ int64_t join(const Loc &lr, const Loc &lc, int &regio
 inline Axis axis_plain(int64_t mult0, int64_t mult1)
 {
     Axis a{};
-    a.decides = 0; a.split = 0; a.seg = 1; a.mult0 = mult0; a.mult1 = mult1; a.seg_stride = 0;
+    a.decides = 0; a.split = 0; a.seg = 1; a.magic = 0; a.mult0 = mult0; a.mult1 = mult1; a.seg_stride = 0;
     return a;
 }
 inline Axis axis_seg(int split, int seg, int64_t mult0, int64_t mult1, int64_t seg_stride)
 {
     Axis a{};
     a.decides = 1; a.split = split; a.seg = seg < 1 ? 1 : seg; a.mult0 = mult0; a.mult1 = mult1; a.seg_stride = seg_stride;
+    a.magic = a.seg > 1 ? (uint32_t)((0x100000000ull + (uint32_t)a.seg - 1) / (uint32_t)a.seg) : 0u;
     return a;
 }
 constexpr int32_t NO_SKIP = 0x3fffffff;
