@@ -543,6 +543,18 @@ struct MfmaBatch {
     int total_wg;
 };
 
+__device__ __forceinline__ MfmaParams pick_params(bool second, const MfmaParams &a, const MfmaParams &b)
+{
+    static_assert(sizeof(MfmaParams) % 4 == 0, "parameter block is a whole number of words");
+    constexpr int WORDS = sizeof(MfmaParams) / 4;
+    union Words { MfmaParams p; uint32_t w[WORDS]; __device__ Words() {} };
+    Words out;
+    const uint32_t *wa = (const uint32_t *)&a, *wb = (const uint32_t *)&b;
+#pragma unroll
+    for (int i = 0; i < WORDS; ++i) out.w[i] = second ? wb[i] : wa[i];
+    return out.p;
+}
+
 template <int KA, int KB, int VA, int VB, typename TOut, bool ATOMIC, bool PAIR>
 __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
 {
@@ -555,11 +567,12 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
         const int per = batch.total_wg >> 3;
         if (wg < per * 8) wg = (wg & 7) * per + (wg >> 3);
     }
-    // PAIR is a template parameter because choosing between the two parameter blocks at run time
-    // makes every later read of a parameter a dependent memory access (measured: 1.8 us per launch)
+    // Indexing the two parameter blocks with a run-time value turns every later read of a parameter
+    // into a small dependent load (measured: 1.8 us per launch); a single product reads its block
+    // directly, a pair selects word by word between two blocks that are both read with fixed offsets
     const bool second = PAIR && wg >= batch.p[0].total_wg;
     if (second) wg -= batch.p[0].total_wg;
-    const MfmaParams &P = PAIR ? batch.p[second ? 1 : 0] : batch.p[0];
+    const MfmaParams P = PAIR ? pick_params(second, batch.p[0], batch.p[1]) : batch.p[0];
     const int tiles = P.tiles_m * P.tiles_n;
     const int g = wg / (tiles * P.ksplit);
     int rem = wg - g * tiles * P.ksplit;
