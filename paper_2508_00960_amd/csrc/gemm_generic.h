@@ -21,6 +21,8 @@ struct Epilogue {
     int64_t aux_ld;      //   plain row-major [M x N]
     int64_t aux_g;
     int32_t aux_f32;     // aux holds float instead of the storage type
+    float *colsum;       // MFMA kernel only, optional: the column sums of the stored output (as rounded to
+    int64_t colsum_g;    //   the output type) are ADDED to colsum[N] per group; the caller zeroes it first
 };
 
 constexpr int GT = 64;   // tile edge

@@ -463,6 +463,10 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
     const Epilogue &ep = P.ep;
     constexpr int PER_ROW = MT / VEC;                  // vectors per tile row
     constexpr int PASSES = MT * PER_ROW / MFMA_THREADS;
+    static_assert(MFMA_THREADS % PER_ROW == 0, "a thread keeps its columns from pass to pass");
+    float csum[VEC];                                   // this thread's share of the column sums (ep.colsum)
+#pragma unroll
+    for (int u = 0; u < VEC; ++u) csum[u] = 0.f;
 #pragma unroll 2
     for (int i = 0; i < PASSES; ++i) {
         const int v = threadIdx.x + i * MFMA_THREADS;
@@ -518,6 +522,26 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
 #pragma unroll
             for (int u = 0; u < VEC; ++u) o[u] = from_f32<TOut>(x[u]);
             *(OutV *)dst = o;
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) csum[u] += (float)o[u];
+        }
+    }
+    if constexpr (!ATOMIC) {
+        if (ep.colsum) {                               // uniform
+            // threads tid, tid + PER_ROW, ... hold partial sums of the same VEC columns: add them up through
+            // LDS (over the fp32 tiles, once every thread has read its share), one atomic per column
+            constexpr int SHARERS = MFMA_THREADS / PER_ROW;
+            float *red = const_cast<float *>(ctile);
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) red[(threadIdx.x / PER_ROW) * MT + (threadIdx.x % PER_ROW) * VEC + u] = csum[u];
+            __syncthreads();
+            if (threadIdx.x < MT && n0 + (int)threadIdx.x < P.N) {
+                float t = 0.f;
+#pragma unroll 8
+                for (int r = 0; r < SHARERS; ++r) t += red[r * MT + threadIdx.x];
+                unsafeAtomicAdd(ep.colsum + g * ep.colsum_g + n0 + threadIdx.x, t);
+            }
         }
     }
 }

@@ -176,7 +176,7 @@ BwdWs carve_bwd(Arena &a, const Geo &g)
 struct StepWs {
     std::vector<void *> Y, A, G;
     void *dYa, *dYb, *dG_send, *dg_own;
-    float *dLw, *dCw, *dDw, *dbias, *mse_partial;
+    float *dLw, *dCw, *dDw, *dbias, *mse_partial;   // dbias: [layers][groups, s], one block
     BwdWs bwd;
 };
 
@@ -197,7 +197,7 @@ StepWs carve_step(Arena &a, const Geo &g)
     w.dLw = (float *)a.take((size_t)g.groups * g.s * g.s * 4);
     w.dCw = (float *)a.take((size_t)g.groups * g.k * g.s * 4 + 16);
     w.dDw = (float *)a.take((size_t)g.groups * g.q * g.s * g.k * 4 + 16);
-    w.dbias = (float *)a.take((size_t)g.groups * g.s * 4);
+    w.dbias = (float *)a.take((size_t)g.layers * g.groups * g.s * 4);
     w.mse_partial = (float *)a.take(MSE_BLOCKS * sizeof(float));
     w.bwd = carve_bwd(a, g);
     return w;
@@ -432,6 +432,10 @@ struct BwdArgs {
     bool dx_S_f32;             // step only: dx_S holds float
     const void *dx_S;          // step only: multiply dX by sigma'(dx_S) on the way out, which makes it the
                                //   previous layer's delta with a single rounding (Eq. (backprop))
+    float *dx_colsum;          // step only: zeroed [groups, s]; the input-gradient product adds the column sums
+                               //   of what it stores, i.e. the layer below's bias gradient (Eq. (bpb))
+    bool dbias_ready;          // step only: dbias already holds the column sums of delta
+    bool dbias_zeroed;         // step only: dbias is zero on entry
 };
 
 template <typename T>
@@ -458,17 +462,19 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
         if (g.dtype == PH_F32) chunks = 1;      // the fp32 path keeps a fixed summation order
         const int rows_per_chunk = (int)((B + chunks - 1) / chunks);
         chunks = (int)((B + rows_per_chunk - 1) / rows_per_chunk);
-        if (chunks > 1) {
+        if (chunks > 1 && !b.dbias_zeroed && !b.dbias_ready) {
             ProfScope prof("clear bias gradient", 0, (int64_t)g.groups * s, 0, 1, st);
             hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks_for((int64_t)g.groups * s)), dim3(256), 0, st, b.dbias,
                                (int64_t)g.groups * s);
             PH_TRY(check_launch("clear bias gradient"));
         }
-        dim3 grid((unsigned)strips, (unsigned)g.groups, (unsigned)chunks);
-        ProfScope prof("bias gradient", 0, act_count, 0, 1, st);
-        hipLaunchKernelGGL((colsum_kernel<T>), grid, dim3(256), 0, st, (const T *)delta, b.dbias, (int)B, (int)s,
-                           rows_per_chunk);
-        PH_TRY(check_launch("bias gradient"));
+        if (!b.dbias_ready) {
+            dim3 grid((unsigned)strips, (unsigned)g.groups, (unsigned)chunks);
+            ProfScope prof("bias gradient", 0, act_count, 0, 1, st);
+            hipLaunchKernelGGL((colsum_kernel<T>), grid, dim3(256), 0, st, (const T *)delta, b.dbias, (int)B, (int)s,
+                               rows_per_chunk);
+            PH_TRY(check_launch("bias gradient"));
+        }
     }
 
     // error compression: dG_send[i] = delta . D_i   ([B, s] x [s, k] for every peer, one product over N = q*k)
@@ -493,6 +499,7 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
         dx.ep.mode = EPI_DACT; dx.ep.act = g.act; dx.ep.aux = const_cast<void *>(b.dx_S); dx.ep.aux_ld = s;
         dx.ep.aux_g = B * s; dx.ep.aux_f32 = b.dx_S_f32;
     }
+    dx.ep.colsum = b.dx_colsum; dx.ep.colsum_g = s;
     dx.M = b.dX ? B : 0; dx.N = s; dx.K = s + k;
 
     const GemmPlan plan_x{LD_KC, LD_KM, g.vec, false};
@@ -604,9 +611,29 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
     PH_TRY(check_launch("loss"));
     }
 
+    // Bias gradients (Eq. (bpb)) are column sums of delta.  On the MFMA path the product that writes a
+    // layer's delta (the input gradient of the layer above) adds them up on its way out, so every
+    // layer's bias gradient has a buffer of its own that is zeroed here, once for the whole step.
+    const bool fused_dbias = std::is_same<T, bf16_t>::value && g.vec > 0;
+    const int64_t bias_count = (int64_t)g.groups * s;
+    auto dbias_of = [&](int l) { return a.dbias ? a.dbias[l] : w.dbias + (int64_t)l * bias_count; };
+    if (a.dbias) {
+        for (int l = 0; l < L; ++l) {
+            hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks_for(bias_count)), dim3(256), 0, st, a.dbias[l], bias_count);
+            PH_TRY(check_launch("clear bias gradients"));
+        }
+    } else {
+        ProfScope prof("clear bias gradients", 0, bias_count * L, 0, 1, st);
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks_for(bias_count * L)), dim3(256), 0, st, w.dbias, bias_count * L);
+        PH_TRY(check_launch("clear bias gradients"));
+    }
+
     void *dY = w.dYa, *dX = w.dYb;    // delta of the current layer / of the layer below
     for (int l = L - 1; l >= 0; --l) {
         BwdArgs b{};
+        b.dbias_zeroed = true;
+        b.dbias_ready = fused_dbias && l < L - 1;
+        b.dx_colsum = (fused_dbias && l > 0) ? dbias_of(l - 1) : nullptr;
         b.delta_ready = dY; b.X = inputs[l];
         b.dx_S = l > 0 ? (g.act == PH_ACT_GELU ? w.A[l - 1] : w.Y[l - 1]) : nullptr;
         b.dx_S_f32 = g.act == PH_ACT_GELU;
@@ -617,7 +644,7 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
         b.dLw = a.dLw ? a.dLw[l] : w.dLw;
         b.dCw = q ? (a.dCw ? a.dCw[l] : w.dCw) : nullptr;
         b.dDw = q ? (a.dDw ? a.dDw[l] : w.dDw) : nullptr;
-        b.dbias = a.dbias ? a.dbias[l] : w.dbias;
+        b.dbias = dbias_of(l);
         b.dG_send = w.dG_send;
         PH_TRY(bwd_impl<T>(g, b, w.bwd, st));
 
