@@ -24,10 +24,14 @@ __global__ __launch_bounds__(256) void delta_kernel(const T *__restrict__ dY, co
 // owns CSUM_COLS columns of one group and rows [chunk*rows_per_chunk, ...): 16-byte loads, row lanes x
 // column lanes, one LDS reduction at the end.  With one chunk the result is stored (deterministic);
 // with several chunks (few columns, many rows) each adds its part atomically into the cleared output.
+// Rider (step only, loss_partial != NULL): workgroup (0,0,0) also adds up the per-workgroup partial
+// sums that the output-error kernel left, in index order, into loss = scale * sum; this kernel is the
+// next one in the stream, and a launch of its own for a 1024-element sum costs 4 us.
 constexpr int CSUM_COLS = 128;
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ delta, float *__restrict__ out, int rows, int cols,
-                                                    int rows_per_chunk)
+                                                    int rows_per_chunk, const float *__restrict__ loss_partial,
+                                                    int n_partial, float scale, float *__restrict__ loss)
 {
     constexpr int VEC = 16 / (int)sizeof(T);            // elements per 16-byte load
     constexpr int CL = CSUM_COLS / VEC;                 // column lanes
@@ -68,6 +72,18 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ delta
             else unsafeAtomicAdd(out + (int64_t)g * cols + c, sum);
         }
     }
+    if (loss_partial && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) {      // uniform
+        __shared__ float lred[256];
+        float acc_l = 0.f;
+        for (int i = threadIdx.x; i < n_partial; i += 256) acc_l += loss_partial[i];
+        lred[threadIdx.x] = acc_l;
+        __syncthreads();
+        for (int w = 128; w > 0; w >>= 1) {
+            if ((int)threadIdx.x < w) lred[threadIdx.x] += lred[threadIdx.x + w];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) *loss = lred[0] * scale;
+    }
 }
 
 // In-memory Reduce-Scatter of Algorithm 1's backward: dg_own[i] = sum_{j != i} dG_send[j][slot of i on j].
@@ -89,24 +105,51 @@ __global__ __launch_bounds__(256) void reduce_scatter_kernel(const T *__restrict
 }
 
 // MSE output error (Section IV-B, "Local error at the output", Eq. (deltaL)):
-// delta_L = ((Y - T) / B) * sigma'(S) with one rounding, and per-block partial sums of (Y - T)^2;
-// mse_final_kernel turns them into loss = 1/(2B) * sum.  S: pre-activation, or the output for ReLU.
-template <typename T>
+// delta_L = ((Y - T) / B) * sigma'(S) with one rounding (Eq. (deltaL) for the MSE loss), and one partial
+// sum of (Y - T)^2 per workgroup (added up by the rider of colsum_kernel).  S: pre-activation, or the
+// output for ReLU.  VEC elements per thread and iteration (VEC > 1: count is a multiple of VEC and
+// every pointer is VEC-element aligned).
+template <typename T, int VEC>
 __global__ __launch_bounds__(256) void mse_delta_kernel(const T *__restrict__ Y, const T *__restrict__ Tg,
                                                        const void *__restrict__ S, int s_f32, T *__restrict__ delta,
                                                        int64_t count, float inv_b, int act,
                                                        float *__restrict__ partial)
 {
+    typedef T TV __attribute__((ext_vector_type(VEC)));
+    typedef float FV __attribute__((ext_vector_type(VEC)));
     __shared__ float red[256];
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) * VEC;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x * VEC;
     float acc = 0.f;
     for (; i < count; i += stride) {
-        float d = to_f32(Y[i]) - to_f32(Tg[i]);
-        acc += d * d;
-        float e = d * inv_b;
-        if (act != ACT_IDENTITY) e *= act_deriv(act, s_f32 ? ((const float *)S)[i] : to_f32(((const T *)S)[i]));
-        delta[i] = from_f32<T>(e);
+        TV y, t, o;
+        FV sv;
+        if constexpr (VEC > 1) {
+            y = *(const TV *)(Y + i);
+            t = *(const TV *)(Tg + i);
+            if (act != ACT_IDENTITY) {
+                if (s_f32) {
+                    sv = *(const FV *)((const float *)S + i);
+                } else {
+                    const TV sraw = *(const TV *)((const T *)S + i);
+#pragma unroll
+                    for (int u = 0; u < VEC; ++u) sv[u] = to_f32((T)sraw[u]);
+                }
+            }
+        } else {
+            y[0] = Y[i]; t[0] = Tg[i];
+            if (act != ACT_IDENTITY) sv[0] = s_f32 ? ((const float *)S)[i] : to_f32(((const T *)S)[i]);
+        }
+#pragma unroll
+        for (int u = 0; u < VEC; ++u) {
+            const float d = to_f32((T)y[u]) - to_f32((T)t[u]);
+            acc += d * d;
+            float e = d * inv_b;
+            if (act != ACT_IDENTITY) e *= act_deriv(act, sv[u]);
+            o[u] = from_f32<T>(e);
+        }
+        if constexpr (VEC > 1) *(TV *)(delta + i) = o;
+        else delta[i] = o[0];
     }
     red[threadIdx.x] = acc;
     __syncthreads();
@@ -115,21 +158,6 @@ __global__ __launch_bounds__(256) void mse_delta_kernel(const T *__restrict__ Y,
         __syncthreads();
     }
     if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
-}
-
-__global__ __launch_bounds__(256) void mse_final_kernel(const float *__restrict__ partial, int n, float scale,
-                                                       float *__restrict__ loss)
-{
-    __shared__ float red[256];
-    float acc = 0.f;
-    for (int i = threadIdx.x; i < n; i += 256) acc += partial[i];
-    red[threadIdx.x] = acc;
-    __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
-        if ((int)threadIdx.x < w) red[threadIdx.x] += red[threadIdx.x + w];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) *loss = red[0] * scale;
 }
 
 // SGD.  fp32 storage: w -= lr * g.  bf16 storage: master -= lr * g, w = bf16(master).

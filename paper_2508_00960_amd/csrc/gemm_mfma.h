@@ -548,7 +548,7 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
 
 #ifdef PHANTOM_TIMELINE   // cycle stamps for the development micro-benchmark, never built into the library
 #define PH_PHASE(slot) do { __builtin_amdgcn_sched_barrier(0); if ((blockIdx.x == 0 || blockIdx.x == gridDim.x - 1) && threadIdx.x == 0) \
-        ((long long *)batch.p[0].ep.aux)[(blockIdx.x ? 8 : 0) + (slot)] = clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
+        ((long long *)batch.p[0].ep.aux)[(blockIdx.x ? 16 : 0) + (slot)] = clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
 #else
 #define PH_PHASE(slot) do { } while (0)
 #endif

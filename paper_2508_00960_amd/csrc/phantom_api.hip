@@ -436,6 +436,10 @@ struct BwdArgs {
                                //   of what it stores, i.e. the layer below's bias gradient (Eq. (bpb))
     bool dbias_ready;          // step only: dbias already holds the column sums of delta
     bool dbias_zeroed;         // step only: dbias is zero on entry
+    const float *loss_partial; // step only, last layer: the bias-gradient kernel also finishes the loss
+    int loss_parts;            //   = loss_scale * sum of loss_partial[0 .. loss_parts)
+    float loss_scale;
+    float *loss;
 };
 
 template <typename T>
@@ -472,7 +476,7 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
             dim3 grid((unsigned)strips, (unsigned)g.groups, (unsigned)chunks);
             ProfScope prof("bias gradient", 0, act_count, 0, 1, st);
             hipLaunchKernelGGL((colsum_kernel<T>), grid, dim3(256), 0, st, (const T *)delta, b.dbias, (int)B, (int)s,
-                               rows_per_chunk);
+                               rows_per_chunk, b.loss_partial, b.loss_parts, b.loss_scale, b.loss);
             PH_TRY(check_launch("bias gradient"));
         }
     }
@@ -597,20 +601,6 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
     }
     if (a.mode == PH_STEP_FORWARD) return PH_OK;
 
-    // output error of the MSE loss, already multiplied by sigma_L' (Eq. (deltaL))
-    const unsigned mse_blocks = blocks_for(act_count, 256, MSE_BLOCKS);
-    {
-    ProfScope prof("output error", 0, act_count, 0, 1, st);
-    hipLaunchKernelGGL((mse_delta_kernel<T>), dim3(mse_blocks), dim3(256), 0, st, (const T *)w.Y[L - 1], (const T *)a.T,
-                       (const void *)(g.act == PH_ACT_GELU ? w.A[L - 1] : w.Y[L - 1]), (int)(g.act == PH_ACT_GELU),
-                       (T *)w.dYa, act_count,
-                       1.0f / (float)B, g.act, w.mse_partial);
-    PH_TRY(check_launch("output error"));
-    hipLaunchKernelGGL(mse_final_kernel, dim3(1), dim3(256), 0, st, (const float *)w.mse_partial, (int)mse_blocks,
-                       0.5f / (float)B, a.loss);
-    PH_TRY(check_launch("loss"));
-    }
-
     // Bias gradients (Eq. (bpb)) are column sums of delta.  On the MFMA path the product that writes a
     // layer's delta (the input gradient of the layer above) adds them up on its way out, so every
     // layer's bias gradient has a buffer of its own that is zeroed here, once for the whole step.
@@ -628,10 +618,30 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
         PH_TRY(check_launch("clear bias gradients"));
     }
 
+    // output error of the MSE loss, already multiplied by sigma_L' (Eq. (deltaL)); the loss's partial sums are
+    // added up by the last layer's bias-gradient kernel, the next launch
+    unsigned mse_blocks = 0;
+    {
+        const void *S = g.act == PH_ACT_GELU ? w.A[L - 1] : w.Y[L - 1];
+        const bool wide = act_count % 8 == 0 && (((uintptr_t)a.T | (uintptr_t)w.Y[L - 1] | (uintptr_t)S | (uintptr_t)w.dYa) & 31) == 0;
+        mse_blocks = blocks_for(wide ? act_count / 8 : act_count, 256, MSE_BLOCKS);
+        ProfScope prof("output error", 0, act_count, 0, 1, st);
+        if (wide)
+            hipLaunchKernelGGL((mse_delta_kernel<T, 8>), dim3(mse_blocks), dim3(256), 0, st, (const T *)w.Y[L - 1],
+                               (const T *)a.T, S, (int)(g.act == PH_ACT_GELU), (T *)w.dYa, act_count, 1.0f / (float)B, g.act,
+                               w.mse_partial);
+        else
+            hipLaunchKernelGGL((mse_delta_kernel<T, 1>), dim3(mse_blocks), dim3(256), 0, st, (const T *)w.Y[L - 1],
+                               (const T *)a.T, S, (int)(g.act == PH_ACT_GELU), (T *)w.dYa, act_count, 1.0f / (float)B, g.act,
+                               w.mse_partial);
+        PH_TRY(check_launch("output error"));
+    }
+
     void *dY = w.dYa, *dX = w.dYb;    // delta of the current layer / of the layer below
     for (int l = L - 1; l >= 0; --l) {
         BwdArgs b{};
         b.dbias_zeroed = true;
+        if (l == L - 1) { b.loss_partial = w.mse_partial; b.loss_parts = (int)mse_blocks; b.loss_scale = 0.5f / (float)B; b.loss = a.loss; }
         b.dbias_ready = fused_dbias && l < L - 1;
         b.dx_colsum = (fused_dbias && l > 0) ? dbias_of(l - 1) : nullptr;
         b.delta_ready = dY; b.X = inputs[l];
