@@ -160,24 +160,39 @@ __global__ __launch_bounds__(256) void mse_delta_kernel(const T *__restrict__ Y,
     if (threadIdx.x == 0) partial[blockIdx.x] = red[0];
 }
 
-// SGD.  fp32 storage: w -= lr * g.  bf16 storage: master -= lr * g, w = bf16(master).
-__global__ __launch_bounds__(256) void sgd_f32_kernel(float *__restrict__ w, const float *__restrict__ g, float lr,
-                                                     int64_t count)
-{
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (; i < count; i += stride) w[i] = w[i] - lr * g[i];
-}
+// SGD on the (up to four) parameter tensors of one layer in one launch; blockIdx.y picks the tensor.
+// fp32 storage: w -= lr * g.  bf16 storage: master -= lr * g, w = bf16(master).
+struct SgdTensor {
+    void *w;             // storage-type weights
+    float *master;       // bf16 storage: fp32 master copy
+    const float *grad;
+    int64_t count;
+};
+struct SgdBatch {
+    SgdTensor t[4];
+};
 
-__global__ __launch_bounds__(256) void sgd_bf16_kernel(float *__restrict__ master, bf16_t *__restrict__ w,
-                                                      const float *__restrict__ g, float lr, int64_t count)
+template <typename T>
+__global__ __launch_bounds__(256) void sgd_kernel(SgdBatch batch, float lr)
 {
+    // fixed-index copies selected by value: indexing the argument block with blockIdx.y would make
+    // every access a dependent load
+    SgdTensor t = batch.t[0];
+    if (blockIdx.y == 1) t = batch.t[1];
+    if (blockIdx.y == 2) t = batch.t[2];
+    if (blockIdx.y == 3) t = batch.t[3];
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (; i < count; i += stride) {
-        float m = master[i] - lr * g[i];
-        master[i] = m;
-        w[i] = from_f32<bf16_t>(m);
+    if constexpr (sizeof(T) == 4) {
+        float *w = (float *)t.w;
+        for (; i < t.count; i += stride) w[i] = w[i] - lr * t.grad[i];
+    } else {
+        T *w = (T *)t.w;
+        for (; i < t.count; i += stride) {
+            const float m = t.master[i] - lr * t.grad[i];
+            t.master[i] = m;
+            w[i] = from_f32<T>(m);
+        }
     }
 }
 

@@ -667,15 +667,18 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
             {q ? a.Cw[l] : nullptr, (q && a.Cw_master) ? a.Cw_master[l] : nullptr, b.dCw, (int64_t)g.groups * k * s},
             {q ? a.Dw[l] : nullptr, (q && a.Dw_master) ? a.Dw_master[l] : nullptr, b.dDw, (int64_t)g.groups * q * s * k},
         };
+        SgdBatch batch{};
+        int tensors = 0;
+        int64_t largest = 0, total = 0;
         for (const Upd &u : upd) {
             if (!u.w || u.count == 0) continue;
-            ProfScope prof("SGD update", 0, u.count, 0, 1, st);
-            if (g.dtype == PH_F32)
-                hipLaunchKernelGGL(sgd_f32_kernel, dim3(blocks_for(u.count)), dim3(256), 0, st, (float *)u.w, u.grad, a.lr,
-                                   u.count);
-            else
-                hipLaunchKernelGGL(sgd_bf16_kernel, dim3(blocks_for(u.count)), dim3(256), 0, st, u.master, (bf16_t *)u.w,
-                                   u.grad, a.lr, u.count);
+            batch.t[tensors++] = SgdTensor{u.w, u.master, u.grad, u.count};
+            largest = std::max(largest, u.count);
+            total += u.count;
+        }
+        if (tensors > 0) {
+            ProfScope prof("SGD update", 0, total, 0, 1, st);
+            hipLaunchKernelGGL((sgd_kernel<T>), dim3(blocks_for(largest, 256, 2048), (unsigned)tensors), dim3(256), 0, st, batch, a.lr);
             PH_TRY(check_launch("SGD update"));
         }
         void *t = dY; dY = dX; dX = t;
