@@ -35,6 +35,10 @@ WORKLOADS = {
     "c5k16": (8192, 8, 16, 8192, 6, "relu", "bf16", 0, "forward", 0.0),
     "c5k64": (8192, 8, 64, 8192, 6, "relu", "bf16", 0, "forward", 0.0),
     "c5k256": (8192, 8, 256, 8192, 6, "relu", "bf16", 0, "forward", 0.0),
+    # configuration 2 generalised to more ranks on the one device (grouped products, in-memory gather / reduce)
+    "a16": (8192, 16, 32, 1024, 4, "relu", "bf16", -1, "no_update", 0.0),
+    "a32": (8192, 32, 16, 1024, 4, "relu", "bf16", -1, "no_update", 0.0),
+    "a64": (16384, 64, 8, 512, 4, "relu", "bf16", -1, "no_update", 0.0),
 }
 
 

@@ -13,7 +13,7 @@
 //   LD_KC  the reduction index is contiguous in memory (X, G, L, D in the forward; delta in dX).
 //          LDS tile [128 rows][64 + 8]; a lane's MFMA operand is one 16-byte LDS read.
 //   LD_KM  the free index is contiguous, the reduction index strides (L, C, D in dX and error
-//          compression; delta, X, G in the weight gradients).  LDS tile [64][128 + 16]; the MFMA
+//          compression; delta, X, G in the weight gradients).  LDS tile [64][128 + 32]; the MFMA
 //          operand is built by two ds_read_b64_tr_b16 (the gfx950 transposing LDS read: within 16
 //          lanes, lanes 4j..4j+3 supply row j of a 4 x 16 block, lane i receives column i).
 // The peers' segments (G_i, D_i) are addressed in place through the View; VEC (8, 4 or 2
@@ -39,9 +39,14 @@ enum { LD_KC = 0, LD_KM = 1 };
 constexpr int MT = 128;               // tile rows (m) and columns (n)
 constexpr int KT = 64;                // reduction step
 constexpr int KC_PITCH = KT + 8;      // elements per LDS row, K-contiguous tile [128][72]
-constexpr int KM_PITCH = MT + 16;     // elements per LDS row, K-major tile [64][144]
-constexpr int TILE_ELEMS = MT * KC_PITCH;   // = KT * KM_PITCH = 9216
-static_assert(MT * KC_PITCH == KT * KM_PITCH, "both tile shapes use the same LDS space");
+#ifndef PH_KM_PITCH
+#define PH_KM_PITCH (MT + 32)
+#endif
+// elements per LDS row, K-major tile [64][160]: 80 words = 16 mod 64, so the four rows that 16 lanes of a
+// transposing read touch start 16 banks apart and the next 16 lanes (16 columns = 8 banks further) fall between
+// them; with 144 the two half-groups met on the same banks (SQ_LDS_BANK_CONFLICT: a quarter of the LDS cycles)
+constexpr int KM_PITCH = PH_KM_PITCH;
+constexpr int TILE_ELEMS = (MT * KC_PITCH > KT * KM_PITCH) ? MT * KC_PITCH : KT * KM_PITCH;   // one operand stage
 constexpr int MFMA_THREADS = 512;       // two teams of four wavefronts
 constexpr int MFMA_LDS_BYTES = 2 /*teams*/ * 2 /*stages*/ * 2 /*operands*/ * TILE_ELEMS * 2;
 

@@ -132,6 +132,9 @@ ALL_RANK_CASES = [
     (48, 1, 0, 20, "relu", "f32"),
     (1024, 8, 32, 136, "relu", "bf16"),
     (792, 6, 10, 70, "gelu", "bf16"),
+    # many ranks on the device (grouped products with 16 / 64 groups, the skipped slot moves with the group)
+    (2048, 16, 8, 200, "relu", "bf16"),
+    (4096, 64, 4, 96, "gelu", "bf16"),
 ]
 
 
@@ -252,12 +255,45 @@ def test_step_tiny_fp32_all_ranks():
     (1024, 8, 16, 136, 3, "gelu", "bf16", -1),
     (792, 6, 10, 70, 2, "identity", "bf16", 3),
     (2048, 16, 32, 200, 4, "gelu", "bf16", 0),
+    (2048, 16, 8, 136, 2, "gelu", "bf16", -1),
+    (2048, 32, 4, 72, 2, "gelu", "bf16", -1),
 ])
 def test_step_smooth_activations(n, p, k, B, L, act, dtype, rank):
     print(f"case step n={n} p={p} k={k} B={B} L={L} {act} {dtype} rank={rank}", flush=True)
     prob = pin.Problem(n=n, p=p, k=k, batch=B, layers=L, act=act, dtype=dtype, rank=rank)
     out = run_step(prob, seed=3, lr=0.05)
     check_step(prob, *out, 0.05)
+
+
+def test_training_several_steps_fp32():
+    """Five SGD steps in a row (weights updated in place by one call feed the next) against the oracle
+    taking the same five steps: the loss of every step and the final weights."""
+    prob = pin.Problem(n=256, p=4, k=8, batch=40, layers=2, act="gelu", dtype="f32", rank=-1)
+    lr, steps = 0.05, 5
+    data = pin.all_rank_step_inputs(prob, seed=7)
+    layers = [dict(P) for P in data["layers"]]
+    want_loss = []
+    for _ in range(steps):
+        ref = oracle.ffn_step("gelu", data["X0"], data["T"], layers, lr, storage="f32", all_ranks=True)
+        want_loss.append(ref["loss"])
+        layers = ref["layers"]
+    pc = _prob_c(prob)
+    ws = workspace(ph.workspace_bytes(pc))
+    names = ("Lw", "Cw", "Dw", "bias")
+    W = {nm: [to_gpu(P[nm], "f32") for P in data["layers"]] for nm in names}
+    X0, T = to_gpu(data["X0"], "f32"), to_gpu(data["T"], "f32")
+    loss = empty_f32((4,))
+    got_loss = []
+    for _ in range(steps):
+        ph.ffn_step(pc, X0, T, W["Lw"], W["Cw"], W["Dw"], W["bias"], loss=loss, lr=lr, workspace=ws)
+        torch.cuda.synchronize()
+        got_loss.append(float(loss[0]))
+    assert want_loss[-1] < want_loss[0]                       # the oracle's own loss goes down
+    for g, w in zip(got_loss, want_loss):
+        assert abs(g - w) <= 1e-5 * abs(w), (got_loss, want_loss)
+    for l in range(prob.layers):
+        for nm in names:
+            assert_close(f"{nm}[{l}] after {steps} steps", W[nm][l], layers[l][nm], "f32", 5e-5)
 
 
 def test_step_forward_only():
