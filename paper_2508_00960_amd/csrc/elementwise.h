@@ -88,20 +88,49 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ delta
 
 // In-memory Reduce-Scatter of Algorithm 1's backward: dg_own[i] = sum_{j != i} dG_send[j][slot of i on j].
 // dG_send [p, p-1, B*k], dg_own [p, B*k]; on holder j, source i sits in slot i (i < j) or i-1 (i > j).
-template <typename T>
+// A workgroup owns 32 * VEC consecutive elements of one receiver: thread = (element vector, sender lane);
+// sender lane g adds the senders g, g + 8, g + 16, ... in fp32, the eight partial sums are added in lane
+// order through LDS (a fixed order, whatever p is).  With one thread walking all p-1 senders the kernel
+// was bound by the latency of its own loads (33 MB in 24 us at p = 64).
+constexpr int RS_LANES = 8;
+template <typename T, int VEC>
 __global__ __launch_bounds__(256) void reduce_scatter_kernel(const T *__restrict__ dG_send, T *__restrict__ dg_own,
                                                             int p, int64_t per_slot)
 {
-    const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    typedef T TV __attribute__((ext_vector_type(VEC)));
+    __shared__ float part[RS_LANES][32 * VEC + 1];
+    const int ev = threadIdx.x & 31, lane = threadIdx.x >> 5;
+    const int64_t e = ((int64_t)blockIdx.x * 32 + ev) * VEC;
     const int i = blockIdx.y;
-    if (e >= per_slot) return;
-    float acc = 0.f;
-    for (int j = 0; j < p; ++j) {
-        if (j == i) continue;
-        const int slot = i < j ? i : i - 1;
-        acc += to_f32(dG_send[((int64_t)j * (p - 1) + slot) * per_slot + e]);
+    float acc[VEC];
+#pragma unroll
+    for (int u = 0; u < VEC; ++u) acc[u] = 0.f;
+    if (e < per_slot) {
+        for (int j = lane; j < p; j += RS_LANES) {
+            if (j == i) continue;
+            const int slot = i < j ? i : i - 1;
+            const T *src = dG_send + ((int64_t)j * (p - 1) + slot) * per_slot + e;
+            if constexpr (VEC > 1) {
+                const TV v = *(const TV *)src;
+#pragma unroll
+                for (int u = 0; u < VEC; ++u) acc[u] += to_f32((T)v[u]);
+            } else {
+                acc[0] += to_f32(src[0]);
+            }
+        }
     }
-    dg_own[(int64_t)i * per_slot + e] = from_f32<T>(acc);
+#pragma unroll
+    for (int u = 0; u < VEC; ++u) part[lane][ev * VEC + u] = acc[u];
+    __syncthreads();
+    // 256 threads, 32 * VEC elements: thread t finishes elements t, t + 256, ...
+    for (int c = threadIdx.x; c < 32 * VEC; c += 256) {
+        const int64_t at = (int64_t)blockIdx.x * 32 * VEC + c;
+        if (at >= per_slot) continue;
+        float sum = 0.f;
+#pragma unroll
+        for (int g = 0; g < RS_LANES; ++g) sum += part[g][c];
+        dg_own[(int64_t)i * per_slot + at] = from_f32<T>(sum);
+    }
 }
 
 // MSE output error (Section IV-B, "Local error at the output", Eq. (deltaL)):

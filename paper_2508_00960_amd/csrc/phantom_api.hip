@@ -516,10 +516,17 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
         PH_TRY((launch_products<T, T>(plan_x, &send, 1, g.groups, st, "error compression")));
         if (q > 0) {
             const int64_t per_slot = B * k;
-            dim3 grid((unsigned)((per_slot + 255) / 256), (unsigned)g.p);
+            constexpr int RS_VEC = 16 / (int)sizeof(T);
+            const bool wide = per_slot % RS_VEC == 0 && (((uintptr_t)b.dG_send | (uintptr_t)b.dg_own) & 15) == 0;
+            const int64_t per_wg = 32 * (wide ? RS_VEC : 1);
+            dim3 grid((unsigned)((per_slot + per_wg - 1) / per_wg), (unsigned)g.p);
             ProfScope prof("reduce-scatter", 0, per_slot * g.p * (g.p - 1), 0, 1, st);
-            hipLaunchKernelGGL((reduce_scatter_kernel<T>), grid, dim3(256), 0, st, (const T *)b.dG_send, (T *)b.dg_own,
-                               (int)g.p, per_slot);
+            if (wide)
+                hipLaunchKernelGGL((reduce_scatter_kernel<T, RS_VEC>), grid, dim3(256), 0, st, (const T *)b.dG_send,
+                                   (T *)b.dg_own, (int)g.p, per_slot);
+            else
+                hipLaunchKernelGGL((reduce_scatter_kernel<T, 1>), grid, dim3(256), 0, st, (const T *)b.dG_send,
+                                   (T *)b.dg_own, (int)g.p, per_slot);
             PH_TRY(check_launch("reduce-scatter"));
         }
         PH_TRY((launch_products<T, T>(plan_x, &dx, 1, g.groups, st, "input gradient")));
