@@ -81,12 +81,15 @@ __device__ __forceinline__ V load_global(const __bf16 *p)
 // last valid row; what they produce lands in outputs the epilogue never writes.  A tile that
 // reaches past the end of the reduction range takes the slow path: indices are clamped to the last
 // valid position and the store zeroes what was loaded for reduction indices >= c_lim.
-template <int KIND, int VEC>
+// PART = 2: the 256 threads of a team stage only half of the tile's rows (the other team stages the
+// other half of an operand tile that both teams read; see the DUAL mode of gemm_mfma_kernel)
+template <int KIND, int VEC, int PART = 1>
 struct StageCfg {
     typedef typename VecOf<VEC>::type V;
     static constexpr int PER_ROW = (KIND == LD_KC ? KT : MT) / VEC;   // vectors per LDS row
     static constexpr int ROWS = KIND == LD_KC ? MT : KT;
-    static constexpr int NV = ROWS * PER_ROW / 256;                   // vectors per thread
+    static constexpr int NV = ROWS * PER_ROW / 256 / PART;            // vectors per thread
+    static_assert(NV >= 1 && NV * 256 * PART == ROWS * PER_ROW, "the team's threads tile its share of the rows");
     static constexpr int ROW_STEP = 256 / PER_ROW;
     static constexpr int PITCH = KIND == LD_KC ? KC_PITCH : KM_PITCH;
 };
@@ -109,17 +112,18 @@ struct StageState {          // scalars only, so that it lives in registers
 
 // off0[j], off1[j]: element offsets of the thread's j-th vector that do not depend on the step, in
 // region 0 and region 1.  LD_KC: row * row stride.  LD_KM: fixed free-index offset + (row0 + j*ROW_STEP) * c stride.
-template <int KIND, int VEC>
+template <int KIND, int VEC, int PART = 1>
 __device__ __forceinline__ StageState stage_init(const View &v, int g, int r0, int r_limit, int c_limit, int tid,
-                                                 int (&off0)[StageCfg<KIND, VEC>::NV], int (&off1)[StageCfg<KIND, VEC>::NV])
+                                                 int (&off0)[StageCfg<KIND, VEC, PART>::NV],
+                                                 int (&off1)[StageCfg<KIND, VEC, PART>::NV], int row_shift = 0)
 {
-    typedef StageCfg<KIND, VEC> C;
+    typedef StageCfg<KIND, VEC, PART> C;
     StageState s;
     s.base0 = (const __bf16 *)v.p0 + g * v.g0;
     s.base1 = (const __bf16 *)v.p1 + g * v.g1;
     const int skip = v.skip0 + g * v.skip_g;
     s.col = (tid % C::PER_ROW) * VEC;
-    s.row0 = tid / C::PER_ROW;
+    s.row0 = tid / C::PER_ROW + row_shift;           // row_shift: first row of this team's share (PART = 2)
     s.c_lim = c_limit;
     s.c_decides = v.c.decides;
     s.c_split = v.c.decides ? v.c.split : 0x7fffffff;
@@ -162,12 +166,12 @@ __device__ __forceinline__ StageState stage_init(const View &v, int g, int r0, i
 
 // issue the global loads of vectors J0 .. J1-1 of the tile whose reduction index starts at c0 (any shape).
 // CAREFUL = false: the caller guarantees c0 + KT <= c_lim (a full interior tile).
-template <int KIND, int VEC, bool CAREFUL, int J0 = 0, int J1 = StageCfg<KIND, VEC>::NV>
-__device__ __forceinline__ void stage_fetch(const StageState &s, const int (&off0)[StageCfg<KIND, VEC>::NV],
-                                            const int (&off1)[StageCfg<KIND, VEC>::NV],
-                                            typename VecOf<VEC>::type (&regs)[StageCfg<KIND, VEC>::NV], int c0)
+template <int KIND, int VEC, bool CAREFUL, int PART = 1, int J0 = 0, int J1 = StageCfg<KIND, VEC, PART>::NV>
+__device__ __forceinline__ void stage_fetch(const StageState &s, const int (&off0)[StageCfg<KIND, VEC, PART>::NV],
+                                            const int (&off1)[StageCfg<KIND, VEC, PART>::NV],
+                                            typename VecOf<VEC>::type (&regs)[StageCfg<KIND, VEC, PART>::NV], int c0)
 {
-    typedef StageCfg<KIND, VEC> C;
+    typedef StageCfg<KIND, VEC, PART> C;
     typedef typename C::V V;
     const bool interior = !CAREFUL || c0 + KT <= s.c_lim;   // uniform
     if (KIND == LD_KC) {
@@ -237,12 +241,12 @@ __device__ __forceinline__ FastStep fast_step_addr(const StageState &s, int c0 /
     return f;
 }
 
-template <int KIND, int VEC, int J0, int J1>
-__device__ __forceinline__ void fast_fetch(const FastStep &f, const int (&off0)[StageCfg<KIND, VEC>::NV],
-                                           const int (&off1)[StageCfg<KIND, VEC>::NV],
-                                           typename VecOf<VEC>::type (&regs)[StageCfg<KIND, VEC>::NV])
+template <int KIND, int VEC, int PART, int J0, int J1>
+__device__ __forceinline__ void fast_fetch(const FastStep &f, const int (&off0)[StageCfg<KIND, VEC, PART>::NV],
+                                           const int (&off1)[StageCfg<KIND, VEC, PART>::NV],
+                                           typename VecOf<VEC>::type (&regs)[StageCfg<KIND, VEC, PART>::NV])
 {
-    typedef typename StageCfg<KIND, VEC>::V V;
+    typedef typename StageCfg<KIND, VEC, PART>::V V;
 #pragma unroll
     for (int j = J0; j < J1; ++j) {
         const int o0 = off0[j], o1 = off1[j];          // values first: a conditional on the array elements themselves
@@ -252,11 +256,11 @@ __device__ __forceinline__ void fast_fetch(const FastStep &f, const int (&off0)[
 }
 
 // move vectors J0 .. J1-1 of the tile fetched for reduction start c0 into LDS; CAREFUL zeroes reduction indices >= c_lim
-template <int KIND, int VEC, bool CAREFUL, int J0 = 0, int J1 = StageCfg<KIND, VEC>::NV>
-__device__ __forceinline__ void stage_store(const StageState &s, const typename VecOf<VEC>::type (&regs)[StageCfg<KIND, VEC>::NV],
+template <int KIND, int VEC, bool CAREFUL, int PART = 1, int J0 = 0, int J1 = StageCfg<KIND, VEC, PART>::NV>
+__device__ __forceinline__ void stage_store(const StageState &s, const typename VecOf<VEC>::type (&regs)[StageCfg<KIND, VEC, PART>::NV],
                                             __bf16 *tile, int c0)
 {
-    typedef StageCfg<KIND, VEC> C;
+    typedef StageCfg<KIND, VEC, PART> C;
     typedef typename C::V V;
     __bf16 *dst = tile + s.row0 * C::PITCH + s.col;
 #pragma unroll
@@ -324,17 +328,18 @@ __device__ __forceinline__ void mfma_tile(f32x16 (&acc)[2][2], const __bf16 *ta,
 // this order the LDS writes (128 B/clk) and the global loads (64 B/clk through the vector L1, which
 // for a 128 x 128 tile is as many cycles as the MFMAs themselves) run under the MFMAs instead of
 // before them.
-template <int KA, int KB, int VA, int VB, bool CAREFUL, int Q>
+template <int KA, int KB, int VA, int VB, bool CAREFUL, int Q, int BP>
 __device__ __forceinline__ void fused_quarter(f32x16 (&acc)[2][2], const __bf16 *ta, const __bf16 *tb, int wm, int wn, int lane,
                                               const StageState &sa, const int (&a_off0)[StageCfg<KA, VA>::NV],
                                               const int (&a_off1)[StageCfg<KA, VA>::NV],
                                               typename VecOf<VA>::type (&ra)[StageCfg<KA, VA>::NV], __bf16 *na,
-                                              const StageState &sb, const int (&b_off0)[StageCfg<KB, VB>::NV],
-                                              const int (&b_off1)[StageCfg<KB, VB>::NV],
-                                              typename VecOf<VB>::type (&rb)[StageCfg<KB, VB>::NV], __bf16 *nb,
+                                              const StageState &sb, const int (&b_off0)[StageCfg<KB, VB, BP>::NV],
+                                              const int (&b_off1)[StageCfg<KB, VB, BP>::NV],
+                                              typename VecOf<VB>::type (&rb)[StageCfg<KB, VB, BP>::NV], __bf16 *nb,
                                               int c_store, int c_fetch)
 {
-    constexpr int PA = StageCfg<KA, VA>::NV / 4, PB = StageCfg<KB, VB>::NV / 4;
+    constexpr int NA = StageCfg<KA, VA>::NV, NB = StageCfg<KB, VB, BP>::NV;
+    constexpr int A0 = Q * NA / 4, A1 = (Q + 1) * NA / 4, B0 = Q * NB / 4, B1 = (Q + 1) * NB / 4;   // this quarter's vectors
     bf16x8 av[2], bv[2];
     av[0] = lds_operand<KA>(ta, wm, Q, lane);
     av[1] = lds_operand<KA>(ta, wm + 32, Q, lane);
@@ -345,10 +350,10 @@ __device__ __forceinline__ void fused_quarter(f32x16 (&acc)[2][2], const __bf16 
 #pragma unroll
         for (int j = 0; j < 2; ++j)
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bv[j], av[i], acc[i][j], 0, 0, 0);   // B first: see acc_to_lds
-    stage_store<KA, VA, CAREFUL, Q * PA, (Q + 1) * PA>(sa, ra, na, c_store);
-    stage_store<KB, VB, CAREFUL, Q * PB, (Q + 1) * PB>(sb, rb, nb, c_store);
-    stage_fetch<KA, VA, CAREFUL, Q * PA, (Q + 1) * PA>(sa, a_off0, a_off1, ra, c_fetch);
-    stage_fetch<KB, VB, CAREFUL, Q * PB, (Q + 1) * PB>(sb, b_off0, b_off1, rb, c_fetch);
+    stage_store<KA, VA, CAREFUL, 1, A0, A1>(sa, ra, na, c_store);
+    stage_store<KB, VB, CAREFUL, BP, B0, B1>(sb, rb, nb, c_store);
+    stage_fetch<KA, VA, CAREFUL, 1, A0, A1>(sa, a_off0, a_off1, ra, c_fetch);
+    stage_fetch<KB, VB, CAREFUL, BP, B0, B1>(sb, b_off0, b_off1, rb, c_fetch);
 }
 
 // One reduction step of the fast path.  Per quarter kk (16 of the 64 reduction indices):
@@ -373,23 +378,23 @@ __device__ __forceinline__ void read_operands(bf16x8 (&f)[4], const __bf16 *ta, 
 
 constexpr int part_lo(int n, int q) { return n * q / 3; }       // the q-th third of n vectors
 
-template <int KA, int KB, int VA, int VB>
+template <int KA, int KB, int VA, int VB, int BP>
 __device__ __forceinline__ void fast_step(f32x16 (&acc)[2][2], bf16x8 (&fr)[2][4], const __bf16 *ta, const __bf16 *tb,
                                           int wm, int wn, int lane,
                                           const StageState &sa, const int (&a_off0)[StageCfg<KA, VA>::NV],
                                           const int (&a_off1)[StageCfg<KA, VA>::NV],
                                           typename VecOf<VA>::type (&ra)[StageCfg<KA, VA>::NV], __bf16 *na,
-                                          const StageState &sb, const int (&b_off0)[StageCfg<KB, VB>::NV],
-                                          const int (&b_off1)[StageCfg<KB, VB>::NV],
-                                          typename VecOf<VB>::type (&rb)[StageCfg<KB, VB>::NV], __bf16 *nb, int c_fetch)
+                                          const StageState &sb, const int (&b_off0)[StageCfg<KB, VB, BP>::NV],
+                                          const int (&b_off1)[StageCfg<KB, VB, BP>::NV],
+                                          typename VecOf<VB>::type (&rb)[StageCfg<KB, VB, BP>::NV], __bf16 *nb, int c_fetch)
 {
-    constexpr int NA = StageCfg<KA, VA>::NV, NB = StageCfg<KB, VB>::NV;
+    constexpr int NA = StageCfg<KA, VA>::NV, NB = StageCfg<KB, VB, BP>::NV;
     const FastStep fa = fast_step_addr<KA, VA>(sa, c_fetch), fb = fast_step_addr<KB, VB>(sb, c_fetch);
 #define PH_MFMA(buf, i, j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[buf][2 + j], fr[buf][i], acc[i][j], 0, 0, 0)
-#define PH_STORE_A(q) stage_store<KA, VA, false, part_lo(NA, q), part_lo(NA, q + 1)>(sa, ra, na, 0)
-#define PH_STORE_B(q) stage_store<KB, VB, false, part_lo(NB, q), part_lo(NB, q + 1)>(sb, rb, nb, 0)
-#define PH_FETCH_A(q) fast_fetch<KA, VA, part_lo(NA, q), part_lo(NA, q + 1)>(fa, a_off0, a_off1, ra)
-#define PH_FETCH_B(q) fast_fetch<KB, VB, part_lo(NB, q), part_lo(NB, q + 1)>(fb, b_off0, b_off1, rb)
+#define PH_STORE_A(q) stage_store<KA, VA, false, 1, part_lo(NA, q), part_lo(NA, q + 1)>(sa, ra, na, 0)
+#define PH_STORE_B(q) stage_store<KB, VB, false, BP, part_lo(NB, q), part_lo(NB, q + 1)>(sb, rb, nb, 0)
+#define PH_FETCH_A(q) fast_fetch<KA, VA, 1, part_lo(NA, q), part_lo(NA, q + 1)>(fa, a_off0, a_off1, ra)
+#define PH_FETCH_B(q) fast_fetch<KB, VB, BP, part_lo(NB, q), part_lo(NB, q + 1)>(fb, b_off0, b_off1, rb)
 #define PH_PIN __builtin_amdgcn_sched_barrier(0)   /* the compiler's scheduler would regroup the sequence */
     // quarter 0
     PH_PIN; read_operands<KA, KB>(fr[1], ta, tb, wm, wn, 1, lane); PH_PIN;
@@ -456,10 +461,12 @@ __device__ __forceinline__ void acc_to_lds(float *ctile, const f32x16 (&acc)[2][
 
 template <typename T, int VEC> struct PackOf { typedef T type __attribute__((ext_vector_type(VEC))); };
 
-// rows [m0, m0+128) x columns [n0, n0+128) of the output = sum of the two teams' fp32 tiles in LDS
-template <int VEC, typename TOut, bool ATOMIC>
-__device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, const float *ctile, int m0, int n0)
+// rows [m0, m0+128) x columns [n0, n0+128) of the output = sum of the two teams' fp32 tiles in LDS, walked by
+// all 512 threads; SOLO: the tile at ctile alone, walked by the 256 threads of one team (thread = 0..255)
+template <int VEC, typename TOut, bool ATOMIC, bool SOLO>
+__device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, const float *ctile, int m0, int n0, int thread)
 {
+    constexpr int THREADS = SOLO ? 256 : MFMA_THREADS;
     typedef typename PackOf<TOut, VEC>::type OutV;
     typedef typename PackOf<__bf16, VEC>::type BfV;
     typedef typename PackOf<float, VEC>::type FlV;
@@ -467,23 +474,28 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
     const int skip_o = P.o.skip0 + g * P.o.skip_g;
     const Epilogue &ep = P.ep;
     constexpr int PER_ROW = MT / VEC;                  // vectors per tile row
-    constexpr int PASSES = MT * PER_ROW / MFMA_THREADS;
-    static_assert(MFMA_THREADS % PER_ROW == 0, "a thread keeps its columns from pass to pass");
+    constexpr int PASSES = MT * PER_ROW / THREADS;
+    static_assert(THREADS % PER_ROW == 0, "a thread keeps its columns from pass to pass");
     float csum[VEC];                                   // this thread's share of the column sums (ep.colsum)
 #pragma unroll
     for (int u = 0; u < VEC; ++u) csum[u] = 0.f;
 #pragma unroll 2
     for (int i = 0; i < PASSES; ++i) {
-        const int v = threadIdx.x + i * MFMA_THREADS;
+        const int v = thread + i * THREADS;
         const int row = v / PER_ROW, col = (v % PER_ROW) * VEC;
         const int m = m0 + row, n = n0 + col;
         if (m >= P.M || n >= P.N) continue;
         float x[VEC];
         {
             const FlV c0 = *(const FlV *)(ctile + row * CT_PITCH + col);
-            const FlV c1 = *(const FlV *)(ctile + CT_ELEMS + row * CT_PITCH + col);
+            if constexpr (SOLO) {
 #pragma unroll
-            for (int u = 0; u < VEC; ++u) x[u] = c0[u] + c1[u];
+                for (int u = 0; u < VEC; ++u) x[u] = c0[u];
+            } else {
+                const FlV c1 = *(const FlV *)(ctile + CT_ELEMS + row * CT_PITCH + col);
+#pragma unroll
+                for (int u = 0; u < VEC; ++u) x[u] = c0[u] + c1[u];
+            }
         }
         const int64_t aux_at = g * ep.aux_g + (int64_t)m * ep.aux_ld + n;
         if (ep.mode == EPI_BIAS_ACT) {
@@ -535,17 +547,17 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
         if (ep.colsum) {                               // uniform
             // threads tid, tid + PER_ROW, ... hold partial sums of the same VEC columns: add them up through
             // LDS (over the fp32 tiles, once every thread has read its share), one atomic per column
-            constexpr int SHARERS = MFMA_THREADS / PER_ROW;
-            float *red = const_cast<float *>(ctile);
+            constexpr int SHARERS = THREADS / PER_ROW;
+            float *red = const_cast<float *>(ctile);       // SOLO: each team reduces over its own tile
             __syncthreads();
 #pragma unroll
-            for (int u = 0; u < VEC; ++u) red[(threadIdx.x / PER_ROW) * MT + (threadIdx.x % PER_ROW) * VEC + u] = csum[u];
+            for (int u = 0; u < VEC; ++u) red[(thread / PER_ROW) * MT + (thread % PER_ROW) * VEC + u] = csum[u];
             __syncthreads();
-            if (threadIdx.x < MT && n0 + (int)threadIdx.x < P.N) {
+            if (thread < MT && n0 + thread < P.N) {
                 float t = 0.f;
 #pragma unroll 8
-                for (int r = 0; r < SHARERS; ++r) t += red[r * MT + threadIdx.x];
-                unsafeAtomicAdd(ep.colsum + g * ep.colsum_g + n0 + threadIdx.x, t);
+                for (int r = 0; r < SHARERS; ++r) t += red[r * MT + thread];
+                unsafeAtomicAdd(ep.colsum + g * ep.colsum_g + n0 + thread, t);
             }
         }
     }
@@ -584,10 +596,17 @@ __device__ __forceinline__ MfmaParams pick_params(bool second, const MfmaParams 
     return out.p;
 }
 
-template <int KA, int KB, int VA, int VB, typename TOut, bool ATOMIC, bool PAIR>
+// DUAL: the two teams take two tiles that lie one above the other (rows m0 .. m0+127 and m0+128 .. m0+255)
+// instead of alternate reduction steps of one tile.  They share the B tile (each team stages half of its
+// rows), so per FLOP a quarter less goes through the vector-memory return path and into LDS, which is
+// what bounds the loop; the price is half as many workgroups, so this is for launches with more tiles
+// than compute units (the host decides).  Each team finishes its own tile: no sum in the epilogue.
+template <int KA, int KB, int VA, int VB, typename TOut, bool ATOMIC, bool PAIR, bool DUAL>
 __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    static_assert(!(DUAL && ATOMIC), "a split reduction keeps the two-teams-per-tile form");
+    constexpr int BP = DUAL ? 2 : 1;                   // share of the B tile one team stages
     PH_PHASE(0);
 
     // XCD-aware id: hardware deals workgroup ids round-robin over 8 XCDs
@@ -602,40 +621,44 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
     const bool second = PAIR && wg >= batch.p[0].total_wg;
     if (second) wg -= batch.p[0].total_wg;
     const MfmaParams P = PAIR ? pick_params(second, batch.p[0], batch.p[1]) : batch.p[0];
-    const int tiles = P.tiles_m * P.tiles_n;
+    const int tiles = P.tiles_m * P.tiles_n;           // DUAL: tiles_m counts pairs of tile rows
     const int g = wg / (tiles * P.ksplit);
     int rem = wg - g * tiles * P.ksplit;
     const int ks = rem / tiles;
     rem -= ks * tiles;
     // tiles are walked in bands of RASTER_M tile rows, down the band first: the workgroups that run
     // together on one XCD then cover a near-square patch of C and share both operand panels in L2
-    constexpr int RASTER_M = 8;
+    constexpr int RASTER_M = DUAL ? 4 : 8;
     const int band = rem / (RASTER_M * P.tiles_n);
     const int in_band = rem - band * (RASTER_M * P.tiles_n);
     const int band_rows = min(P.tiles_m - band * RASTER_M, RASTER_M);
     const int tn = in_band / band_rows;
     const int tm = band * RASTER_M + (in_band - tn * band_rows);
-    const int m0 = tm * MT, n0 = tn * MT;
+    const int team = threadIdx.x >> 8;
+    const int team_u = __builtin_amdgcn_readfirstlane(team);
+    const int m0 = DUAL ? (tm * 2 + team_u) * MT : tm * MT, n0 = tn * MT;
     const int k_begin = ks * P.k_per_split;
     const int k_end = min(P.K, k_begin + P.k_per_split);
     PH_PHASE(6);
 
-    const int team = threadIdx.x >> 8;
     const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
     const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
 
     typedef StageCfg<KA, VA> SA;
-    typedef StageCfg<KB, VB> SB;
+    typedef StageCfg<KB, VB, BP> SB;
     int a_off0[SA::NV], a_off1[SA::NV], b_off0[SB::NV], b_off1[SB::NV];
-    const StageState sa = stage_init<KA, VA>(P.a, g, m0, P.M, k_end, tid, a_off0, a_off1);
-    const StageState sb = stage_init<KB, VB>(P.b, g, n0, P.N, k_end, tid, b_off0, b_off1);
+    // a DUAL team whose tile lies below the last row still stages its half of B and keeps the barriers:
+    // its loaders read the last valid row, its epilogue writes nothing
+    const StageState sa = stage_init<KA, VA>(P.a, g, min(m0, (P.M - 1) / MT * MT), P.M, k_end, tid, a_off0, a_off1);
+    const StageState sb = stage_init<KB, VB, BP>(P.b, g, n0, P.N, k_end, tid, b_off0, b_off1,
+                                                 DUAL ? team_u * (SB::ROWS / 2) : 0);
     PH_PHASE(7);
     typename SA::V ra0[SA::NV], ra1[SA::NV];
     typename SB::V rb0[SB::NV], rb1[SB::NV];
 #define PH_FETCH(set, c0) do { stage_fetch<KA, VA, true>(sa, a_off0, a_off1, ra##set, (c0)); \
-                               stage_fetch<KB, VB, true>(sb, b_off0, b_off1, rb##set, (c0)); } while (0)
+                               stage_fetch<KB, VB, true, BP>(sb, b_off0, b_off1, rb##set, (c0)); } while (0)
 #define PH_STORE(set, stage, c0) do { stage_store<KA, VA, true>(sa, ra##set, s##stage##a, (c0)); \
-                                      stage_store<KB, VB, true>(sb, rb##set, s##stage##b, (c0)); } while (0)
+                                      stage_store<KB, VB, true, BP>(sb, rb##set, s##stage##b, (c0)); } while (0)
 
     f32x16 acc[2][2];
 #pragma unroll
@@ -646,14 +669,23 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     PH_PHASE(1);
 
-    __bf16 *smem = (__bf16 *)smem_raw + team * 4 * TILE_ELEMS;
-    __bf16 *s0a = smem, *s0b = smem + TILE_ELEMS, *s1a = smem + 2 * TILE_ELEMS, *s1b = smem + 3 * TILE_ELEMS;
-    // both teams run the same number of steps (one barrier serves all 512 threads); a step past the
-    // end of the reduction range multiplies zeros
+    // LDS: two stages per operand tile.  Two teams on one tile: each team has its own A and B stages
+    // (8 tiles).  DUAL: own A stages, the B stages are common (6 tiles).
+    __bf16 *smem = (__bf16 *)smem_raw;
+    __bf16 *s0a, *s0b, *s1a, *s1b;
+    if (DUAL) {
+        s0a = smem + team * 2 * TILE_ELEMS; s1a = s0a + TILE_ELEMS;
+        s0b = smem + 4 * TILE_ELEMS; s1b = s0b + TILE_ELEMS;
+    } else {
+        s0a = smem + team * 4 * TILE_ELEMS; s0b = s0a + TILE_ELEMS; s1a = s0a + 2 * TILE_ELEMS; s1b = s0a + 3 * TILE_ELEMS;
+    }
+    // Two teams on one tile: team q takes the steps q, q+2, ...; both run the same number of steps (one
+    // barrier serves all 512 threads), a step past the end of the reduction range multiplies zeros.
+    // DUAL: every team takes every step.
     const int all_steps = (k_end - k_begin + KT - 1) / KT;
-    const int steps = (all_steps + 1) >> 1;
-    const int kfirst = k_begin + __builtin_amdgcn_readfirstlane(team) * KT;     // reduction start of this team's step i: kfirst + 2*i*KT
-    constexpr int KS = 2 * KT;
+    const int steps = DUAL ? all_steps : (all_steps + 1) >> 1;
+    const int kfirst = DUAL ? k_begin : k_begin + team_u * KT;     // reduction start of this team's step i: kfirst + i*KS
+    constexpr int KS = DUAL ? KT : 2 * KT;
 
     // prologue: step 0 into LDS stage 0; steps 1 and 2 on their way in register sets 1 and 0
     PH_FETCH(0, kfirst);
@@ -667,10 +699,10 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
     // are moved to the other LDS stage, whose readers finished before the barrier that ended step t-1
     int t = 0;
 #define PH_STEP(careful, set, cur, nxt, c_store, c_fetch) do { \
-        fused_quarter<KA, KB, VA, VB, careful, 0>(acc, s##cur##a, s##cur##b, wm, wn, lane, sa, a_off0, a_off1, ra##set, s##nxt##a, sb, b_off0, b_off1, rb##set, s##nxt##b, (c_store), (c_fetch)); \
-        fused_quarter<KA, KB, VA, VB, careful, 1>(acc, s##cur##a, s##cur##b, wm, wn, lane, sa, a_off0, a_off1, ra##set, s##nxt##a, sb, b_off0, b_off1, rb##set, s##nxt##b, (c_store), (c_fetch)); \
-        fused_quarter<KA, KB, VA, VB, careful, 2>(acc, s##cur##a, s##cur##b, wm, wn, lane, sa, a_off0, a_off1, ra##set, s##nxt##a, sb, b_off0, b_off1, rb##set, s##nxt##b, (c_store), (c_fetch)); \
-        fused_quarter<KA, KB, VA, VB, careful, 3>(acc, s##cur##a, s##cur##b, wm, wn, lane, sa, a_off0, a_off1, ra##set, s##nxt##a, sb, b_off0, b_off1, rb##set, s##nxt##b, (c_store), (c_fetch)); \
+        fused_quarter<KA, KB, VA, VB, careful, 0, BP>(acc, s##cur##a, s##cur##b, wm, wn, lane, sa, a_off0, a_off1, ra##set, s##nxt##a, sb, b_off0, b_off1, rb##set, s##nxt##b, (c_store), (c_fetch)); \
+        fused_quarter<KA, KB, VA, VB, careful, 1, BP>(acc, s##cur##a, s##cur##b, wm, wn, lane, sa, a_off0, a_off1, ra##set, s##nxt##a, sb, b_off0, b_off1, rb##set, s##nxt##b, (c_store), (c_fetch)); \
+        fused_quarter<KA, KB, VA, VB, careful, 2, BP>(acc, s##cur##a, s##cur##b, wm, wn, lane, sa, a_off0, a_off1, ra##set, s##nxt##a, sb, b_off0, b_off1, rb##set, s##nxt##b, (c_store), (c_fetch)); \
+        fused_quarter<KA, KB, VA, VB, careful, 3, BP>(acc, s##cur##a, s##cur##b, wm, wn, lane, sa, a_off0, a_off1, ra##set, s##nxt##a, sb, b_off0, b_off1, rb##set, s##nxt##b, (c_store), (c_fetch)); \
     } while (0)
     // fast path while every tile touched (stored: t+1, t+2; fetched: t+3, t+4) lies fully inside the
     // reduction range; it ends in the state the general loop below expects (next tile complete in
@@ -679,10 +711,10 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
         bf16x8 fr[2][4];
         read_operands<KA, KB>(fr[0], s0a, s0b, wm, wn, 0, lane);
         for (; t + 1 < steps && kfirst + (t + 4) * KS + KT <= k_end; t += 2) {
-            fast_step<KA, KB, VA, VB>(acc, fr, s0a, s0b, wm, wn, lane, sa, a_off0, a_off1, ra1, s1a, sb, b_off0, b_off1, rb1, s1b,
-                                      kfirst + (t + 3) * KS);
-            fast_step<KA, KB, VA, VB>(acc, fr, s1a, s1b, wm, wn, lane, sa, a_off0, a_off1, ra0, s0a, sb, b_off0, b_off1, rb0, s0b,
-                                      kfirst + (t + 4) * KS);
+            fast_step<KA, KB, VA, VB, BP>(acc, fr, s0a, s0b, wm, wn, lane, sa, a_off0, a_off1, ra1, s1a, sb, b_off0, b_off1, rb1, s1b,
+                                          kfirst + (t + 3) * KS);
+            fast_step<KA, KB, VA, VB, BP>(acc, fr, s1a, s1b, wm, wn, lane, sa, a_off0, a_off1, ra0, s0a, sb, b_off0, b_off1, rb0, s0b,
+                                          kfirst + (t + 4) * KS);
         }
     }
     for (; t + 1 < steps; t += 2) {
@@ -698,13 +730,14 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
 #undef PH_FETCH
 #undef PH_STORE
 
-    // the two teams hold partial sums of the same tile: each writes its own fp32 tile over the
-    // staging space (free after the barrier above), the epilogue adds the two while reading
+    // each team writes its fp32 tile over the staging space (free after the barrier above).  Two teams
+    // on one tile hold partial sums of it: the epilogue adds the two while reading.
     float *ctile = (float *)smem_raw;
     acc_to_lds(ctile + team * CT_ELEMS, acc, wm, wn, lane);
     __syncthreads();
     PH_PHASE(4);
-    epilogue_from_lds<VA, TOut, ATOMIC>(P, g, ctile, m0, n0);
+    if (DUAL) epilogue_from_lds<VA, TOut, ATOMIC, true>(P, g, ctile + team * CT_ELEMS, m0, n0, tid);
+    else epilogue_from_lds<VA, TOut, ATOMIC, false>(P, g, ctile, m0, n0, (int)threadIdx.x);
     PH_PHASE(5);
 }
 

@@ -227,10 +227,10 @@ struct Product {
     int64_t M, N, K;
 };
 
-template <int KA, int KB, int VEC, typename TOut, bool ATOMIC, bool PAIR>
-ph_status launch_mfma_pair(const MfmaBatch &batch, hipStream_t st, const char *what)
+template <int KA, int KB, int VEC, typename TOut, bool ATOMIC, bool PAIR, bool DUAL>
+ph_status launch_mfma_kernel(const MfmaBatch &batch, hipStream_t st, const char *what)
 {
-    auto kern = gemm_mfma_kernel<KA, KB, VEC, VEC, TOut, ATOMIC, PAIR>;
+    auto kern = gemm_mfma_kernel<KA, KB, VEC, VEC, TOut, ATOMIC, PAIR, DUAL>;
     static thread_local bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, MFMA_LDS_BYTES);
@@ -243,28 +243,35 @@ ph_status launch_mfma_pair(const MfmaBatch &batch, hipStream_t st, const char *w
 }
 
 template <int KA, int KB, int VEC, typename TOut, bool ATOMIC>
-ph_status launch_mfma_inst(const MfmaBatch &batch, hipStream_t st, const char *what)
+ph_status launch_mfma_inst(const MfmaBatch &batch, bool dual, hipStream_t st, const char *what)
 {
-    if (batch.count == 2) return launch_mfma_pair<KA, KB, VEC, TOut, ATOMIC, true>(batch, st, what);
-    return launch_mfma_pair<KA, KB, VEC, TOut, ATOMIC, false>(batch, st, what);
+    if constexpr (!ATOMIC) {
+        if (dual) {
+            if (batch.count == 2) return launch_mfma_kernel<KA, KB, VEC, TOut, false, true, true>(batch, st, what);
+            return launch_mfma_kernel<KA, KB, VEC, TOut, false, false, true>(batch, st, what);
+        }
+    }
+    if (batch.count == 2) return launch_mfma_kernel<KA, KB, VEC, TOut, ATOMIC, true, false>(batch, st, what);
+    return launch_mfma_kernel<KA, KB, VEC, TOut, ATOMIC, false, false>(batch, st, what);
 }
 
 template <int KA, int KB, typename TOut, bool ATOMIC>
-ph_status launch_mfma_vec(const MfmaBatch &batch, int vec, hipStream_t st, const char *what)
+ph_status launch_mfma_vec(const MfmaBatch &batch, int vec, bool dual, hipStream_t st, const char *what)
 {
     switch (vec) {
-    case 8: return launch_mfma_inst<KA, KB, 8, TOut, ATOMIC>(batch, st, what);
-    case 4: return launch_mfma_inst<KA, KB, 4, TOut, ATOMIC>(batch, st, what);
-    default: return launch_mfma_inst<KA, KB, 2, TOut, ATOMIC>(batch, st, what);
+    case 8: return launch_mfma_inst<KA, KB, 8, TOut, ATOMIC>(batch, dual, st, what);
+    case 4: return launch_mfma_inst<KA, KB, 4, TOut, ATOMIC>(batch, dual, st, what);
+    default: return launch_mfma_inst<KA, KB, 2, TOut, ATOMIC>(batch, dual, st, what);
     }
 }
 
-MfmaParams mfma_params(const Product &pr, int groups, int ksplit)
+MfmaParams mfma_params(const Product &pr, int groups, int ksplit, bool dual)
 {
     MfmaParams P{};
     P.a = pr.a; P.b = pr.b; P.o = pr.o; P.ep = pr.ep;
     P.M = (int)pr.M; P.N = (int)pr.N; P.K = (int)pr.K;
-    P.tiles_m = (int)((pr.M + MT - 1) / MT);
+    const int mt = dual ? 2 * MT : MT;               // rows of C per workgroup
+    P.tiles_m = (int)((pr.M + mt - 1) / mt);
     P.tiles_n = (int)((pr.N + MT - 1) / MT);
     const int ksteps = (int)((pr.K + KT - 1) / KT);
     const int steps_per = (ksteps + ksplit - 1) / ksplit;
@@ -292,12 +299,23 @@ ph_status launch_mfma(const GemmPlan &plan, const Product *prods, int count, int
         if (tiles < 96 && ksteps >= 32)
             ksplit = (int)std::max<int64_t>(1, std::min<int64_t>((256 + tiles - 1) / tiles, ksteps / 8));
     }
+    // More tiles than compute units: the launch would run in rounds.  Then two tiles, one above the other,
+    // go to one workgroup (its teams share the B tile): fewer bytes staged per FLOP and half the rounds.
+    // PHANTOM_DUAL=0 / 1 forces the choice (for measurements).
+    bool dual = false;
+    if (ksplit == 1) {
+        int64_t all_tiles = tiles;
+        if (count == 2) all_tiles += ((prods[1].M + MT - 1) / MT) * ((prods[1].N + MT - 1) / MT) * groups;
+        dual = all_tiles > 256;
+        static const char *force = getenv("PHANTOM_DUAL");
+        if (force) dual = force[0] == '1';
+    }
     MfmaBatch batch{};
     batch.count = count;
-    batch.p[0] = mfma_params(first, groups, ksplit);
+    batch.p[0] = mfma_params(first, groups, ksplit, dual);
     batch.total_wg = batch.p[0].total_wg;
     if (count == 2) {
-        batch.p[1] = mfma_params(prods[1], groups, 1);
+        batch.p[1] = mfma_params(prods[1], groups, 1, dual);
         batch.total_wg += batch.p[1].total_wg;
     }
     const Product &second = prods[count - 1];
@@ -314,15 +332,15 @@ ph_status launch_mfma(const GemmPlan &plan, const Product *prods, int count, int
                 PH_TRY(check_launch("clear split-K output"));
             }
             ProfScope prof(what, first.M, first.N, first.K, groups, st);
-            if (plan.ka == LD_KM && plan.kb == LD_KM) return launch_mfma_vec<LD_KM, LD_KM, float, true>(batch, plan.vec, st, what);
+            if (plan.ka == LD_KM && plan.kb == LD_KM) return launch_mfma_vec<LD_KM, LD_KM, float, true>(batch, plan.vec, false, st, what);
         }
         return fail(PH_ERR_UNSUPPORTED, "%s: split reduction not available for this operand layout", what);
     }
     ProfScope prof(what, first.M, first.N, first.K, groups, st, count == 2 ? second.M : 0, count == 2 ? second.N : 0,
                    count == 2 ? second.K : 0);
-    if (plan.ka == LD_KC && plan.kb == LD_KC) return launch_mfma_vec<LD_KC, LD_KC, TOut, false>(batch, plan.vec, st, what);
-    if (plan.ka == LD_KC && plan.kb == LD_KM) return launch_mfma_vec<LD_KC, LD_KM, TOut, false>(batch, plan.vec, st, what);
-    if (plan.ka == LD_KM && plan.kb == LD_KM) return launch_mfma_vec<LD_KM, LD_KM, TOut, false>(batch, plan.vec, st, what);
+    if (plan.ka == LD_KC && plan.kb == LD_KC) return launch_mfma_vec<LD_KC, LD_KC, TOut, false>(batch, plan.vec, dual, st, what);
+    if (plan.ka == LD_KC && plan.kb == LD_KM) return launch_mfma_vec<LD_KC, LD_KM, TOut, false>(batch, plan.vec, dual, st, what);
+    if (plan.ka == LD_KM && plan.kb == LD_KM) return launch_mfma_vec<LD_KM, LD_KM, TOut, false>(batch, plan.vec, dual, st, what);
     return fail(PH_ERR_UNSUPPORTED, "%s: operand layout pair not built", what);
 }
 

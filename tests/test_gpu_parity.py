@@ -135,6 +135,11 @@ ALL_RANK_CASES = [
     # many ranks on the device (grouped products with 16 / 64 groups, the skipped slot moves with the group)
     (2048, 16, 8, 200, "relu", "bf16"),
     (4096, 64, 4, 96, "gelu", "bf16"),
+    # more tiles than compute units: two tiles per workgroup.  17 tile rows (an odd number, the last one ragged)
+    # x 16 groups in the forward, the error compression and the input gradient ...
+    (2048, 16, 8, 2100, "relu", "bf16"),
+    # ... and 2 x 6 tiles x 32 groups in the weight gradients, with the compressor gradient beside them
+    (8192, 32, 16, 200, "gelu", "bf16"),
 ]
 
 
