@@ -18,6 +18,7 @@
 #include "elementwise.h"
 #include "gemm_generic.h"
 #include "gemm_mfma.h"
+#include "thin_product.h"
 #include "views.h"
 
 using namespace phantom;
@@ -433,12 +434,36 @@ ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
     update.ep.mode = EPI_BIAS_ACT; update.ep.act = g.act; update.ep.bias = f.bias; update.ep.bias_g = s;
     update.ep.aux = f.A_save; update.ep.aux_ld = s; update.ep.aux_g = B * s; update.ep.aux_f32 = f.a_f32;
     update.M = B; update.N = s; update.K = g.Kc;
+    // A compression with few phantom neurons has a kernel of its own (32 rows per workgroup instead of 128)
+    bool thin = false;
+    if constexpr (std::is_same<T, bf16_t>::value) thin = q > 0 && k <= THIN_MAX_N && s % 16 == 0 && g.vec > 0;
+    auto launch_thin = [&]() -> ph_status {
+        if constexpr (std::is_same<T, bf16_t>::value) {
+            ProfScope prof("compression", B, k, s, g.groups, st);
+            dim3 grid((unsigned)((B + THIN_ROWS - 1) / THIN_ROWS), (unsigned)g.groups);
+            if (k <= 32)
+                hipLaunchKernelGGL((thin_product_kernel<1>), grid, dim3(256), 0, st, (const __bf16 *)f.X, (const __bf16 *)f.Cw,
+                                   (__bf16 *)f.g_own, (int)B, (int)k, (int)s, B * s, k * s, B * k);
+            else
+                hipLaunchKernelGGL((thin_product_kernel<2>), grid, dim3(256), 0, st, (const __bf16 *)f.X, (const __bf16 *)f.Cw,
+                                   (__bf16 *)f.g_own, (int)B, (int)k, (int)s, B * s, k * s, B * k);
+            return check_launch("compression");
+        }
+        return PH_OK;
+    };
     if (g.all) {
         // every rank reads the other ranks' g: the compression of all ranks has to finish first
-        PH_TRY((launch_products<T, T>(plan, &compress, 1, g.groups, st, "compression")));
+        if (thin) PH_TRY(launch_thin());
+        else PH_TRY((launch_products<T, T>(plan, &compress, 1, g.groups, st, "compression")));
         return launch_products<T, T>(plan, &update, 1, g.groups, st, "layer update");
     }
-    // one rank: the peers' g are inputs, so the rank's own compression runs beside the update
+    // one rank: the peers' g are inputs, so the rank's own compression runs beside the update when the two
+    // fit the device together
+    const int64_t tiles_both = (((B + MT - 1) / MT) * ((s + MT - 1) / MT) + ((B + MT - 1) / MT) * ((k + MT - 1) / MT)) * g.groups;
+    if (thin && tiles_both > 256) {
+        PH_TRY(launch_thin());
+        return launch_products<T, T>(plan, &update, 1, g.groups, st, "layer update");
+    }
     Product both[2] = {update, compress};
     return launch_products<T, T>(plan, both, 2, g.groups, st, "layer update + compression", "layer update", "compression");
 }

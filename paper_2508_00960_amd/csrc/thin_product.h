@@ -1,0 +1,90 @@
+// The compression g = C y of Eq. (ylq) as a kernel of its own: G[m, n] = sum_c X[m, c] * C[n, c] with a
+// short n range (k <= 64 phantom neurons), bf16 in, fp32 accumulate, bf16 out.
+//
+// As a tile of the general product it has few workgroups (one per 128 rows: 64 for an 8192-row batch)
+// and every one of them walks the whole reduction range, so three quarters of the device wait for
+// 14 us.  Here a workgroup owns 32 rows and all n; its four wavefronts split the reduction range and
+// feed the MFMAs straight from global memory (a lane's operand is 16 contiguous bytes of one row; the
+// four 16-byte pieces of a 128-byte line are used by consecutive steps of the same wavefront, from L1),
+// then add their partial sums through LDS.  C (k x s, at most 128 KB) is read by every workgroup, from L2.
+#pragma once
+#include "common.h"
+
+namespace phantom {
+
+constexpr int THIN_ROWS = 32;       // rows of X per workgroup
+constexpr int THIN_MAX_N = 64;
+
+typedef __bf16 thin_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float thin_f32x16 __attribute__((ext_vector_type(16)));
+
+// NF = number of 32-wide column blocks (1: N <= 32, 2: N <= 64).  K is a multiple of 16.
+// x_g, c_g, o_g: element offsets per group (blockIdx.y).
+template <int NF>
+__global__ __launch_bounds__(256) void thin_product_kernel(const __bf16 *__restrict__ X, const __bf16 *__restrict__ C,
+                                                          __bf16 *__restrict__ G, int M, int N, int K,
+                                                          int64_t x_g, int64_t c_g, int64_t o_g)
+{
+    __shared__ float part[4][NF][16][64];              // [wavefront][column block][accumulator][lane]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int grp = blockIdx.y;
+    const int m0 = blockIdx.x * THIN_ROWS;
+    const __bf16 *x = X + grp * x_g, *c = C + grp * c_g;
+    __bf16 *out = G + grp * o_g;
+
+    // this wavefront's share of the K / 16 reduction chunks
+    const int chunks = K >> 4;
+    const int c_lo = (int)((int64_t)chunks * wave / 4), c_hi = (int)((int64_t)chunks * (wave + 1) / 4);
+    // MFMA operand of a lane: row (lane & 31), 8 consecutive reduction indices starting at 8 * (lane >> 5).
+    // Rows past the end read the last row; what they produce is never stored.
+    const int half = (lane >> 5) * 8;
+    const __bf16 *xrow = x + (int64_t)min(m0 + (lane & 31), M - 1) * K + half;
+    const __bf16 *crow[NF];
+#pragma unroll
+    for (int f = 0; f < NF; ++f) crow[f] = c + (int64_t)min(f * 32 + (lane & 31), N - 1) * K + half;
+
+    thin_f32x16 acc[NF];
+#pragma unroll
+    for (int f = 0; f < NF; ++f)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[f][e] = 0.f;
+    int ch = c_lo;
+    for (; ch + 4 <= c_hi; ch += 4) {                  // four chunks' loads in flight together
+        thin_bf16x8 a[4], b[NF][4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            a[u] = *(const thin_bf16x8 *)(xrow + (ch + u) * 16);
+#pragma unroll
+            for (int f = 0; f < NF; ++f) b[f][u] = *(const thin_bf16x8 *)(crow[f] + (ch + u) * 16);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int f = 0; f < NF; ++f) acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u], b[f][u], acc[f], 0, 0, 0);
+    }
+    for (; ch < c_hi; ++ch) {
+        const thin_bf16x8 a = *(const thin_bf16x8 *)(xrow + ch * 16);
+#pragma unroll
+        for (int f = 0; f < NF; ++f) {
+            const thin_bf16x8 b = *(const thin_bf16x8 *)(crow[f] + ch * 16);
+            acc[f] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[f], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int f = 0; f < NF; ++f)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) part[wave][f][e][lane] = acc[f][e];
+    __syncthreads();
+
+    // accumulator e of lane l in column block f is element (row 8*(e/4) + 4*(l>>5) + e%4, column 32*f + (l&31))
+    for (int o = threadIdx.x; o < THIN_ROWS * NF * 32; o += 256) {
+        const int row = o / (NF * 32), col = o - row * (NF * 32);
+        const int m = m0 + row;
+        if (m >= M || col >= N) continue;
+        const int f = col >> 5, e = (row >> 3) * 4 + (row & 3), l = (col & 31) + 32 * ((row >> 2) & 1);
+        const float sum = (part[0][f][e][l] + part[1][f][e][l]) + (part[2][f][e][l] + part[3][f][e][l]);
+        out[(int64_t)m * N + col] = (__bf16)sum;
+    }
+}
+
+}  // namespace phantom
