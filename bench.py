@@ -4,7 +4,7 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2]
 
 A "step" is one pass of the whole hot path over one batch of synthetic input that already sits in
-HBM: for the default workload (BASELINE configuration 2: n=4096, p=8, shard 512, k=32, batch 1024,
+HBM: for the default workload (benchmark configuration 2: n=4096, p=8, shard 512, k=32, batch 1024,
 4 layers, ReLU, MSE, bf16 storage / fp32 accumulate, all 8 emulated ranks on the GPU) that is the
 forward through every layer, the loss, and the backward through every layer, via phantom_ffn_step.
 Prints ONE JSON line: whole-step throughput (TFLOP/s from the algorithmic FLOP count

@@ -245,7 +245,7 @@ def check_step(prob, data, ref, W, M, Gd, Y_out, loss, lr, grad_tol=None):
 
 
 def test_step_tiny_fp32_all_ranks():
-    """BASELINE configuration 1: n=256, p=4 (shard 64), k=8, batch 32, 2 layers, ReLU, MSE, SGD lr=1e-2."""
+    """benchmark configuration 1: n=256, p=4 (shard 64), k=8, batch 32, 2 layers, ReLU, MSE, SGD lr=1e-2."""
     prob = pin.Problem(n=256, p=4, k=8, batch=32, layers=2, act="relu", dtype="f32", rank=-1)
     data, ref, W, M, Gd, Y_out, loss = run_step(prob, seed=0, lr=1e-2)
     # no pre-activation of this seed sits within fp32 rounding of the ReLU kink (oracle-side check)
