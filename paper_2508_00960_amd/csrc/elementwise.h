@@ -138,12 +138,17 @@ __global__ __launch_bounds__(256) void reduce_scatter_kernel(const T *__restrict
 // sum of (Y - T)^2 per workgroup (added up by the rider of colsum_kernel).  S: pre-activation, or the
 // output for ReLU.  VEC elements per thread and iteration (VEC > 1: count is a multiple of VEC and
 // every pointer is VEC-element aligned).
+// Rider: the kernel also clears `zero_count` floats at `zero` (the step's bias-gradient buffers, which later
+// launches add into), a launch of its own otherwise.
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void mse_delta_kernel(const T *__restrict__ Y, const T *__restrict__ Tg,
                                                        const void *__restrict__ S, int s_f32, T *__restrict__ delta,
                                                        int64_t count, float inv_b, int act,
-                                                       float *__restrict__ partial)
+                                                       float *__restrict__ partial, float *__restrict__ zero,
+                                                       int64_t zero_count)
 {
+    for (int64_t z = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; z < zero_count; z += (int64_t)gridDim.x * blockDim.x)
+        zero[z] = 0.f;
     typedef T TV __attribute__((ext_vector_type(VEC)));
     typedef float FV __attribute__((ext_vector_type(VEC)));
     __shared__ float red[256];

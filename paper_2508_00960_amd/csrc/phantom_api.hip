@@ -666,11 +666,10 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
             hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks_for(bias_count)), dim3(256), 0, st, a.dbias[l], bias_count);
             PH_TRY(check_launch("clear bias gradients"));
         }
-    } else {
-        ProfScope prof("clear bias gradients", 0, bias_count * L, 0, 1, st);
-        hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks_for(bias_count * L)), dim3(256), 0, st, w.dbias, bias_count * L);
-        PH_TRY(check_launch("clear bias gradients"));
     }
+    // (the workspace's own bias-gradient buffers are one block: the output-error kernel clears it on its way)
+    float *clear_at = a.dbias ? nullptr : w.dbias;
+    const int64_t clear_count = a.dbias ? 0 : bias_count * L;
 
     // output error of the MSE loss, already multiplied by sigma_L' (Eq. (deltaL)); the loss's partial sums are
     // added up by the last layer's bias-gradient kernel, the next launch
@@ -683,11 +682,11 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
         if (wide)
             hipLaunchKernelGGL((mse_delta_kernel<T, 8>), dim3(mse_blocks), dim3(256), 0, st, (const T *)w.Y[L - 1],
                                (const T *)a.T, S, (int)(g.act == PH_ACT_GELU), (T *)w.dYa, act_count, 1.0f / (float)B, g.act,
-                               w.mse_partial);
+                               w.mse_partial, clear_at, clear_count);
         else
             hipLaunchKernelGGL((mse_delta_kernel<T, 1>), dim3(mse_blocks), dim3(256), 0, st, (const T *)w.Y[L - 1],
                                (const T *)a.T, S, (int)(g.act == PH_ACT_GELU), (T *)w.dYa, act_count, 1.0f / (float)B, g.act,
-                               w.mse_partial);
+                               w.mse_partial, clear_at, clear_count);
         PH_TRY(check_launch("output error"));
     }
 
