@@ -210,3 +210,17 @@ def all_rank_step_inputs(prob: Problem, seed: int) -> dict:
     layers = [all_rank_params(prob, l, seed) for l in range(prob.layers)]
     X0, T = network_io(prob, seed)
     return {"layers": layers, "X0": shard_columns(X0, prob.p), "T": shard_columns(T, prob.p)}
+
+
+def regression_task(n: int, samples: int, seed: int, dtype: str = "f32") -> tuple:
+    """The data set of the paper's training experiments (Section VI, "Data and Hardware"):
+    pairs (x_i, y_i), y_i = relu(W relu(x_i)), with one Gaussian n x n matrix W kept fixed.
+
+    The paper leaves the distribution of x and the scale of W open.  Here x ~ N(0, 1) and
+    W ~ N(0, 1) / sqrt(n / 2), which keeps the entries of y of order one whatever n is.
+    Returns (X, Y), [samples, n] each, rounded to the storage type.
+    """
+    W = normal((n, n), seed=seed, tensor="W_dense", layer=-2, rank=0, scale=1.0 / math.sqrt(n / 2.0))
+    X = normal((samples, n), seed=seed, tensor="X", layer=-2, rank=0)
+    Y = np.maximum(np.maximum(X, 0.0) @ W.T, 0.0)
+    return round_to_storage(X, dtype), round_to_storage(Y, dtype)
