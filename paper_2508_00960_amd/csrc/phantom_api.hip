@@ -362,17 +362,23 @@ ph_status launch_products(const GemmPlan &plan, const Product *prods_in, int cou
     if (count == 0 || groups <= 0) return PH_OK;
     if constexpr (std::is_same<TIn, bf16_t>::value) {
         if (plan.vec > 0) {
-            // Two products share a launch only when that does not add a round of workgroups: a tile
-            // occupies a whole compute unit, so 256 + 32 tiles take two rounds where 256, then 32, take
-            // one round and a short one.  PHANTOM_PAIR=0 / 1 forces the choice (for measurements).
+            // Two products share a launch when the launch-time model below says the pair is faster.  A
+            // workgroup occupies a whole compute unit, so up to 256 tiles run at once (fixed cost ~8.6 us +
+            // 0.5 us per 64 of the reduction length); above that, workgroups take two tiles each (~9.5 us +
+            // 0.76 us per 64) and run in rounds of 256.  Separate launches pay ~2.5 us for the extra launch.
+            // PHANTOM_PAIR=0 / 1 forces the choice (for measurements).
             bool pair = count == 2;
             if (pair) {
-                const int64_t t0 = ((prods[0].M + MT - 1) / MT) * ((prods[0].N + MT - 1) / MT) * groups;
-                const int64_t t1 = ((prods[1].M + MT - 1) / MT) * ((prods[1].N + MT - 1) / MT) * groups;
-                const int64_t cus = 256;
-                pair = (t0 + t1 + cus - 1) / cus <= (t0 + cus - 1) / cus + (t1 + cus - 1) / cus - 1 || t0 + t1 <= cus;
-                // a small partner with the same reduction length costs its tiles either way; together saves a launch
-                if (prods[0].K == prods[1].K && std::min(t0, t1) * 8 <= std::max(t0, t1)) pair = true;
+                auto tiles_of = [&](const Product &pr) { return ((pr.M + MT - 1) / MT) * ((pr.N + MT - 1) / MT) * groups; };
+                auto launch_us = [](int64_t tiles, int64_t K) {
+                    const double steps = (double)((K + KT - 1) / KT);
+                    if (tiles <= 256) return 8.6 + 0.5 * steps;
+                    return (double)(((tiles + 1) / 2 + 255) / 256) * (9.5 + 0.76 * steps);
+                };
+                const int64_t t0 = tiles_of(prods[0]), t1 = tiles_of(prods[1]);
+                const double together = launch_us(t0 + t1, std::max(prods[0].K, prods[1].K));
+                const double apart = launch_us(t0, prods[0].K) + launch_us(t1, prods[1].K) + 2.5;
+                pair = together < apart;
                 static const char *force = getenv("PHANTOM_PAIR");
                 if (force) pair = force[0] == '1';
             }
