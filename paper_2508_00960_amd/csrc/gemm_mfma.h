@@ -207,6 +207,15 @@ __device__ __forceinline__ void stage_fetch(const StageState &s, const int (&off
     }
 }
 
+// whether stage_init would call the tile whose free index starts at r0 regular (same predicate, no state)
+template <int KIND>
+__device__ __forceinline__ bool tile_is_regular(const View &v, int r0)
+{
+    if (KIND == LD_KC) return !v.c.decides || (v.c.split % KT == 0 && (KT % v.c.seg == 0 || v.c.seg % KT == 0));
+    const bool r_uniform = !v.r.decides || r0 + MT <= v.r.split || r0 >= v.r.split;
+    return r_uniform && (!v.c.decides || v.c.split % KT == 0);
+}
+
 // ---- the fast path: regular shapes, full interior tiles ----------------------------------
 // What a step's loads share: a base pointer that is the same for the whole workgroup (it lives in
 // scalar registers and the load takes it as its scalar base), which of the two offset arrays
@@ -378,7 +387,10 @@ __device__ __forceinline__ void read_operands(bf16x8 (&f)[4], const __bf16 *ta, 
 
 constexpr int part_lo(int n, int q) { return n * q / 3; }       // the q-th third of n vectors
 
-template <int KA, int KB, int VA, int VB, int BP>
+// DRAIN = true: the last steps of a team's run, where a part of the work no longer exists; do_mfma (this
+// step's tile exists), do_store (the next tile exists) and do_fetch (the tile three steps on exists) are
+// the same for the whole team.  DRAIN = false ignores them: everything exists.
+template <int KA, int KB, int VA, int VB, int BP, bool DRAIN>
 __device__ __forceinline__ void fast_step(f32x16 (&acc)[2][2], bf16x8 (&fr)[2][4], const __bf16 *ta, const __bf16 *tb,
                                           int wm, int wn, int lane,
                                           const StageState &sa, const int (&a_off0)[StageCfg<KA, VA>::NV],
@@ -386,15 +398,18 @@ __device__ __forceinline__ void fast_step(f32x16 (&acc)[2][2], bf16x8 (&fr)[2][4
                                           typename VecOf<VA>::type (&ra)[StageCfg<KA, VA>::NV], __bf16 *na,
                                           const StageState &sb, const int (&b_off0)[StageCfg<KB, VB, BP>::NV],
                                           const int (&b_off1)[StageCfg<KB, VB, BP>::NV],
-                                          typename VecOf<VB>::type (&rb)[StageCfg<KB, VB, BP>::NV], __bf16 *nb, int c_fetch)
+                                          typename VecOf<VB>::type (&rb)[StageCfg<KB, VB, BP>::NV], __bf16 *nb, int c_fetch,
+                                          bool do_mfma = true, bool do_store = true, bool do_fetch = true)
 {
     constexpr int NA = StageCfg<KA, VA>::NV, NB = StageCfg<KB, VB, BP>::NV;
-    const FastStep fa = fast_step_addr<KA, VA>(sa, c_fetch), fb = fast_step_addr<KB, VB>(sb, c_fetch);
-#define PH_MFMA(buf, i, j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[buf][2 + j], fr[buf][i], acc[i][j], 0, 0, 0)
-#define PH_STORE_A(q) stage_store<KA, VA, false, 1, part_lo(NA, q), part_lo(NA, q + 1)>(sa, ra, na, 0)
-#define PH_STORE_B(q) stage_store<KB, VB, false, BP, part_lo(NB, q), part_lo(NB, q + 1)>(sb, rb, nb, 0)
-#define PH_FETCH_A(q) fast_fetch<KA, VA, 1, part_lo(NA, q), part_lo(NA, q + 1)>(fa, a_off0, a_off1, ra)
-#define PH_FETCH_B(q) fast_fetch<KB, VB, BP, part_lo(NB, q), part_lo(NB, q + 1)>(fb, b_off0, b_off1, rb)
+    // a tile that does not exist has no valid address: its step start is replaced by one that does
+    const int c_safe = (DRAIN && !do_fetch) ? sa.c_lim - KT : c_fetch;
+    const FastStep fa = fast_step_addr<KA, VA>(sa, c_safe), fb = fast_step_addr<KB, VB>(sb, c_safe);
+#define PH_MFMA(buf, i, j) do { if (!DRAIN || do_mfma) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fr[buf][2 + j], fr[buf][i], acc[i][j], 0, 0, 0); } while (0)
+#define PH_STORE_A(q) do { if (!DRAIN || do_store) stage_store<KA, VA, false, 1, part_lo(NA, q), part_lo(NA, q + 1)>(sa, ra, na, 0); } while (0)
+#define PH_STORE_B(q) do { if (!DRAIN || do_store) stage_store<KB, VB, false, BP, part_lo(NB, q), part_lo(NB, q + 1)>(sb, rb, nb, 0); } while (0)
+#define PH_FETCH_A(q) do { if (!DRAIN || do_fetch) fast_fetch<KA, VA, 1, part_lo(NA, q), part_lo(NA, q + 1)>(fa, a_off0, a_off1, ra); } while (0)
+#define PH_FETCH_B(q) do { if (!DRAIN || do_fetch) fast_fetch<KB, VB, BP, part_lo(NB, q), part_lo(NB, q + 1)>(fb, b_off0, b_off1, rb); } while (0)
 #define PH_PIN __builtin_amdgcn_sched_barrier(0)   /* the compiler's scheduler would regroup the sequence */
     // quarter 0
     PH_PIN; read_operands<KA, KB>(fr[1], ta, tb, wm, wn, 1, lane); PH_PIN;
@@ -679,52 +694,71 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
     } else {
         s0a = smem + team * 4 * TILE_ELEMS; s0b = s0a + TILE_ELEMS; s1a = s0a + 2 * TILE_ELEMS; s1b = s0a + 3 * TILE_ELEMS;
     }
-    // Two teams on one tile: team q takes the steps q, q+2, ...; both run the same number of steps (one
-    // barrier serves all 512 threads), a step past the end of the reduction range multiplies zeros.
-    // DUAL: every team takes every step.
+    // The reduction range is cut into tiles of KT.  Two teams on one tile: team q takes the tiles q, q+2, ...;
+    // DUAL: every team takes every tile.  Both teams pass the same number of barriers (`steps`).
     const int all_steps = (k_end - k_begin + KT - 1) / KT;
     const int steps = DUAL ? all_steps : (all_steps + 1) >> 1;
-    const int kfirst = DUAL ? k_begin : k_begin + team_u * KT;     // reduction start of this team's step i: kfirst + i*KS
+    const int my_steps = DUAL ? all_steps : (all_steps - team_u + 1) >> 1;      // tiles this team really has
     constexpr int KS = DUAL ? KT : 2 * KT;
-
-    // prologue: step 0 into LDS stage 0; steps 1 and 2 on their way in register sets 1 and 0
-    PH_FETCH(0, kfirst);
-    PH_FETCH(1, kfirst + KS);
-    PH_STORE(0, 0, kfirst);
-    PH_FETCH(0, kfirst + 2 * KS);
-    __syncthreads();
-    PH_PHASE(2);
-
-    // step t multiplies LDS stage t%2; on entry the operands of step t+1 sit in register set (t+1)%2 and
-    // are moved to the other LDS stage, whose readers finished before the barrier that ended step t-1
+    const int kfirst = DUAL ? k_begin : k_begin + team_u * KT;     // start of this team's first tile
+    // Regular shapes walk their tiles from the LAST one down: the only tile that can be ragged (the end of the
+    // reduction range) then comes first and is staged by the careful prologue; every later tile is a full
+    // one and every step takes the fast path.  Other shapes walk upwards through the general loop.
+    const bool regular = sa.regular && sb.regular &&
+                         (!DUAL || tile_is_regular<KA>(P.a, min((tm * 2 + (1 - team_u)) * MT, (P.M - 1) / MT * MT)));
     int t = 0;
-#define PH_STEP(careful, set, cur, nxt, c_store, c_fetch) do { \
-        fused_quarter<KA, KB, VA, VB, careful, 0, BP>(acc, s##cur##a, s##cur##b, wm, wn, lane, sa, a_off0, a_off1, ra##set, s##nxt##a, sb, b_off0, b_off1, rb##set, s##nxt##b, (c_store), (c_fetch)); \
-        fused_quarter<KA, KB, VA, VB, careful, 1, BP>(acc, s##cur##a, s##cur##b, wm, wn, lane, sa, a_off0, a_off1, ra##set, s##nxt##a, sb, b_off0, b_off1, rb##set, s##nxt##b, (c_store), (c_fetch)); \
-        fused_quarter<KA, KB, VA, VB, careful, 2, BP>(acc, s##cur##a, s##cur##b, wm, wn, lane, sa, a_off0, a_off1, ra##set, s##nxt##a, sb, b_off0, b_off1, rb##set, s##nxt##b, (c_store), (c_fetch)); \
-        fused_quarter<KA, KB, VA, VB, careful, 3, BP>(acc, s##cur##a, s##cur##b, wm, wn, lane, sa, a_off0, a_off1, ra##set, s##nxt##a, sb, b_off0, b_off1, rb##set, s##nxt##b, (c_store), (c_fetch)); \
-    } while (0)
-    // fast path while every tile touched (stored: t+1, t+2; fetched: t+3, t+4) lies fully inside the
-    // reduction range; it ends in the state the general loop below expects (next tile complete in
-    // the other LDS stage and a barrier passed, the two tiles after it on their way in registers)
-    if (sa.regular && sb.regular && t + 1 < steps && kfirst + 4 * KS + KT <= k_end) {      // uniform
+    if (regular) {                                                  // uniform (in DUAL for both teams alike)
+        const int c_last = kfirst + (my_steps - 1) * KS;            // start of the tile processed first
+        auto c_of = [c_last](int i) { return c_last - i * KS; };    // tile processed in step i (i < my_steps)
+        if (my_steps > 0) PH_FETCH(0, c_of(0));
+        if (my_steps > 1) PH_FETCH(1, c_of(1));
+        if (my_steps > 0) PH_STORE(0, 0, c_of(0));
+        if (my_steps > 2) PH_FETCH(0, c_of(2));
+        __syncthreads();
+        PH_PHASE(2);
+        // step i multiplies LDS stage i%2; on entry tile i+1 sits in register set (i+1)%2 and is moved to the other
+        // stage (whose readers finished before the barrier inside step i-1), tile i+2 in the other set
         bf16x8 fr[2][4];
         read_operands<KA, KB>(fr[0], s0a, s0b, wm, wn, 0, lane);
-        for (; t + 1 < steps && kfirst + (t + 4) * KS + KT <= k_end; t += 2) {
-            fast_step<KA, KB, VA, VB, BP>(acc, fr, s0a, s0b, wm, wn, lane, sa, a_off0, a_off1, ra1, s1a, sb, b_off0, b_off1, rb1, s1b,
-                                          kfirst + (t + 3) * KS);
-            fast_step<KA, KB, VA, VB, BP>(acc, fr, s1a, s1b, wm, wn, lane, sa, a_off0, a_off1, ra0, s0a, sb, b_off0, b_off1, rb0, s0b,
-                                          kfirst + (t + 4) * KS);
+        for (; t + 1 < steps && t + 4 < my_steps; t += 2) {          // everything these two steps touch exists
+            fast_step<KA, KB, VA, VB, BP, false>(acc, fr, s0a, s0b, wm, wn, lane, sa, a_off0, a_off1, ra1, s1a, sb, b_off0, b_off1,
+                                                 rb1, s1b, c_of(t + 3));
+            fast_step<KA, KB, VA, VB, BP, false>(acc, fr, s1a, s1b, wm, wn, lane, sa, a_off0, a_off1, ra0, s0a, sb, b_off0, b_off1,
+                                                 rb0, s0b, c_of(t + 4));
         }
-    }
-    for (; t + 1 < steps; t += 2) {
-        PH_STEP(true, 1, 0, 1, kfirst + (t + 1) * KS, kfirst + (t + 3) * KS);
+        for (; t + 1 < steps; t += 2) {                              // the last steps: the pipeline runs empty
+            fast_step<KA, KB, VA, VB, BP, true>(acc, fr, s0a, s0b, wm, wn, lane, sa, a_off0, a_off1, ra1, s1a, sb, b_off0, b_off1,
+                                                rb1, s1b, c_of(t + 3), t < my_steps, t + 1 < my_steps, t + 3 < my_steps);
+            fast_step<KA, KB, VA, VB, BP, true>(acc, fr, s1a, s1b, wm, wn, lane, sa, a_off0, a_off1, ra0, s0a, sb, b_off0, b_off1,
+                                                rb0, s0b, c_of(t + 4), t + 1 < my_steps, t + 2 < my_steps, t + 4 < my_steps);
+        }
+        if (t < steps)
+            fast_step<KA, KB, VA, VB, BP, true>(acc, fr, s0a, s0b, wm, wn, lane, sa, a_off0, a_off1, ra1, s1a, sb, b_off0, b_off1,
+                                                rb1, s1b, 0, t < my_steps, false, false);
+    } else {
+        // prologue: tile 0 into LDS stage 0; tiles 1 and 2 on their way in register sets 1 and 0.  A tile past the
+        // end of the range (the shorter team's last step) is stored as zeros.
+        PH_FETCH(0, kfirst);
+        PH_FETCH(1, kfirst + KS);
+        PH_STORE(0, 0, kfirst);
+        PH_FETCH(0, kfirst + 2 * KS);
         __syncthreads();
-        PH_STEP(true, 0, 1, 0, kfirst + (t + 2) * KS, kfirst + (t + 4) * KS);
-        __syncthreads();
-    }
+        PH_PHASE(2);
+#define PH_STEP(set, cur, nxt, c_store, c_fetch) do { \
+        fused_quarter<KA, KB, VA, VB, true, 0, BP>(acc, s##cur##a, s##cur##b, wm, wn, lane, sa, a_off0, a_off1, ra##set, s##nxt##a, sb, b_off0, b_off1, rb##set, s##nxt##b, (c_store), (c_fetch)); \
+        fused_quarter<KA, KB, VA, VB, true, 1, BP>(acc, s##cur##a, s##cur##b, wm, wn, lane, sa, a_off0, a_off1, ra##set, s##nxt##a, sb, b_off0, b_off1, rb##set, s##nxt##b, (c_store), (c_fetch)); \
+        fused_quarter<KA, KB, VA, VB, true, 2, BP>(acc, s##cur##a, s##cur##b, wm, wn, lane, sa, a_off0, a_off1, ra##set, s##nxt##a, sb, b_off0, b_off1, rb##set, s##nxt##b, (c_store), (c_fetch)); \
+        fused_quarter<KA, KB, VA, VB, true, 3, BP>(acc, s##cur##a, s##cur##b, wm, wn, lane, sa, a_off0, a_off1, ra##set, s##nxt##a, sb, b_off0, b_off1, rb##set, s##nxt##b, (c_store), (c_fetch)); \
+    } while (0)
+        for (; t + 1 < steps; t += 2) {
+            PH_STEP(1, 0, 1, kfirst + (t + 1) * KS, kfirst + (t + 3) * KS);
+            __syncthreads();
+            PH_STEP(0, 1, 0, kfirst + (t + 2) * KS, kfirst + (t + 4) * KS);
+            __syncthreads();
+        }
 #undef PH_STEP
-    if (t < steps) mfma_tile<KA, KB>(acc, s0a, s0b, wm, wn, lane);
+        if (t < steps) mfma_tile<KA, KB>(acc, s0a, s0b, wm, wn, lane);
+    }
     __syncthreads();
     PH_PHASE(3);
 #undef PH_FETCH
