@@ -21,6 +21,8 @@ struct Epilogue {
     int64_t aux_ld;      //   plain row-major [M x N]
     int64_t aux_g;
     int32_t aux_f32;     // aux holds float instead of the storage type
+    int32_t aux_deriv;   // aux holds sigma'(pre-activation) in fp16 instead of the pre-activation:
+                         //   EPI_BIAS_ACT writes it, EPI_DACT multiplies by it as it stands (aux_f32 = 0)
     float *colsum;       // MFMA kernel only, optional: the column sums of the stored output (as rounded to
     int64_t colsum_g;    //   the output type) are ADDED to colsum[N] per group; the caller zeroes it first
 };
@@ -103,16 +105,22 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(View va, View vb, Vie
             int reg; int64_t off = join(lm, ln, reg);
             float v = acc[i][j];
             if (ep.mode == EPI_BIAS_ACT) {
-                v += to_f32(((const TIn *)ep.bias + g * ep.bias_g)[n]);
+                v += to_f32(((const TIn *)ep.bias)[g * ep.bias_g + n]);
                 if (ep.aux) {
                     const int64_t at = g * ep.aux_g + (int64_t)m * ep.aux_ld + n;
-                    if (ep.aux_f32) ((float *)ep.aux)[at] = v; else ((TIn *)ep.aux)[at] = from_f32<TIn>(v);
+                    if (ep.aux_deriv) ((_Float16 *)ep.aux)[at] = (_Float16)act_deriv(ep.act, v);
+                    else if (ep.aux_f32) ((float *)ep.aux)[at] = v;
+                    else ((TIn *)ep.aux)[at] = from_f32<TIn>(v);
                 }
                 v = act_apply(ep.act, v);
             } else if (ep.mode == EPI_DACT) {
                 const int64_t at = g * ep.aux_g + (int64_t)m * ep.aux_ld + n;
-                float a = ep.aux_f32 ? ((const float *)ep.aux)[at] : to_f32(((const TIn *)ep.aux)[at]);
-                v *= act_deriv(ep.act, a);
+                if (ep.aux_deriv) {
+                    v *= (float)((const _Float16 *)ep.aux)[at];
+                } else {
+                    const float a = ep.aux_f32 ? ((const float *)ep.aux)[at] : to_f32(((const TIn *)ep.aux)[at]);
+                    v *= act_deriv(ep.act, a);
+                }
             }
             (reg ? o1 : o0)[off] = from_f32<TOut>(v);
         }

@@ -188,7 +188,8 @@ StepWs carve_step(Arena &a, const Geo &g)
     const size_t gath_bytes = (size_t)g.groups * g.B * g.k * g.esz;   // all-ranks: [p,B,k]; one-rank: [B,k]
     for (int l = 0; l < g.layers; ++l) {
         w.Y.push_back(a.take(act_bytes));
-        w.A.push_back(g.act == PH_ACT_GELU ? a.take((size_t)g.groups * g.B * g.s * sizeof(float)) : nullptr);
+        // GELU keeps per layer: fp32 storage, the pre-activation; bf16 storage, sigma'(pre-activation) in fp16
+        w.A.push_back(g.act == PH_ACT_GELU ? a.take(g.esz == 2 ? act_bytes : (size_t)g.groups * g.B * g.s * sizeof(float)) : nullptr);
         w.G.push_back(g.q > 0 ? a.take(gath_bytes) : nullptr);
     }
     w.dYa = a.take(act_bytes);
@@ -419,6 +420,7 @@ struct FwdArgs {
     const void *X, *Lw, *Cw, *Dw, *bias, *G;
     void *Y, *g_own, *A_save;
     bool a_f32;   // step only: A_save is float
+    bool a_deriv; // step only: A_save receives sigma'(A) in fp16 instead of A
 };
 
 template <typename T>
@@ -438,7 +440,7 @@ ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
     update.b = q > 0 ? view_rowseg(f.Lw, s, (int)s, s * s, f.Dw, (int)k, s * k, q * s * k) : view_plain(f.Lw, s, s * s);
     update.o = view_plain(f.Y, s, B * s);
     update.ep.mode = EPI_BIAS_ACT; update.ep.act = g.act; update.ep.bias = f.bias; update.ep.bias_g = s;
-    update.ep.aux = f.A_save; update.ep.aux_ld = s; update.ep.aux_g = B * s; update.ep.aux_f32 = f.a_f32;
+    update.ep.aux = f.A_save; update.ep.aux_ld = s; update.ep.aux_g = B * s; update.ep.aux_f32 = f.a_f32; update.ep.aux_deriv = f.a_deriv;
     update.M = B; update.N = s; update.K = g.Kc;
     // A compression with few phantom neurons has a kernel of its own (32 rows per workgroup instead of 128)
     bool thin = false;
@@ -483,6 +485,7 @@ struct BwdArgs {
     void *dG_send;
     const void *delta_ready;   // step only: delta already formed (dY, S unused)
     bool dx_S_f32;             // step only: dx_S holds float
+    bool dx_S_deriv;           // step only: dx_S holds sigma' itself, in fp16
     const void *dx_S;          // step only: multiply dX by sigma'(dx_S) on the way out, which makes it the
                                //   previous layer's delta with a single rounding (Eq. (backprop))
     float *dx_colsum;          // step only: zeroed [groups, s]; the input-gradient product adds the column sums
@@ -554,7 +557,7 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
     dx.ep = epi_store();
     if (b.dx_S && g.act != PH_ACT_IDENTITY) {
         dx.ep.mode = EPI_DACT; dx.ep.act = g.act; dx.ep.aux = const_cast<void *>(b.dx_S); dx.ep.aux_ld = s;
-        dx.ep.aux_g = B * s; dx.ep.aux_f32 = b.dx_S_f32;
+        dx.ep.aux_g = B * s; dx.ep.aux_f32 = b.dx_S_f32; dx.ep.aux_deriv = b.dx_S_deriv;
     }
     dx.ep.colsum = b.dx_colsum; dx.ep.colsum_g = s;
     dx.M = b.dX ? B : 0; dx.N = s; dx.K = s + k;
@@ -644,13 +647,21 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
     const int64_t B = g.B, s = g.s, k = g.k, q = g.q;
     const int64_t act_count = (int64_t)g.groups * B * s;
 
+    // What the backward pass needs of a layer's pre-activation A is sigma'(A) alone.  ReLU reads it off the
+    // layer's output.  GELU in bf16 storage has the forward epilogue, which evaluates erf and exp for
+    // sigma(A) anyway, store sigma'(A) in fp16 (values in [-0.13, 1.13]; 11 significant bits, four times finer
+    // than the bf16 that delta is rounded to): half the bytes of an fp32 A both ways and no second
+    // evaluation in the input-gradient epilogue.  fp32 storage keeps A itself.
+    const bool gelu = g.act == PH_ACT_GELU;
+    const bool save_deriv = gelu && std::is_same<T, bf16_t>::value;
+
     // forward through every layer; y_l stays in the storage type between layers
     const void *in = a.X0;
     std::vector<const void *> inputs(L);
     for (int l = 0; l < L; ++l) {
         inputs[l] = in;
         FwdArgs f{in, a.Lw[l], q ? a.Cw[l] : nullptr, q ? a.Dw[l] : nullptr, a.bias[l],
-                  (q && !g.all) ? a.G[l] : nullptr, w.Y[l], w.G[l], w.A[l], true};
+                  (q && !g.all) ? a.G[l] : nullptr, w.Y[l], w.G[l], w.A[l], !save_deriv, save_deriv};
         PH_TRY(fwd_impl<T>(g, f, st));
         in = w.Y[l];
     }
@@ -681,17 +692,18 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
     // added up by the last layer's bias-gradient kernel, the next launch
     unsigned mse_blocks = 0;
     {
-        const void *S = g.act == PH_ACT_GELU ? w.A[L - 1] : w.Y[L - 1];
+        const void *S = gelu ? w.A[L - 1] : w.Y[L - 1];
+        const int s_kind = save_deriv ? 2 : (gelu ? 1 : 0);
         const bool wide = act_count % 8 == 0 && (((uintptr_t)a.T | (uintptr_t)w.Y[L - 1] | (uintptr_t)S | (uintptr_t)w.dYa) & 31) == 0;
         mse_blocks = blocks_for(wide ? act_count / 8 : act_count, 256, MSE_BLOCKS);
         ProfScope prof("output error", 0, act_count, 0, 1, st);
         if (wide)
             hipLaunchKernelGGL((mse_delta_kernel<T, 8>), dim3(mse_blocks), dim3(256), 0, st, (const T *)w.Y[L - 1],
-                               (const T *)a.T, S, (int)(g.act == PH_ACT_GELU), (T *)w.dYa, act_count, 1.0f / (float)B, g.act,
+                               (const T *)a.T, S, s_kind, (T *)w.dYa, act_count, 1.0f / (float)B, g.act,
                                w.mse_partial, clear_at, clear_count);
         else
             hipLaunchKernelGGL((mse_delta_kernel<T, 1>), dim3(mse_blocks), dim3(256), 0, st, (const T *)w.Y[L - 1],
-                               (const T *)a.T, S, (int)(g.act == PH_ACT_GELU), (T *)w.dYa, act_count, 1.0f / (float)B, g.act,
+                               (const T *)a.T, S, s_kind, (T *)w.dYa, act_count, 1.0f / (float)B, g.act,
                                w.mse_partial, clear_at, clear_count);
         PH_TRY(check_launch("output error"));
     }
@@ -705,7 +717,8 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
         b.dx_colsum = (fused_dbias && l > 0) ? dbias_of(l - 1) : nullptr;
         b.delta_ready = dY; b.X = inputs[l];
         b.dx_S = l > 0 ? (g.act == PH_ACT_GELU ? w.A[l - 1] : w.Y[l - 1]) : nullptr;
-        b.dx_S_f32 = g.act == PH_ACT_GELU;
+        b.dx_S_f32 = gelu && !save_deriv;
+        b.dx_S_deriv = save_deriv;
         b.Lw = a.Lw[l]; b.Cw = q ? a.Cw[l] : nullptr; b.Dw = q ? a.Dw[l] : nullptr;
         b.G = q ? (g.all ? w.G[l] : a.G[l]) : nullptr;
         b.dg_own = q ? (g.all ? w.dg_own : const_cast<void *>(a.dg_own[l])) : nullptr;
@@ -846,7 +859,7 @@ ph_status phantom_layer_bwd(const ph_problem *prob, const void *dY, const void *
 {
     Geo g;
     PH_TRY(make_geo(prob, g));
-    BwdArgs b{dY, X, A_or_Y, Lw, Cw, Dw, G, dg_own, dX, dLw, dCw, dDw, dbias, dG_send, nullptr, false, nullptr};
+    BwdArgs b{dY, X, A_or_Y, Lw, Cw, Dw, G, dg_own, dX, dLw, dCw, dDw, dbias, dG_send, nullptr, false, false, nullptr};
     PH_TRY(check_bwd_args(g, b));
     Arena sizing{nullptr, 0};
     carve_bwd(sizing, g);
