@@ -203,6 +203,7 @@ __global__ __launch_bounds__(256) void mse_delta_kernel(const T *__restrict__ Y,
 
 // SGD on the (up to four) parameter tensors of one layer in one launch; blockIdx.y picks the tensor.
 // fp32 storage: w -= lr * g.  bf16 storage: master -= lr * g, w = bf16(master).
+// Four elements per thread and iteration where the count allows (every pointer is 16-byte aligned).
 struct SgdTensor {
     void *w;             // storage-type weights
     float *master;       // bf16 storage: fp32 master copy
@@ -222,17 +223,36 @@ __global__ __launch_bounds__(256) void sgd_kernel(SgdBatch batch, float lr)
     if (blockIdx.y == 1) t = batch.t[1];
     if (blockIdx.y == 2) t = batch.t[2];
     if (blockIdx.y == 3) t = batch.t[3];
+    typedef float F4 __attribute__((ext_vector_type(4)));
+    typedef T T4 __attribute__((ext_vector_type(4)));
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    if constexpr (sizeof(T) == 4) {
-        float *w = (float *)t.w;
-        for (; i < t.count; i += stride) w[i] = w[i] - lr * t.grad[i];
-    } else {
-        T *w = (T *)t.w;
-        for (; i < t.count; i += stride) {
-            const float m = t.master[i] - lr * t.grad[i];
+    if ((t.count & 3) == 0) {                          // uniform
+        for (const int64_t quads = t.count >> 2; i < quads; i += stride) {
+            const F4 gr = ((const F4 *)t.grad)[i];
+            if constexpr (sizeof(T) == 4) {
+                F4 *w = (F4 *)t.w;
+                w[i] = w[i] - lr * gr;
+            } else {
+                const F4 m = ((const F4 *)t.master)[i] - lr * gr;
+                ((F4 *)t.master)[i] = m;
+                T4 o;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) o[u] = from_f32<T>(m[u]);
+                ((T4 *)t.w)[i] = o;
+            }
+        }
+        return;
+    }
+    for (; i < t.count; i += stride) {
+        const float gr = t.grad[i];
+        if constexpr (sizeof(T) == 4) {
+            float *w = (float *)t.w;
+            w[i] = w[i] - lr * gr;
+        } else {
+            const float m = t.master[i] - lr * gr;
             t.master[i] = m;
-            w[i] = from_f32<T>(m);
+            ((T *)t.w)[i] = from_f32<T>(m);
         }
     }
 }

@@ -516,7 +516,7 @@ __device__ __forceinline__ void epilogue_prefetch(const MfmaParams &P, int g, in
 
 // rows [m0, m0+128) x columns [n0, n0+128) of the output = sum of the two teams' fp32 tiles in LDS, walked by
 // all 512 threads; SOLO: the tile at ctile alone, walked by the 256 threads of one team (thread = 0..255)
-template <int VEC, typename TOut, bool ATOMIC, bool SOLO>
+template <int VEC, typename TOut, bool SOLO>
 __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, const float *ctile, int m0, int n0, int thread,
                                                   const AuxAhead<VEC, SOLO> &ah)
 {
@@ -652,34 +652,69 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
         const Loc ln = locate(P.o.c, n, skip_o);
         const int region = ln.region > 0 ? 1 : 0;
         TOut *dst = (region ? o1 + ln.off1 : o0 + ln.off0) + (int64_t)m * (region ? P.o.r.mult1 : P.o.r.mult0);
-        if constexpr (ATOMIC) {
+        OutV o;
 #pragma unroll
-            for (int u = 0; u < VEC; ++u) unsafeAtomicAdd((float *)dst + u, x[u]);
-        } else {
-            OutV o;
+        for (int u = 0; u < VEC; ++u) o[u] = from_f32<TOut>(x[u]);
+        *(OutV *)dst = o;
 #pragma unroll
-            for (int u = 0; u < VEC; ++u) o[u] = from_f32<TOut>(x[u]);
-            *(OutV *)dst = o;
+        for (int u = 0; u < VEC; ++u) csum[u] += (float)o[u];
+    }
+    if (ep.colsum) {                                   // uniform
+        // threads tid, tid + PER_ROW, ... hold partial sums of the same VEC columns: add them up through
+        // LDS (over the fp32 tiles, once every thread has read its share), one atomic per column
+        constexpr int SHARERS = THREADS / PER_ROW;
+        float *red = const_cast<float *>(ctile);       // SOLO: each team reduces over its own tile
+        __syncthreads();
 #pragma unroll
-            for (int u = 0; u < VEC; ++u) csum[u] += (float)o[u];
+        for (int u = 0; u < VEC; ++u) red[(thread / PER_ROW) * MT + (thread % PER_ROW) * VEC + u] = csum[u];
+        __syncthreads();
+        if (thread < MT && n0 + thread < P.N) {
+            float t = 0.f;
+#pragma unroll 8
+            for (int r = 0; r < SHARERS; ++r) t += red[r * MT + thread];
+            unsafeAtomicAdd(ep.colsum + g * ep.colsum_g + n0 + thread, t);
         }
     }
-    if constexpr (!ATOMIC) {
-        if (ep.colsum) {                               // uniform
-            // threads tid, tid + PER_ROW, ... hold partial sums of the same VEC columns: add them up through
-            // LDS (over the fp32 tiles, once every thread has read its share), one atomic per column
-            constexpr int SHARERS = THREADS / PER_ROW;
-            float *red = const_cast<float *>(ctile);       // SOLO: each team reduces over its own tile
-            __syncthreads();
+}
+
+// Split reductions: the sum of the two teams' fp32 tiles is ADDED to a float output, element by element
+// (plain store semantics only: no bias, activation or column sums).  Device-wide float atomics that
+// fall into one 64-byte line are served together, so the 16 lanes that share a tile row take 16
+// consecutive columns per instruction (thread: row t / 16 of each group of 32 rows, columns
+// t % 16 + 16 u), four full lines per wavefront instruction; eight consecutive columns per lane touch 32
+// half-used lines per instruction (measured on a 1024 x 1984 x 4096 product cut into 390 partial tiles:
+// 186 us against 47 us for the whole launch).  What remains is about one add per clock and memory
+// channel, 15-20 us for those 6.4 M adds, which is why a split reduction is a last resort.
+__device__ __forceinline__ void epilogue_atomic_from_lds(const MfmaParams &P, int g, const float *ctile, int m0, int n0, int thread)
+{
+    constexpr int LANES = 16;                          // lanes per tile row
+    constexpr int COLS = MT / LANES;                   // columns per thread
+    constexpr int ROWS_PER_PASS = MFMA_THREADS / LANES;
+    float *o0 = (float *)P.o.p0 + g * P.o.g0, *o1 = (float *)P.o.p1 + g * P.o.g1;
+    const int skip_o = P.o.skip0 + g * P.o.skip_g;
+    const int cl = thread % LANES, r0 = thread / LANES;
+    // a thread keeps its columns from pass to pass: their places in the output, once
+    int64_t col_off[COLS];
+    bool col_tail[COLS];
 #pragma unroll
-            for (int u = 0; u < VEC; ++u) red[(thread / PER_ROW) * MT + (thread % PER_ROW) * VEC + u] = csum[u];
-            __syncthreads();
-            if (thread < MT && n0 + thread < P.N) {
-                float t = 0.f;
-#pragma unroll 8
-                for (int r = 0; r < SHARERS; ++r) t += red[r * MT + thread];
-                unsafeAtomicAdd(ep.colsum + g * ep.colsum_g + n0 + thread, t);
-            }
+    for (int u = 0; u < COLS; ++u) {
+        const int n = min(n0 + cl + LANES * u, P.N - 1);
+        const Loc ln = locate(P.o.c, n, skip_o);
+        col_tail[u] = ln.region > 0;
+        col_off[u] = col_tail[u] ? ln.off1 : ln.off0;
+    }
+#pragma unroll 2
+    for (int i = 0; i < MT / ROWS_PER_PASS; ++i) {
+        const int row = r0 + i * ROWS_PER_PASS;
+        const int m = m0 + row;
+        if (m >= P.M) continue;
+#pragma unroll
+        for (int u = 0; u < COLS; ++u) {
+            const int col = cl + LANES * u;
+            if (n0 + col >= P.N) continue;
+            const float x = ctile[row * CT_PITCH + col] + ctile[CT_ELEMS + row * CT_PITCH + col];
+            float *dst = (col_tail[u] ? o1 + (int64_t)m * P.o.r.mult1 : o0 + (int64_t)m * P.o.r.mult0) + col_off[u];
+            unsafeAtomicAdd(dst, x);
         }
     }
 }
@@ -878,8 +913,9 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
     acc_to_lds(ctile + team * CT_ELEMS, acc, wm, wn, lane);
     __syncthreads();
     PH_PHASE(4);
-    if constexpr (DUAL) epilogue_from_lds<VA, TOut, ATOMIC, true>(P, g, ctile + team * CT_ELEMS, m0, n0, tid, ahead);
-    else epilogue_from_lds<VA, TOut, ATOMIC, false>(P, g, ctile, m0, n0, (int)threadIdx.x, ahead);
+    if constexpr (ATOMIC) epilogue_atomic_from_lds(P, g, ctile, m0, n0, (int)threadIdx.x);
+    else if constexpr (DUAL) epilogue_from_lds<VA, TOut, true>(P, g, ctile + team * CT_ELEMS, m0, n0, tid, ahead);
+    else epilogue_from_lds<VA, TOut, false>(P, g, ctile, m0, n0, (int)threadIdx.x, ahead);
     PH_PHASE(5);
 }
 

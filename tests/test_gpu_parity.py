@@ -42,6 +42,8 @@ ONE_RANK_CASES = [
     (1032, 4, 6, 260, "gelu", "bf16", 2),         # shard 258, k = 6: 4-byte vectors
     (2048, 8, 32, 1100, "relu", "bf16", 0),       # several tiles in every dimension, split reduction
     (1536, 4, 16, 520, "identity", "bf16", 3),    # shard 384 = 3 tiles
+    (2048, 8, 32, 4100, "gelu", "bf16", 0),       # few tiles, long batch (65 reduction steps in the weight gradients)
+    (1032, 4, 6, 3000, "relu", "bf16", 1),        # the same with 4-byte vectors and ragged tiles
 ]
 
 
@@ -197,18 +199,19 @@ def relu_margin(fw):
     return min(float(np.min(np.abs(A)) / np.sqrt(np.mean(A * A))) for A in fw["A"])
 
 
-def run_step(prob: pin.Problem, seed: int, lr: float):
+def run_step(prob: pin.Problem, seed: int, lr: float, with_grads: bool = True, ws=None):
     dt, L, q = prob.dtype, prob.layers, prob.peers
     all_ranks = prob.rank < 0
     data = pin.all_rank_step_inputs(prob, seed) if all_ranks else pin.one_rank_step_inputs(prob, seed)
     ref = oracle.ffn_step(prob.act, data["X0"], data["T"], data["layers"], lr, storage=dt, all_ranks=all_ranks)
     has = q > 0
     pc = _prob_c(prob)
-    ws = workspace(ph.workspace_bytes(pc))
+    if ws is None:
+        ws = workspace(ph.workspace_bytes(pc))
     names = ["Lw", "bias"] + (["Cw", "Dw"] if has else [])
     W = {nm: [to_gpu(P[nm], dt) for P in data["layers"]] for nm in names}
     M = {nm: [to_gpu_f32(P[nm]) for P in data["layers"]] for nm in names} if dt == "bf16" else {}
-    Gd = {nm: [empty_f32(P[nm].shape) for P in data["layers"]] for nm in names}
+    Gd = {nm: [empty_f32(P[nm].shape) for P in data["layers"]] for nm in names} if with_grads else {}
     G = [to_gpu(P["G"], dt) for P in data["layers"]] if (has and not all_ranks) else None
     dg = [to_gpu(P["dg_own"], dt) for P in data["layers"]] if (has and not all_ranks) else None
     X0, T = to_gpu(data["X0"], dt), to_gpu(data["T"], dt)
@@ -216,7 +219,7 @@ def run_step(prob: pin.Problem, seed: int, lr: float):
     loss = empty_f32((4,))
     ph.ffn_step(pc, X0, T, W["Lw"], W.get("Cw"), W.get("Dw"), W["bias"],
                 Lw_master=M.get("Lw"), Cw_master=M.get("Cw"), Dw_master=M.get("Dw"), bias_master=M.get("bias"),
-                G=G, dg_own=dg, dLw=Gd["Lw"], dCw=Gd.get("Cw"), dDw=Gd.get("Dw"), dbias=Gd["bias"],
+                G=G, dg_own=dg, dLw=Gd.get("Lw"), dCw=Gd.get("Cw"), dDw=Gd.get("Dw"), dbias=Gd.get("bias"),
                 Y_out=Y_out, loss=loss, lr=lr, workspace=ws)
     torch.cuda.synchronize()
     return data, ref, W, M, Gd, Y_out, float(loss[0])
@@ -268,6 +271,32 @@ def test_step_smooth_activations(n, p, k, B, L, act, dtype, rank):
     prob = pin.Problem(n=n, p=p, k=k, batch=B, layers=L, act=act, dtype=dtype, rank=rank)
     out = run_step(prob, seed=3, lr=0.05)
     check_step(prob, *out, 0.05)
+
+
+@pytest.mark.parametrize("n,p,k,B,L,act,rank", [
+    (2048, 8, 32, 4100, 2, "gelu", 0),       # one rank, long batch
+    (1024, 8, 16, 136, 3, "gelu", -1),       # all ranks on the device
+])
+def test_step_without_gradient_outputs(n, p, k, B, L, act, rank):
+    """A training step that is not asked for its gradients keeps them in the workspace: what the update
+    moved the master weights by against the oracle's gradients, the bf16 copies against the masters.
+    The workspace starts out full of NaN patterns, and is used for a second call as the first one left it."""
+    print(f"case step/no grads n={n} p={p} k={k} B={B} L={L} {act} rank={rank}", flush=True)
+    prob = pin.Problem(n=n, p=p, k=k, batch=B, layers=L, act=act, dtype="bf16", rank=rank)
+    lr = 0.05
+    ws = workspace(ph.workspace_bytes(_prob_c(prob)))
+    ws.fill_(0xFF)                            # whatever the step expects to be zero, it has to clear itself
+    for call in ("first call", "second call, same workspace"):
+        data, ref, W, M, _, Y_out, loss = run_step(prob, seed=5, lr=lr, with_grads=False, ws=ws)
+        assert_close("Y_L", Y_out, ref["forward"]["Y"][-1], "bf16")
+        assert abs(loss - ref["loss"]) <= 2e-2 * abs(ref["loss"]), call
+        for l in range(L):
+            for nm in W:
+                old = data["layers"][l][nm].astype(np.float32).astype(np.float64)
+                # the step moved the master weight by -lr * gradient: compare the movement with the oracle's gradient
+                moved = (M[nm][l].double().cpu().numpy() - old) / -lr
+                assert_close(f"d{nm}[{l}] (from the update, {call})", torch.from_numpy(moved), ref["grads"][l]["d" + nm], "bf16")
+                assert torch.equal(W[nm][l], M[nm][l].to(torch.bfloat16))
 
 
 def test_training_several_steps_fp32():
