@@ -20,18 +20,42 @@ __global__ __launch_bounds__(256) void delta_kernel(const T *__restrict__ dY, co
     }
 }
 
+// The loss of a step is left as partial sums (one per workgroup of the output-error kernel, or one per tile of
+// the last layer's product); a launch of its own for adding up to 1024 of them costs 4 us, so the first
+// memory-bound kernel that follows in the stream carries the sum as a rider: one of its workgroups (all
+// 256 threads) calls finish_loss, which adds the partial sums in a fixed order into loss = scale * sum.
+struct LossTail {
+    const float *partial;    // NULL: nothing to do
+    int n;
+    float scale;
+    float *loss;
+};
+
+__device__ __forceinline__ void finish_loss(const LossTail &t)
+{
+    __shared__ float lred[256];
+    float acc = 0.f;
+    for (int i = threadIdx.x; i < t.n; i += 256) acc += t.partial[i];
+    lred[threadIdx.x] = acc;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) lred[threadIdx.x] += lred[threadIdx.x + w];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *t.loss = lred[0] * t.scale;
+}
+
+__global__ __launch_bounds__(256) void loss_kernel(LossTail t) { finish_loss(t); }
+
 // Column sums of delta [rows x cols] (Eq. (bpb): dLoss/db = sum over the batch of delta).  One workgroup
 // owns CSUM_COLS columns of one group and rows [chunk*rows_per_chunk, ...): 16-byte loads, row lanes x
 // column lanes, one LDS reduction at the end.  With one chunk the result is stored (deterministic);
 // with several chunks (few columns, many rows) each adds its part atomically into the cleared output.
-// Rider (step only, loss_partial != NULL): workgroup (0,0,0) also adds up the per-workgroup partial
-// sums that the output-error kernel left, in index order, into loss = scale * sum; this kernel is the
-// next one in the stream, and a launch of its own for a 1024-element sum costs 4 us.
+// Rider (step only): workgroup (0,0,0) also finishes the loss (see LossTail).
 constexpr int CSUM_COLS = 128;
 template <typename T>
 __global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ delta, float *__restrict__ out, int rows, int cols,
-                                                    int rows_per_chunk, const float *__restrict__ loss_partial,
-                                                    int n_partial, float scale, float *__restrict__ loss)
+                                                    int rows_per_chunk, LossTail tail)
 {
     constexpr int VEC = 16 / (int)sizeof(T);            // elements per 16-byte load
     constexpr int CL = CSUM_COLS / VEC;                 // column lanes
@@ -72,18 +96,7 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ delta
             else unsafeAtomicAdd(out + (int64_t)g * cols + c, sum);
         }
     }
-    if (loss_partial && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) {      // uniform
-        __shared__ float lred[256];
-        float acc_l = 0.f;
-        for (int i = threadIdx.x; i < n_partial; i += 256) acc_l += loss_partial[i];
-        lred[threadIdx.x] = acc_l;
-        __syncthreads();
-        for (int w = 128; w > 0; w >>= 1) {
-            if ((int)threadIdx.x < w) lred[threadIdx.x] += lred[threadIdx.x + w];
-            __syncthreads();
-        }
-        if (threadIdx.x == 0) *loss = lred[0] * scale;
-    }
+    if (tail.partial && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) finish_loss(tail);      // uniform
 }
 
 // In-memory Reduce-Scatter of Algorithm 1's backward: dg_own[i] = sum_{j != i} dG_send[j][slot of i on j].
@@ -91,11 +104,12 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ delta
 // A workgroup owns 32 * VEC consecutive elements of one receiver: thread = (element vector, sender lane);
 // sender lane g adds the senders g, g + 8, g + 16, ... in fp32, the eight partial sums are added in lane
 // order through LDS (a fixed order, whatever p is).  With one thread walking all p-1 senders the kernel
-// was bound by the latency of its own loads (33 MB in 24 us at p = 64).
+// was bound by the latency of its own loads (33 MB in 24 us at p = 64).  Workgroup (0,0) may carry the
+// loss rider (LossTail).
 constexpr int RS_LANES = 8;
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void reduce_scatter_kernel(const T *__restrict__ dG_send, T *__restrict__ dg_own,
-                                                            int p, int64_t per_slot)
+                                                            int p, int64_t per_slot, LossTail tail)
 {
     typedef T TV __attribute__((ext_vector_type(VEC)));
     __shared__ float part[RS_LANES][32 * VEC + 1];
@@ -131,6 +145,7 @@ __global__ __launch_bounds__(256) void reduce_scatter_kernel(const T *__restrict
         for (int g = 0; g < RS_LANES; ++g) sum += part[g][c];
         dg_own[(int64_t)i * per_slot + at] = from_f32<T>(sum);
     }
+    if (tail.partial && blockIdx.x == 0 && blockIdx.y == 0) finish_loss(tail);      // uniform; rider, see LossTail
 }
 
 // MSE output error (Section IV-B, "Local error at the output", Eq. (deltaL)):
@@ -212,6 +227,7 @@ struct SgdTensor {
 };
 struct SgdBatch {
     SgdTensor t[4];
+    LossTail tail;       // rider for workgroup (0,0), see LossTail
 };
 
 template <typename T>
@@ -223,6 +239,7 @@ __global__ __launch_bounds__(256) void sgd_kernel(SgdBatch batch, float lr)
     if (blockIdx.y == 1) t = batch.t[1];
     if (blockIdx.y == 2) t = batch.t[2];
     if (blockIdx.y == 3) t = batch.t[3];
+    if (batch.tail.partial && blockIdx.x == 0 && blockIdx.y == 0) finish_loss(batch.tail);      // uniform
     typedef float F4 __attribute__((ext_vector_type(4)));
     typedef T T4 __attribute__((ext_vector_type(4)));
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;

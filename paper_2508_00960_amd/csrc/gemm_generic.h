@@ -18,6 +18,7 @@ struct Epilogue {
     const void *bias;    // EPI_BIAS_ACT: [N] per group, storage type
     int64_t bias_g;
     void *aux;           // EPI_BIAS_ACT: optional pre-activation out; EPI_DACT: pre-activation (or ReLU output) in
+                         //   (MFMA kernel: NULL = multiply by nothing, for the column sums alone)
     int64_t aux_ld;      //   plain row-major [M x N]
     int64_t aux_g;
     int32_t aux_f32;     // aux holds float instead of the storage type
@@ -25,6 +26,17 @@ struct Epilogue {
                          //   EPI_BIAS_ACT writes it, EPI_DACT multiplies by it as it stands (aux_f32 = 0)
     float *colsum;       // MFMA kernel only, optional: the column sums of the stored output (as rounded to
     int64_t colsum_g;    //   the output type) are ADDED to colsum[N] per group; the caller zeroes it first
+    // MFMA kernel only, EPI_BIAS_ACT, optional (mse_target != NULL): the layer is the last one and the MSE output
+    // error is formed on the way out (Eq. (deltaL)): with y the output as stored and t = mse_target (laid out
+    // like aux: aux_ld, aux_g, storage type), mse_delta <- ((y - t) * mse_inv_b) * sigma'(pre-activation)
+    // (sigma' as the backward pass would read it back: through fp16 for GELU, from y for ReLU), colsum
+    // then receives the column sums of mse_delta instead of y's, and mse_partial[tile] <- sum over the
+    // tile of (y - t)^2, tile = (group * ceil(M/128) + tile row) * ceil(N/128) + tile column.
+    const void *mse_target;
+    void *mse_delta;
+    float *mse_partial;
+    float mse_inv_b;
+    int32_t pad_;
 };
 
 constexpr int GT = 64;   // tile edge

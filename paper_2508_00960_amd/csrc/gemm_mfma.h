@@ -453,7 +453,7 @@ __device__ __forceinline__ void fast_step(f32x16 (&acc)[2][2], bf16x8 (&fr)[2][4
 constexpr int CT_PITCH = MT + 4;                       // floats per row of an fp32 tile in LDS (132 = 4 mod 64: the 16-byte
                                                        // writes of 16 lanes in 16 different rows fall on 64 different banks)
 constexpr int CT_ELEMS = MT * CT_PITCH;                // one tile per team
-static_assert(2 * CT_ELEMS * 4 <= MFMA_LDS_BYTES, "both teams' fp32 tiles fit in the staging space");
+static_assert((2 * CT_ELEMS + MFMA_THREADS / 64) * 4 <= MFMA_LDS_BYTES, "both teams' fp32 tiles and one float per wavefront fit in the staging space");
 
 // A wavefront's 64 x 64 block of accumulators -> its team's fp32 tile in LDS.
 // The MFMAs are issued with the B operand first, i.e. they compute the transpose of each 32 x 32 block:
@@ -489,13 +489,13 @@ struct AuxAhead {
     uint4 raw[ON ? PASSES : 1][2];
 };
 
-template <int VEC, bool SOLO>
+template <int VEC, bool SOLO, int EPI>
 __device__ __forceinline__ void epilogue_prefetch(const MfmaParams &P, int g, int m0, int n0, int thread, AuxAhead<VEC, SOLO> &ah)
 {
     typedef AuxAhead<VEC, SOLO> AH;
-    if constexpr (AH::ON) {
+    if constexpr (AH::ON && EPI == EPI_DACT) {
         const Epilogue &ep = P.ep;
-        if (ep.mode != EPI_DACT) return;               // uniform
+        if (ep.mode != EPI_DACT || !ep.aux) return;    // uniform
 #pragma unroll
         for (int i = 0; i < AH::PASSES; ++i) {
             const int v = thread + i * AH::THREADS;
@@ -516,11 +516,14 @@ __device__ __forceinline__ void epilogue_prefetch(const MfmaParams &P, int g, in
 
 // rows [m0, m0+128) x columns [n0, n0+128) of the output = sum of the two teams' fp32 tiles in LDS, walked by
 // all 512 threads; SOLO: the tile at ctile alone, walked by the 256 threads of one team (thread = 0..255)
-template <int VEC, typename TOut, bool SOLO>
+// EPI: the only mode other than EPI_STORE that the kernel is built for (the first product's; the second
+// product of a pair always stores plainly).  Building every mode into every kernel made the epilogue, which
+// every workgroup runs exactly once and so fetches cold, long enough to cost each launch about 1 us.
+template <int VEC, typename TOut, bool SOLO, int EPI>
 __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, const float *ctile, int m0, int n0, int thread,
-                                                  const AuxAhead<VEC, SOLO> &ah)
+                                                  const AuxAhead<VEC, SOLO> &ah, float *wave_sums)
 {
-    constexpr bool AHEAD = AuxAhead<VEC, SOLO>::ON;
+    constexpr bool AHEAD = AuxAhead<VEC, SOLO>::ON && EPI == EPI_DACT;
     constexpr int THREADS = SOLO ? 256 : MFMA_THREADS;
     typedef typename PackOf<TOut, VEC>::type OutV;
     typedef typename PackOf<__bf16, VEC>::type BfV;
@@ -535,6 +538,7 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
     float csum[VEC];                                   // this thread's share of the column sums (ep.colsum)
 #pragma unroll
     for (int u = 0; u < VEC; ++u) csum[u] = 0.f;
+    float sq_sum = 0.f;                                // ... and of the squared output error (ep.mse_target)
 #pragma unroll AHEAD ? PASSES : 2
     for (int i = 0; i < PASSES; ++i) {
         const int v = thread + i * THREADS;
@@ -554,33 +558,34 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
             }
         }
         const int64_t aux_at = g * ep.aux_g + (int64_t)m * ep.aux_ld + n;
-        if (ep.mode == EPI_BIAS_ACT) {
+        float deriv[VEC];                              // EPI_BIAS_ACT: sigma'(pre-activation), for the output error
+        if (EPI == EPI_BIAS_ACT && ep.mode == EPI_BIAS_ACT) {
             const BfV b = *(const BfV *)((const __bf16 *)ep.bias + g * ep.bias_g + n);
 #pragma unroll
             for (int u = 0; u < VEC; ++u) x[u] += (float)b[u];
             if (ep.act == ACT_GELU) {                  // uniform
-                float d[VEC];
+                float pre[VEC];
 #pragma unroll
                 for (int u = 0; u < VEC; ++u) {
-                    const float pre = x[u];
-                    gelu_both(pre, x[u], d[u]);
-                    if (!ep.aux_deriv) d[u] = pre;
+                    pre[u] = x[u];
+                    gelu_both(pre[u], x[u], deriv[u]);
+                    deriv[u] = (float)(_Float16)deriv[u];      // as stored for, and read back by, the backward pass
                 }
                 if (ep.aux) {
                     if (ep.aux_deriv) {
                         HfV a;
 #pragma unroll
-                        for (int u = 0; u < VEC; ++u) a[u] = (_Float16)d[u];
+                        for (int u = 0; u < VEC; ++u) a[u] = (_Float16)deriv[u];
                         *(HfV *)((_Float16 *)ep.aux + aux_at) = a;
                     } else if (ep.aux_f32) {
                         FlV a;
 #pragma unroll
-                        for (int u = 0; u < VEC; ++u) a[u] = d[u];
+                        for (int u = 0; u < VEC; ++u) a[u] = pre[u];
                         *(FlV *)((float *)ep.aux + aux_at) = a;
                     } else {
                         BfV a;
 #pragma unroll
-                        for (int u = 0; u < VEC; ++u) a[u] = (__bf16)d[u];
+                        for (int u = 0; u < VEC; ++u) a[u] = (__bf16)pre[u];
                         *(BfV *)((__bf16 *)ep.aux + aux_at) = a;
                     }
                 }
@@ -604,9 +609,12 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < VEC; ++u) x[u] = act_apply(ep.act, x[u]);
+                for (int u = 0; u < VEC; ++u) {
+                    deriv[u] = act_deriv(ep.act, x[u]);
+                    x[u] = act_apply(ep.act, x[u]);
+                }
             }
-        } else if (ep.mode == EPI_DACT) {
+        } else if (EPI == EPI_DACT && ep.mode == EPI_DACT && ep.aux) {      // no aux: sigma' = 1, column sums only
             if (ep.aux_f32) {
                 FlV a;
                 if constexpr (AHEAD) {
@@ -656,10 +664,44 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
 #pragma unroll
         for (int u = 0; u < VEC; ++u) o[u] = from_f32<TOut>(x[u]);
         *(OutV *)dst = o;
+        if (EPI == EPI_BIAS_ACT && sizeof(TOut) == 2 && ep.mode == EPI_BIAS_ACT && ep.mse_target) {      // uniform
+            // the MSE output error of Eq. (deltaL) from the output as stored, rounded once
+            const BfV t = *(const BfV *)((const __bf16 *)ep.mse_target + aux_at);
+            BfV dl;
 #pragma unroll
-        for (int u = 0; u < VEC; ++u) csum[u] += (float)o[u];
+            for (int u = 0; u < VEC; ++u) {
+                const float diff = (float)o[u] - (float)t[u];
+                sq_sum += diff * diff;
+                float e = diff * ep.mse_inv_b;
+                if (ep.act != ACT_IDENTITY) e *= deriv[u];
+                dl[u] = (__bf16)e;
+                csum[u] += (float)dl[u];
+            }
+            *(BfV *)((__bf16 *)ep.mse_delta + aux_at) = dl;
+        } else {
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) csum[u] += (float)o[u];
+        }
     }
-    if (ep.colsum) {                                   // uniform
+    if (EPI == EPI_BIAS_ACT && sizeof(TOut) == 2 && ep.mode == EPI_BIAS_ACT && ep.mse_target) {          // uniform
+        // the tile's share of sum (y - t)^2: wavefront sums, then one thread adds those of the tile's wavefronts
+        // (wave_sums lies behind the fp32 tiles; nothing else uses it)
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) sq_sum += __shfl_down(sq_sum, off);
+        const int wave_in_wg = (int)(threadIdx.x >> 6);
+        if ((threadIdx.x & 63) == 0) wave_sums[wave_in_wg] = sq_sum;
+        __syncthreads();
+        if (thread == 0 && m0 < P.M) {
+            constexpr int WAVES = THREADS / 64;
+            const int first = SOLO ? (int)(threadIdx.x >> 6) : 0;
+            float total = 0.f;
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) total += wave_sums[first + w];
+            const int tiles_m = (P.M + MT - 1) / MT, tiles_n = (P.N + MT - 1) / MT;
+            ep.mse_partial[(g * tiles_m + m0 / MT) * tiles_n + n0 / MT] = total;
+        }
+    }
+    if (EPI != EPI_STORE && ep.colsum) {               // uniform
         // threads tid, tid + PER_ROW, ... hold partial sums of the same VEC columns: add them up through
         // LDS (over the fp32 tiles, once every thread has read its share), one atomic per column
         constexpr int SHARERS = THREADS / PER_ROW;
@@ -757,11 +799,12 @@ __device__ __forceinline__ MfmaParams pick_params(bool second, const MfmaParams 
 // rows), so per FLOP a quarter less goes through the vector-memory return path and into LDS, which is
 // what bounds the loop; the price is half as many workgroups, so this is for launches with more tiles
 // than compute units (the host decides).  Each team finishes its own tile: no sum in the epilogue.
-template <int KA, int KB, int VA, int VB, typename TOut, bool ATOMIC, bool PAIR, bool DUAL>
+template <int KA, int KB, int VA, int VB, typename TOut, bool ATOMIC, bool PAIR, bool DUAL, int EPI>
 __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     static_assert(!(DUAL && ATOMIC), "a split reduction keeps the two-teams-per-tile form");
+    static_assert(!ATOMIC || EPI == EPI_STORE, "partial sums are added as they are");
     constexpr int BP = DUAL ? 2 : 1;                   // share of the B tile one team stages
     PH_PHASE(0);
 
@@ -901,7 +944,7 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
         if (t < steps) mfma_tile<KA, KB>(acc, s0a, s0b, wm, wn, lane);
     }
     AuxAhead<VA, DUAL> ahead;
-    epilogue_prefetch<VA, DUAL>(P, g, m0, n0, DUAL ? tid : (int)threadIdx.x, ahead);
+    epilogue_prefetch<VA, DUAL, EPI>(P, g, m0, n0, DUAL ? tid : (int)threadIdx.x, ahead);
     __syncthreads();
     PH_PHASE(3);
 #undef PH_FETCH
@@ -914,8 +957,8 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
     __syncthreads();
     PH_PHASE(4);
     if constexpr (ATOMIC) epilogue_atomic_from_lds(P, g, ctile, m0, n0, (int)threadIdx.x);
-    else if constexpr (DUAL) epilogue_from_lds<VA, TOut, true>(P, g, ctile + team * CT_ELEMS, m0, n0, tid, ahead);
-    else epilogue_from_lds<VA, TOut, false>(P, g, ctile, m0, n0, (int)threadIdx.x, ahead);
+    else if constexpr (DUAL) epilogue_from_lds<VA, TOut, true, EPI>(P, g, ctile + team * CT_ELEMS, m0, n0, tid, ahead, ctile + 2 * CT_ELEMS);
+    else epilogue_from_lds<VA, TOut, false, EPI>(P, g, ctile, m0, n0, (int)threadIdx.x, ahead, ctile + 2 * CT_ELEMS);
     PH_PHASE(5);
 }
 

@@ -214,6 +214,8 @@ inline unsigned blocks_for(int64_t count, int per_block = 256, int cap = 8192)
     return (unsigned)b;
 }
 
+inline int64_t tiles_of(int64_t M, int64_t N) { return ((M + MT - 1) / MT) * ((N + MT - 1) / MT); }
+
 // How a product is to be run: loader kinds of the two operands for the MFMA kernel, the vector
 // width the problem allows (0: use the shape-agnostic kernel), and whether the reduction may be
 // split over workgroups (float outputs only; the output is cleared first and added to atomically).
@@ -229,10 +231,10 @@ struct Product {
     int64_t M, N, K;
 };
 
-template <int KA, int KB, int VEC, typename TOut, bool ATOMIC, bool PAIR, bool DUAL>
+template <int KA, int KB, int VEC, typename TOut, bool ATOMIC, bool PAIR, bool DUAL, int EPI>
 ph_status launch_mfma_kernel(const MfmaBatch &batch, hipStream_t st, const char *what)
 {
-    auto kern = gemm_mfma_kernel<KA, KB, VEC, VEC, TOut, ATOMIC, PAIR, DUAL>;
+    auto kern = gemm_mfma_kernel<KA, KB, VEC, VEC, TOut, ATOMIC, PAIR, DUAL, EPI>;
     static thread_local bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, MFMA_LDS_BYTES);
@@ -244,26 +246,27 @@ ph_status launch_mfma_kernel(const MfmaBatch &batch, hipStream_t st, const char 
     return check_launch(what);
 }
 
-template <int KA, int KB, int VEC, typename TOut, bool ATOMIC>
+template <int KA, int KB, int VEC, typename TOut, bool ATOMIC, int EPI>
 ph_status launch_mfma_inst(const MfmaBatch &batch, bool dual, hipStream_t st, const char *what)
 {
     if constexpr (!ATOMIC) {
         if (dual) {
-            if (batch.count == 2) return launch_mfma_kernel<KA, KB, VEC, TOut, false, true, true>(batch, st, what);
-            return launch_mfma_kernel<KA, KB, VEC, TOut, false, false, true>(batch, st, what);
+            if (batch.count == 2) return launch_mfma_kernel<KA, KB, VEC, TOut, false, true, true, EPI>(batch, st, what);
+            return launch_mfma_kernel<KA, KB, VEC, TOut, false, false, true, EPI>(batch, st, what);
         }
     }
-    if (batch.count == 2) return launch_mfma_kernel<KA, KB, VEC, TOut, ATOMIC, true, false>(batch, st, what);
-    return launch_mfma_kernel<KA, KB, VEC, TOut, ATOMIC, false, false>(batch, st, what);
+    if (batch.count == 2) return launch_mfma_kernel<KA, KB, VEC, TOut, ATOMIC, true, false, EPI>(batch, st, what);
+    return launch_mfma_kernel<KA, KB, VEC, TOut, ATOMIC, false, false, EPI>(batch, st, what);
 }
 
-template <int KA, int KB, typename TOut, bool ATOMIC>
+// EPI: the epilogue mode the kernel is built for besides the plain store (see epilogue_from_lds)
+template <int KA, int KB, typename TOut, bool ATOMIC, int EPI>
 ph_status launch_mfma_vec(const MfmaBatch &batch, int vec, bool dual, hipStream_t st, const char *what)
 {
     switch (vec) {
-    case 8: return launch_mfma_inst<KA, KB, 8, TOut, ATOMIC>(batch, dual, st, what);
-    case 4: return launch_mfma_inst<KA, KB, 4, TOut, ATOMIC>(batch, dual, st, what);
-    default: return launch_mfma_inst<KA, KB, 2, TOut, ATOMIC>(batch, dual, st, what);
+    case 8: return launch_mfma_inst<KA, KB, 8, TOut, ATOMIC, EPI>(batch, dual, st, what);
+    case 4: return launch_mfma_inst<KA, KB, 4, TOut, ATOMIC, EPI>(batch, dual, st, what);
+    default: return launch_mfma_inst<KA, KB, 2, TOut, ATOMIC, EPI>(batch, dual, st, what);
     }
 }
 
@@ -334,16 +337,32 @@ ph_status launch_mfma(const GemmPlan &plan, const Product *prods, int count, int
                 PH_TRY(check_launch("clear split-K output"));
             }
             ProfScope prof(what, first.M, first.N, first.K, groups, st);
-            if (plan.ka == LD_KM && plan.kb == LD_KM) return launch_mfma_vec<LD_KM, LD_KM, float, true>(batch, plan.vec, false, st, what);
+            if (plan.ka == LD_KM && plan.kb == LD_KM) return launch_mfma_vec<LD_KM, LD_KM, float, true, EPI_STORE>(batch, plan.vec, false, st, what);
         }
         return fail(PH_ERR_UNSUPPORTED, "%s: split reduction not available for this operand layout", what);
     }
     ProfScope prof(what, first.M, first.N, first.K, groups, st, count == 2 ? second.M : 0, count == 2 ? second.N : 0,
                    count == 2 ? second.K : 0);
-    if (plan.ka == LD_KC && plan.kb == LD_KC) return launch_mfma_vec<LD_KC, LD_KC, TOut, false>(batch, plan.vec, dual, st, what);
-    if (plan.ka == LD_KC && plan.kb == LD_KM) return launch_mfma_vec<LD_KC, LD_KM, TOut, false>(batch, plan.vec, dual, st, what);
-    if (plan.ka == LD_KM && plan.kb == LD_KM) return launch_mfma_vec<LD_KM, LD_KM, TOut, false>(batch, plan.vec, dual, st, what);
-    return fail(PH_ERR_UNSUPPORTED, "%s: operand layout pair not built", what);
+    // The kernels that exist: the forward layout (both operands read along the reduction index) with the
+    // bias + activation epilogue, the input-gradient layout with the sigma' epilogue, each also with the plain
+    // store alone, in the storage type; the weight-gradient layout with the plain store in float.  The
+    // second product of a pair always stores plainly.
+    const int mode = first.ep.mode;
+    if (count == 2 && second.ep.mode != EPI_STORE) return fail(PH_ERR_UNSUPPORTED, "%s: the second product of a pair must store plainly", what);
+    if constexpr (std::is_same<TOut, float>::value) {
+        if (plan.ka == LD_KM && plan.kb == LD_KM && mode == EPI_STORE)
+            return launch_mfma_vec<LD_KM, LD_KM, float, false, EPI_STORE>(batch, plan.vec, dual, st, what);
+    } else {
+        if (plan.ka == LD_KC && plan.kb == LD_KC) {
+            if (mode == EPI_BIAS_ACT) return launch_mfma_vec<LD_KC, LD_KC, TOut, false, EPI_BIAS_ACT>(batch, plan.vec, dual, st, what);
+            if (mode == EPI_STORE) return launch_mfma_vec<LD_KC, LD_KC, TOut, false, EPI_STORE>(batch, plan.vec, dual, st, what);
+        }
+        if (plan.ka == LD_KC && plan.kb == LD_KM) {
+            if (mode == EPI_DACT) return launch_mfma_vec<LD_KC, LD_KM, TOut, false, EPI_DACT>(batch, plan.vec, dual, st, what);
+            if (mode == EPI_STORE) return launch_mfma_vec<LD_KC, LD_KM, TOut, false, EPI_STORE>(batch, plan.vec, dual, st, what);
+        }
+    }
+    return fail(PH_ERR_UNSUPPORTED, "%s: operand layout, output type and epilogue are not built together", what);
 }
 
 // Runs one product, or two independent ones of the same kind (names: `what` for the pair on the
@@ -421,7 +440,30 @@ struct FwdArgs {
     void *Y, *g_own, *A_save;
     bool a_f32;   // step only: A_save is float
     bool a_deriv; // step only: A_save receives sigma'(A) in fp16 instead of A
+    const struct OutputError *mse;   // step only, last layer: form the MSE output error in the update's epilogue
 };
+
+// What the last layer's update needs to leave the output error of the MSE loss behind (Epilogue::mse_*), and
+// the buffers the compression launch before it clears on its way (they are added into from then on).
+struct OutputError {
+    const void *target;      // [groups, B, s] storage type
+    void *delta;             // [groups, B, s] storage type
+    float *partial;          // one partial sum of squares per tile of the update
+    float inv_b;
+    float *dbias;            // [groups, s], receives the column sums of delta (zero on entry)
+    float *clear_at;         // cleared by the compression launch: clear_count floats
+    int64_t clear_count;
+};
+
+// Does the forward of this geometry run its compression as the thin kernel in a launch of its own (before the
+// update)?  Same conditions as in fwd_impl.
+bool thin_compression_first(const Geo &g)
+{
+    if (g.dtype != PH_BF16 || g.q == 0 || g.k > THIN_MAX_N || g.s % 16 != 0 || g.vec == 0) return false;
+    if (g.all) return true;
+    const int64_t tiles_both = (tiles_of(g.B, g.s) + tiles_of(g.B, g.k)) * g.groups;
+    return tiles_both > 256;
+}
 
 template <typename T>
 ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
@@ -442,6 +484,15 @@ ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
     update.ep.mode = EPI_BIAS_ACT; update.ep.act = g.act; update.ep.bias = f.bias; update.ep.bias_g = s;
     update.ep.aux = f.A_save; update.ep.aux_ld = s; update.ep.aux_g = B * s; update.ep.aux_f32 = f.a_f32; update.ep.aux_deriv = f.a_deriv;
     update.M = B; update.N = s; update.K = g.Kc;
+    float *clear_at = nullptr;
+    int64_t clear_count = 0;
+    if (f.mse) {
+        if (!thin_compression_first(g)) return fail(PH_ERR_LAUNCH, "output error in the update needs the thin compression launch");
+        update.ep.mse_target = f.mse->target; update.ep.mse_delta = f.mse->delta; update.ep.mse_partial = f.mse->partial;
+        update.ep.mse_inv_b = f.mse->inv_b;
+        update.ep.colsum = f.mse->dbias; update.ep.colsum_g = s;
+        clear_at = f.mse->clear_at; clear_count = f.mse->clear_count;
+    }
     // A compression with few phantom neurons has a kernel of its own (32 rows per workgroup instead of 128)
     bool thin = false;
     if constexpr (std::is_same<T, bf16_t>::value) thin = q > 0 && k <= THIN_MAX_N && s % 16 == 0 && g.vec > 0;
@@ -451,10 +502,10 @@ ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
             dim3 grid((unsigned)((B + THIN_ROWS - 1) / THIN_ROWS), (unsigned)g.groups);
             if (k <= 32)
                 hipLaunchKernelGGL((thin_product_kernel<1>), grid, dim3(256), 0, st, (const __bf16 *)f.X, (const __bf16 *)f.Cw,
-                                   (__bf16 *)f.g_own, (int)B, (int)k, (int)s, B * s, k * s, B * k);
+                                   (__bf16 *)f.g_own, (int)B, (int)k, (int)s, B * s, k * s, B * k, clear_at, clear_count);
             else
                 hipLaunchKernelGGL((thin_product_kernel<2>), grid, dim3(256), 0, st, (const __bf16 *)f.X, (const __bf16 *)f.Cw,
-                                   (__bf16 *)f.g_own, (int)B, (int)k, (int)s, B * s, k * s, B * k);
+                                   (__bf16 *)f.g_own, (int)B, (int)k, (int)s, B * s, k * s, B * k, clear_at, clear_count);
             return check_launch("compression");
         }
         return PH_OK;
@@ -467,7 +518,7 @@ ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
     }
     // one rank: the peers' g are inputs, so the rank's own compression runs beside the update when the two
     // fit the device together
-    const int64_t tiles_both = (((B + MT - 1) / MT) * ((s + MT - 1) / MT) + ((B + MT - 1) / MT) * ((k + MT - 1) / MT)) * g.groups;
+    const int64_t tiles_both = (tiles_of(B, s) + tiles_of(B, k)) * g.groups;
     if (thin && tiles_both > 256) {
         PH_TRY(launch_thin());
         return launch_products<T, T>(plan, &update, 1, g.groups, st, "layer update");
@@ -492,10 +543,8 @@ struct BwdArgs {
                                //   of what it stores, i.e. the layer below's bias gradient (Eq. (bpb))
     bool dbias_ready;          // step only: dbias already holds the column sums of delta
     bool dbias_zeroed;         // step only: dbias is zero on entry
-    const float *loss_partial; // step only, last layer: the bias-gradient kernel also finishes the loss
-    int loss_parts;            //   = loss_scale * sum of loss_partial[0 .. loss_parts)
-    float loss_scale;
-    float *loss;
+    LossTail *loss_tail;       // step only, last layer: the first memory-bound kernel of this backward finishes
+                               //   the loss as a rider and clears loss_tail->partial; left alone if there is none
 };
 
 template <typename T>
@@ -513,6 +562,13 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
         PH_TRY(check_launch("local error"));
         delta = w.delta;
     }
+
+    // the loss rider goes to the first launch that can carry it
+    auto take_tail = [&]() {
+        LossTail t{};
+        if (b.loss_tail) { t = *b.loss_tail; b.loss_tail->partial = nullptr; }
+        return t;
+    };
 
     // bias gradient: column sums of delta
     {
@@ -532,7 +588,7 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
             dim3 grid((unsigned)strips, (unsigned)g.groups, (unsigned)chunks);
             ProfScope prof("bias gradient", 0, act_count, 0, 1, st);
             hipLaunchKernelGGL((colsum_kernel<T>), grid, dim3(256), 0, st, (const T *)delta, b.dbias, (int)B, (int)s,
-                               rows_per_chunk, b.loss_partial, b.loss_parts, b.loss_scale, b.loss);
+                               rows_per_chunk, take_tail());
             PH_TRY(check_launch("bias gradient"));
         }
     }
@@ -558,6 +614,8 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
     if (b.dx_S && g.act != PH_ACT_IDENTITY) {
         dx.ep.mode = EPI_DACT; dx.ep.act = g.act; dx.ep.aux = const_cast<void *>(b.dx_S); dx.ep.aux_ld = s;
         dx.ep.aux_g = B * s; dx.ep.aux_f32 = b.dx_S_f32; dx.ep.aux_deriv = b.dx_S_deriv;
+    } else if (b.dx_colsum) {
+        dx.ep.mode = EPI_DACT; dx.ep.act = g.act; dx.ep.aux = nullptr;      // identity: column sums only
     }
     dx.ep.colsum = b.dx_colsum; dx.ep.colsum_g = s;
     dx.M = b.dX ? B : 0; dx.N = s; dx.K = s + k;
@@ -575,10 +633,10 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
             ProfScope prof("reduce-scatter", 0, per_slot * g.p * (g.p - 1), 0, 1, st);
             if (wide)
                 hipLaunchKernelGGL((reduce_scatter_kernel<T, RS_VEC>), grid, dim3(256), 0, st, (const T *)b.dG_send,
-                                   (T *)b.dg_own, (int)g.p, per_slot);
+                                   (T *)b.dg_own, (int)g.p, per_slot, take_tail());
             else
                 hipLaunchKernelGGL((reduce_scatter_kernel<T, 1>), grid, dim3(256), 0, st, (const T *)b.dG_send,
-                                   (T *)b.dg_own, (int)g.p, per_slot);
+                                   (T *)b.dg_own, (int)g.p, per_slot, take_tail());
             PH_TRY(check_launch("reduce-scatter"));
         }
         PH_TRY((launch_products<T, T>(plan_x, &dx, 1, g.groups, st, "input gradient")));
@@ -655,13 +713,40 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
     const bool gelu = g.act == PH_ACT_GELU;
     const bool save_deriv = gelu && std::is_same<T, bf16_t>::value;
 
+    // Bias gradients (Eq. (bpb)) are column sums of delta.  On the MFMA path the product that writes a
+    // layer's delta (the input gradient of the layer above; for the last layer its own update, see below)
+    // adds them up on its way out, so every layer's bias gradient has a buffer of its own that is zeroed once
+    // for the whole step: the caller's buffers by launches of their own, the workspace's (one block) by a
+    // kernel that runs anyway.
+    const bool train = a.mode != PH_STEP_FORWARD;
+    const bool fused_dbias = std::is_same<T, bf16_t>::value && g.vec > 0;
+    const int64_t bias_count = (int64_t)g.groups * s;
+    auto dbias_of = [&](int l) { return a.dbias ? a.dbias[l] : w.dbias + (int64_t)l * bias_count; };
+    if (train && a.dbias) {
+        for (int l = 0; l < L; ++l) {
+            hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks_for(bias_count)), dim3(256), 0, st, a.dbias[l], bias_count);
+            PH_TRY(check_launch("clear bias gradients"));
+        }
+    }
+    float *clear_at = a.dbias ? nullptr : w.dbias;
+    const int64_t clear_count = a.dbias ? 0 : bias_count * L;
+
+    // The output error of the MSE loss (Eq. (deltaL)) is elementwise in the last layer's output, so on the MFMA
+    // path that layer's update forms it in its epilogue, together with the last bias gradient and one partial
+    // sum of the loss per tile: two launches less than a kernel for the error and one for the column sums.
+    // The buffers it adds into are cleared by the compression launch right before it, hence the conditions.
+    const int64_t out_tiles = tiles_of(B, s) * g.groups;
+    const bool mse_in_update = train && fused_dbias && thin_compression_first(g) && out_tiles <= MSE_BLOCKS;
+    OutputError oe{a.T, w.dYa, w.mse_partial, 1.0f / (float)B, dbias_of(L - 1), clear_at, clear_count};
+
     // forward through every layer; y_l stays in the storage type between layers
     const void *in = a.X0;
     std::vector<const void *> inputs(L);
     for (int l = 0; l < L; ++l) {
         inputs[l] = in;
         FwdArgs f{in, a.Lw[l], q ? a.Cw[l] : nullptr, q ? a.Dw[l] : nullptr, a.bias[l],
-                  (q && !g.all) ? a.G[l] : nullptr, w.Y[l], w.G[l], w.A[l], !save_deriv, save_deriv};
+                  (q && !g.all) ? a.G[l] : nullptr, w.Y[l], w.G[l], w.A[l], !save_deriv, save_deriv,
+                  (mse_in_update && l == L - 1) ? &oe : nullptr};
         PH_TRY(fwd_impl<T>(g, f, st));
         in = w.Y[l];
     }
@@ -670,32 +755,18 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
                            (T *)a.Y_out, act_count);
         PH_TRY(check_launch("output copy"));
     }
-    if (a.mode == PH_STEP_FORWARD) return PH_OK;
+    if (!train) return PH_OK;
 
-    // Bias gradients (Eq. (bpb)) are column sums of delta.  On the MFMA path the product that writes a
-    // layer's delta (the input gradient of the layer above) adds them up on its way out, so every
-    // layer's bias gradient has a buffer of its own that is zeroed here, once for the whole step.
-    const bool fused_dbias = std::is_same<T, bf16_t>::value && g.vec > 0;
-    const int64_t bias_count = (int64_t)g.groups * s;
-    auto dbias_of = [&](int l) { return a.dbias ? a.dbias[l] : w.dbias + (int64_t)l * bias_count; };
-    if (a.dbias) {
-        for (int l = 0; l < L; ++l) {
-            hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks_for(bias_count)), dim3(256), 0, st, a.dbias[l], bias_count);
-            PH_TRY(check_launch("clear bias gradients"));
-        }
-    }
-    // (the workspace's own bias-gradient buffers are one block: the output-error kernel clears it on its way)
-    float *clear_at = a.dbias ? nullptr : w.dbias;
-    const int64_t clear_count = a.dbias ? 0 : bias_count * L;
-
-    // output error of the MSE loss, already multiplied by sigma_L' (Eq. (deltaL)); the loss's partial sums are
-    // added up by the last layer's bias-gradient kernel, the next launch
-    unsigned mse_blocks = 0;
-    {
+    // The loss is the sum of partial sums that the output-error computation leaves; the first memory-bound
+    // kernel after it adds them up as a rider (LossTail), a kernel of its own if there is none.
+    LossTail loss_tail{w.mse_partial, (int)out_tiles, 0.5f / (float)B, a.loss};
+    if (!mse_in_update) {
+        // output error as a kernel of its own; it also clears the workspace's bias-gradient block
         const void *S = gelu ? w.A[L - 1] : w.Y[L - 1];
         const int s_kind = save_deriv ? 2 : (gelu ? 1 : 0);
         const bool wide = act_count % 8 == 0 && (((uintptr_t)a.T | (uintptr_t)w.Y[L - 1] | (uintptr_t)S | (uintptr_t)w.dYa) & 31) == 0;
-        mse_blocks = blocks_for(wide ? act_count / 8 : act_count, 256, MSE_BLOCKS);
+        const unsigned mse_blocks = blocks_for(wide ? act_count / 8 : act_count, 256, MSE_BLOCKS);
+        loss_tail.n = (int)mse_blocks;
         ProfScope prof("output error", 0, act_count, 0, 1, st);
         if (wide)
             hipLaunchKernelGGL((mse_delta_kernel<T, 8>), dim3(mse_blocks), dim3(256), 0, st, (const T *)w.Y[L - 1],
@@ -712,8 +783,8 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
     for (int l = L - 1; l >= 0; --l) {
         BwdArgs b{};
         b.dbias_zeroed = true;
-        if (l == L - 1) { b.loss_partial = w.mse_partial; b.loss_parts = (int)mse_blocks; b.loss_scale = 0.5f / (float)B; b.loss = a.loss; }
-        b.dbias_ready = fused_dbias && l < L - 1;
+        b.loss_tail = &loss_tail;
+        b.dbias_ready = fused_dbias && (l < L - 1 || mse_in_update);
         b.dx_colsum = (fused_dbias && l > 0) ? dbias_of(l - 1) : nullptr;
         b.delta_ready = dY; b.X = inputs[l];
         b.dx_S = l > 0 ? (g.act == PH_ACT_GELU ? w.A[l - 1] : w.Y[l - 1]) : nullptr;
@@ -730,7 +801,16 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
         b.dG_send = w.dG_send;
         PH_TRY(bwd_impl<T>(g, b, w.bwd, st));
 
-        if (a.mode == PH_STEP_NO_UPDATE) { void *t = dY; dY = dX; dX = t; continue; }
+        if (a.mode == PH_STEP_NO_UPDATE) {
+            if (loss_tail.partial) {                   // no kernel of this layer's backward could carry the rider
+                ProfScope prof("loss", 0, loss_tail.n, 0, 1, st);
+                hipLaunchKernelGGL(loss_kernel, dim3(1), dim3(256), 0, st, loss_tail);
+                PH_TRY(check_launch("loss"));
+                loss_tail.partial = nullptr;
+            }
+            void *t = dY; dY = dX; dX = t;
+            continue;
+        }
         // SGD on this layer: nothing later in the backward pass reads its weights
         struct Upd { void *w; float *master; const float *grad; int64_t count; };
         Upd upd[4] = {
@@ -749,6 +829,8 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
             total += u.count;
         }
         if (tensors > 0) {
+            batch.tail = loss_tail;                    // still set: no kernel of this layer's backward carried the rider
+            loss_tail.partial = nullptr;
             ProfScope prof("SGD update", 0, total, 0, 1, st);
             hipLaunchKernelGGL((sgd_kernel<T>), dim3(blocks_for(largest, 256, 2048), (unsigned)tensors), dim3(256), 0, st, batch, a.lr);
             PH_TRY(check_launch("SGD update"));

@@ -20,11 +20,17 @@ typedef float thin_f32x16 __attribute__((ext_vector_type(16)));
 
 // NF = number of 32-wide column blocks (1: N <= 32, 2: N <= 64).  K is a multiple of 16.
 // x_g, c_g, o_g: element offsets per group (blockIdx.y).
+// Rider: the kernel also clears zero_count floats at `zero` (buffers that later launches of a training step
+// add into; the compression is the launch before the first of them).
 template <int NF>
 __global__ __launch_bounds__(256) void thin_product_kernel(const __bf16 *__restrict__ X, const __bf16 *__restrict__ C,
                                                           __bf16 *__restrict__ G, int M, int N, int K,
-                                                          int64_t x_g, int64_t c_g, int64_t o_g)
+                                                          int64_t x_g, int64_t c_g, int64_t o_g,
+                                                          float *__restrict__ zero, int64_t zero_count)
 {
+    for (int64_t z = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x; z < zero_count;
+         z += (int64_t)gridDim.x * gridDim.y * 256)
+        zero[z] = 0.f;
     __shared__ float part[4][NF][16][64];              // [wavefront][column block][accumulator][lane]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int grp = blockIdx.y;
