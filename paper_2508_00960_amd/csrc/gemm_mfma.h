@@ -476,44 +476,6 @@ __device__ __forceinline__ void acc_to_lds(float *ctile, const f32x16 (&acc)[2][
 
 template <typename T, int VEC> struct PackOf { typedef T type __attribute__((ext_vector_type(VEC))); };
 
-// EPI_DACT multiplies by sigma'(A) with A read from memory: a load per output vector whose latency would
-// sit between the tile exchange and the stores.  With 8-element vectors (the common case) the loads are
-// issued before the exchange instead and wait in registers: AuxAhead holds their raw 16-byte pieces
-// (fp32 A: two per vector, 16-bit A or sigma': one).
-template <int VEC, bool SOLO>
-struct AuxAhead {
-    static constexpr bool ON = VEC == 8;
-    static constexpr int THREADS = SOLO ? 256 : MFMA_THREADS;
-    static constexpr int PER_ROW = MT / VEC;
-    static constexpr int PASSES = MT * PER_ROW / THREADS;
-    uint4 raw[ON ? PASSES : 1][2];
-};
-
-template <int VEC, bool SOLO, int EPI>
-__device__ __forceinline__ void epilogue_prefetch(const MfmaParams &P, int g, int m0, int n0, int thread, AuxAhead<VEC, SOLO> &ah)
-{
-    typedef AuxAhead<VEC, SOLO> AH;
-    if constexpr (AH::ON && EPI == EPI_DACT) {
-        const Epilogue &ep = P.ep;
-        if (ep.mode != EPI_DACT || !ep.aux) return;    // uniform
-#pragma unroll
-        for (int i = 0; i < AH::PASSES; ++i) {
-            const int v = thread + i * AH::THREADS;
-            const int row = v / AH::PER_ROW, col = (v % AH::PER_ROW) * VEC;
-            const int m = m0 + row, n = n0 + col;
-            if (m >= P.M || n >= P.N) continue;
-            const int64_t aux_at = g * ep.aux_g + (int64_t)m * ep.aux_ld + n;
-            if (ep.aux_f32) {
-                const uint4 *src = (const uint4 *)((const float *)ep.aux + aux_at);
-                ah.raw[i][0] = src[0];
-                ah.raw[i][1] = src[1];
-            } else {
-                ah.raw[i][0] = *(const uint4 *)((const __bf16 *)ep.aux + aux_at);
-            }
-        }
-    }
-}
-
 // rows [m0, m0+128) x columns [n0, n0+128) of the output = sum of the two teams' fp32 tiles in LDS, walked by
 // all 512 threads; SOLO: the tile at ctile alone, walked by the 256 threads of one team (thread = 0..255)
 // EPI: the only mode other than EPI_STORE that the kernel is built for (the first product's; the second
@@ -521,9 +483,8 @@ __device__ __forceinline__ void epilogue_prefetch(const MfmaParams &P, int g, in
 // every workgroup runs exactly once and so fetches cold, long enough to cost each launch about 1 us.
 template <int VEC, typename TOut, bool SOLO, int EPI>
 __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, const float *ctile, int m0, int n0, int thread,
-                                                  const AuxAhead<VEC, SOLO> &ah, float *wave_sums)
+                                                  float *wave_sums)
 {
-    constexpr bool AHEAD = AuxAhead<VEC, SOLO>::ON && EPI == EPI_DACT;
     constexpr int THREADS = SOLO ? 256 : MFMA_THREADS;
     typedef typename PackOf<TOut, VEC>::type OutV;
     typedef typename PackOf<__bf16, VEC>::type BfV;
@@ -539,7 +500,7 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
 #pragma unroll
     for (int u = 0; u < VEC; ++u) csum[u] = 0.f;
     float sq_sum = 0.f;                                // ... and of the squared output error (ep.mse_target)
-#pragma unroll AHEAD ? PASSES : 2
+#pragma unroll 2
     for (int i = 0; i < PASSES; ++i) {
         const int v = thread + i * THREADS;
         const int row = v / PER_ROW, col = (v % PER_ROW) * VEC;
@@ -616,44 +577,19 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
             }
         } else if (EPI == EPI_DACT && ep.mode == EPI_DACT && ep.aux) {      // no aux: sigma' = 1, column sums only
             if (ep.aux_f32) {
-                FlV a;
-                if constexpr (AHEAD) {
-                    const uint4 lo = ah.raw[i][0], hi = ah.raw[i][1];
-                    const uint32_t w[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
-#pragma unroll
-                    for (int u = 0; u < VEC; ++u) a[u] = __uint_as_float(w[u]);
-                } else {
-                    a = *(const FlV *)((const float *)ep.aux + aux_at);
-                }
+                const FlV a = *(const FlV *)((const float *)ep.aux + aux_at);
 #pragma unroll
                 for (int u = 0; u < VEC; ++u) x[u] *= act_deriv(ep.act, a[u]);
             } else {
-                // 16-bit aux: the pre-activation (or ReLU output) in bf16, or sigma' itself in fp16
-                uint32_t w[VEC / 2 > 0 ? VEC / 2 : 1];
-                float a[VEC];
-                if constexpr (AHEAD) {
-                    const uint4 q = ah.raw[i][0];
-                    w[0] = q.x; w[1] = q.y; w[2] = q.z; w[3] = q.w;
-                } else if constexpr (VEC >= 2) {
-                    typedef uint32_t WV __attribute__((ext_vector_type(VEC / 2)));
-                    const WV q = *(const WV *)((const uint16_t *)ep.aux + aux_at);
-#pragma unroll
-                    for (int u = 0; u < VEC / 2; ++u) w[u] = q[u];
-                } else {
-                    w[0] = *((const uint16_t *)ep.aux + aux_at);
-                }
+                // 16-bit aux: sigma' itself in fp16, or the pre-activation (or ReLU output) in bf16
                 if (ep.aux_deriv) {
+                    const HfV a = *(const HfV *)((const _Float16 *)ep.aux + aux_at);
 #pragma unroll
-                    for (int u = 0; u < VEC; ++u) {
-                        const uint16_t bits = (uint16_t)((u & 1) ? (w[u >> 1] >> 16) : (w[u >> 1] & 0xffffu));
-                        x[u] *= (float)__builtin_bit_cast(_Float16, bits);
-                    }
+                    for (int u = 0; u < VEC; ++u) x[u] *= (float)a[u];
                 } else {
+                    const BfV a = *(const BfV *)((const __bf16 *)ep.aux + aux_at);
 #pragma unroll
-                    for (int u = 0; u < VEC; ++u) {    // bf16 = the upper half of the fp32 pattern
-                        a[u] = __uint_as_float((u & 1) ? (w[u >> 1] & 0xffff0000u) : (w[u >> 1] << 16));
-                        x[u] *= act_deriv(ep.act, a[u]);
-                    }
+                    for (int u = 0; u < VEC; ++u) x[u] *= act_deriv(ep.act, (float)a[u]);
                 }
             }
         }
@@ -943,8 +879,6 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
 #undef PH_STEP
         if (t < steps) mfma_tile<KA, KB>(acc, s0a, s0b, wm, wn, lane);
     }
-    AuxAhead<VA, DUAL> ahead;
-    epilogue_prefetch<VA, DUAL, EPI>(P, g, m0, n0, DUAL ? tid : (int)threadIdx.x, ahead);
     __syncthreads();
     PH_PHASE(3);
 #undef PH_FETCH
@@ -957,8 +891,8 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
     __syncthreads();
     PH_PHASE(4);
     if constexpr (ATOMIC) epilogue_atomic_from_lds(P, g, ctile, m0, n0, (int)threadIdx.x);
-    else if constexpr (DUAL) epilogue_from_lds<VA, TOut, true, EPI>(P, g, ctile + team * CT_ELEMS, m0, n0, tid, ahead, ctile + 2 * CT_ELEMS);
-    else epilogue_from_lds<VA, TOut, false, EPI>(P, g, ctile, m0, n0, (int)threadIdx.x, ahead, ctile + 2 * CT_ELEMS);
+    else if constexpr (DUAL) epilogue_from_lds<VA, TOut, true, EPI>(P, g, ctile + team * CT_ELEMS, m0, n0, tid, ctile + 2 * CT_ELEMS);
+    else epilogue_from_lds<VA, TOut, false, EPI>(P, g, ctile, m0, n0, (int)threadIdx.x, ctile + 2 * CT_ELEMS);
     PH_PHASE(5);
 }
 
