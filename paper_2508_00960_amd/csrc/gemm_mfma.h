@@ -699,7 +699,7 @@ __device__ __forceinline__ void epilogue_atomic_from_lds(const MfmaParams &P, in
 
 #ifdef PHANTOM_TIMELINE   // cycle stamps for the development micro-benchmark, never built into the library
 #define PH_PHASE(slot) do { __builtin_amdgcn_sched_barrier(0); if ((blockIdx.x == 0 || blockIdx.x == gridDim.x - 1) && threadIdx.x == 0) \
-        ((long long *)batch.p[0].ep.aux)[(blockIdx.x ? 16 : 0) + (slot)] = clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
+        ((long long *)P.ep.aux)[(blockIdx.x ? 16 : 0) + (slot)] = clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
 #else
 #define PH_PHASE(slot) do { } while (0)
 #endif
@@ -735,27 +735,23 @@ __device__ __forceinline__ MfmaParams pick_params(bool second, const MfmaParams 
 // rows), so per FLOP a quarter less goes through the vector-memory return path and into LDS, which is
 // what bounds the loop; the price is half as many workgroups, so this is for launches with more tiles
 // than compute units (the host decides).  Each team finishes its own tile: no sum in the epilogue.
-template <int KA, int KB, int VA, int VB, typename TOut, bool ATOMIC, bool PAIR, bool DUAL, int EPI>
-__global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
+// XCD-aware id: hardware deals workgroup ids round-robin over 8 XCDs; `first` (a multiple of 8) is the id of the
+// first of `count` consecutive workgroups that share a list of tiles.  Workgroups of one XCD get neighbouring tiles.
+__device__ __forceinline__ int xcd_order(int id, int first, int count)
+{
+    const int i = id - first, per = count >> 3;
+    return i < per * 8 ? (i & 7) * per + (i >> 3) : i;
+}
+
+// One workgroup's work: workgroup number wg (of P.total_wg, in tile order) of the product P.
+template <int KA, int KB, int VA, int VB, typename TOut, bool ATOMIC, bool DUAL, int EPI>
+__device__ __forceinline__ void mfma_workgroup(const MfmaParams &P, int wg)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     static_assert(!(DUAL && ATOMIC), "a split reduction keeps the two-teams-per-tile form");
     static_assert(!ATOMIC || EPI == EPI_STORE, "partial sums are added as they are");
     constexpr int BP = DUAL ? 2 : 1;                   // share of the B tile one team stages
     PH_PHASE(0);
-
-    // XCD-aware id: hardware deals workgroup ids round-robin over 8 XCDs
-    int wg = blockIdx.x;
-    {
-        const int per = batch.total_wg >> 3;
-        if (wg < per * 8) wg = (wg & 7) * per + (wg >> 3);
-    }
-    // Indexing the two parameter blocks with a run-time value turns every later read of a parameter
-    // into a small dependent load (measured: 1.8 us per launch); a single product reads its block
-    // directly, a pair selects word by word between two blocks that are both read with fixed offsets
-    const bool second = PAIR && wg >= batch.p[0].total_wg;
-    if (second) wg -= batch.p[0].total_wg;
-    const MfmaParams P = PAIR ? pick_params(second, batch.p[0], batch.p[1]) : batch.p[0];
     const int tiles = P.tiles_m * P.tiles_n;           // DUAL: tiles_m counts pairs of tile rows
     const int g = wg / (tiles * P.ksplit);
     int rem = wg - g * tiles * P.ksplit;
@@ -894,6 +890,50 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
     else if constexpr (DUAL) epilogue_from_lds<VA, TOut, true, EPI>(P, g, ctile + team * CT_ELEMS, m0, n0, tid, ctile + 2 * CT_ELEMS);
     else epilogue_from_lds<VA, TOut, false, EPI>(P, g, ctile, m0, n0, (int)threadIdx.x, ctile + 2 * CT_ELEMS);
     PH_PHASE(5);
+}
+
+template <int KA, int KB, int VA, int VB, typename TOut, bool ATOMIC, bool PAIR, bool DUAL, int EPI>
+__global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
+{
+    int wg = xcd_order(blockIdx.x, 0, batch.total_wg);
+    // Indexing the two parameter blocks with a run-time value turns every later read of a parameter
+    // into a small dependent load (measured: 1.8 us per launch); a single product reads its block
+    // directly, a pair selects word by word between two blocks that are both read with fixed offsets
+    const bool second = PAIR && wg >= batch.p[0].total_wg;
+    if (second) wg -= batch.p[0].total_wg;
+    const MfmaParams P = PAIR ? pick_params(second, batch.p[0], batch.p[1]) : batch.p[0];
+    mfma_workgroup<KA, KB, VA, VB, TOut, ATOMIC, DUAL, EPI>(P, wg);
+}
+
+// The end of one layer's backward pass and the start of the next one's in one launch (all ranks on the
+// device): the error compression of the layer below, which fills half of the device for a short while, and
+// the weight + compressor gradients of this layer, which need nothing that the first produces.  Three
+// products of two operand layouts and output types: `head` (input-gradient layout, storage type out) runs
+// in the workgroups [0, head_wg) so that it is dispatched first and frees its compute units early,
+// tail[0], tail[1] (weight-gradient layout, float out; tail[1] may be empty: total_wg = 0) follow from
+// tail_first, a multiple of 8.
+struct MfmaTrio {
+    MfmaParams head;
+    MfmaParams tail[2];
+    int head_wg;         // = head.total_wg
+    int tail_first;      // head_wg rounded up to a multiple of 8; the workgroups in between do nothing
+    int total_wg;
+};
+
+template <int VEC>
+__global__ __launch_bounds__(512, 1) void gemm_mfma_trio_kernel(MfmaTrio trio)
+{
+    const int id = blockIdx.x;
+    if (id < trio.tail_first) {                        // uniform
+        if (id >= trio.head_wg) return;
+        mfma_workgroup<LD_KC, LD_KM, VEC, VEC, __bf16, false, false, EPI_STORE>(trio.head, xcd_order(id, 0, trio.head_wg));
+    } else {
+        int wg = xcd_order(id, trio.tail_first, trio.total_wg - trio.tail_first);
+        const bool second = wg >= trio.tail[0].total_wg;
+        if (second) wg -= trio.tail[0].total_wg;
+        const MfmaParams P = pick_params(second, trio.tail[0], trio.tail[1]);
+        mfma_workgroup<LD_KM, LD_KM, VEC, VEC, float, false, false, EPI_STORE>(P, wg);
+    }
 }
 
 }  // namespace phantom

@@ -365,6 +365,45 @@ ph_status launch_mfma(const GemmPlan &plan, const Product *prods, int count, int
     return fail(PH_ERR_UNSUPPORTED, "%s: operand layout, output type and epilogue are not built together", what);
 }
 
+// One launch for the error compression of one layer (head) and the weight + compressor gradients of the layer
+// above it (tail): see MfmaTrio.
+template <int VEC>
+ph_status launch_trio_kernel(const MfmaTrio &trio, hipStream_t st, const char *what)
+{
+    auto kern = gemm_mfma_trio_kernel<VEC>;
+    static thread_local bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, MFMA_LDS_BYTES);
+        if (e != hipSuccess) return fail(PH_ERR_LAUNCH, "%s: cannot reserve %d bytes of LDS: %s", what, MFMA_LDS_BYTES,
+                                         hipGetErrorString(e));
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)trio.total_wg), dim3(MFMA_THREADS), MFMA_LDS_BYTES, st, trio);
+    return check_launch(what);
+}
+
+ph_status launch_trio(const Product &head, const Product &tail0, const Product &tail1, int groups, int vec, hipStream_t st,
+                      const char *what)
+{
+    MfmaTrio trio{};
+    trio.head = mfma_params(head, groups, 1, false);
+    trio.tail[0] = mfma_params(tail0, groups, 1, false);
+    int tail_wg = trio.tail[0].total_wg;
+    if (tail1.M > 0 && tail1.N > 0) {
+        trio.tail[1] = mfma_params(tail1, groups, 1, false);
+        tail_wg += trio.tail[1].total_wg;
+    }
+    trio.head_wg = trio.head.total_wg;
+    trio.tail_first = (trio.head_wg + 7) & ~7;
+    trio.total_wg = trio.tail_first + tail_wg;
+    ProfScope prof(what, tail0.M, tail0.N, tail0.K, groups, st, head.M, head.N, head.K);
+    switch (vec) {
+    case 8: return launch_trio_kernel<8>(trio, st, what);
+    case 4: return launch_trio_kernel<4>(trio, st, what);
+    default: return launch_trio_kernel<2>(trio, st, what);
+    }
+}
+
 // Runs one product, or two independent ones of the same kind (names: `what` for the pair on the
 // matrix cores, `what` / `what2` when they run as separate launches of the shape-agnostic kernel).
 template <typename TIn, typename TOut>
@@ -543,6 +582,9 @@ struct BwdArgs {
                                //   of what it stores, i.e. the layer below's bias gradient (Eq. (bpb))
     bool dbias_ready;          // step only: dbias already holds the column sums of delta
     bool dbias_zeroed;         // step only: dbias is zero on entry
+    bool send_done;            // step only: this layer's error compression was launched by the layer above (below)
+    const void *below_Dw;      // step only, all ranks: D of the layer below; its error compression (dX -> dG_send)
+    bool *below_done;          //   may then ride with this layer's weight gradients; *below_done says whether it did
     LossTail *loss_tail;       // step only, last layer: the first memory-bound kernel of this backward finishes
                                //   the loss as a rider and clears loss_tail->partial; left alone if there is none
 };
@@ -594,16 +636,20 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
     }
 
     // error compression: dG_send[i] = delta . D_i   ([B, s] x [s, k] for every peer, one product over N = q*k)
-    Product send{};
-    send.a = view_plain(delta, s, B * s);
-    send.b.p0 = nullptr; send.b.p1 = const_cast<void *>(b.Dw); send.b.g0 = 0; send.b.g1 = q * s * k;
-    send.b.r = axis_seg(0, (int)k, 0, 1, s * k); send.b.c = axis_plain(0, k);
-    send.b.skip0 = NO_SKIP; send.b.skip_g = 0;
-    send.o.p0 = nullptr; send.o.p1 = b.dG_send; send.o.g0 = 0; send.o.g1 = q * B * k;
-    send.o.r = axis_plain(0, k); send.o.c = axis_seg(0, (int)k, 0, 1, B * k);
-    send.o.skip0 = NO_SKIP; send.o.skip_g = 0;
-    send.ep = epi_store();
-    send.M = q > 0 ? B : 0; send.N = q * k; send.K = s;
+    auto error_compression = [&](const void *dl, const void *Dw) {
+        Product send{};
+        send.a = view_plain(dl, s, B * s);
+        send.b.p0 = nullptr; send.b.p1 = const_cast<void *>(Dw); send.b.g0 = 0; send.b.g1 = q * s * k;
+        send.b.r = axis_seg(0, (int)k, 0, 1, s * k); send.b.c = axis_plain(0, k);
+        send.b.skip0 = NO_SKIP; send.b.skip_g = 0;
+        send.o.p0 = nullptr; send.o.p1 = b.dG_send; send.o.g0 = 0; send.o.g1 = q * B * k;
+        send.o.r = axis_plain(0, k); send.o.c = axis_seg(0, (int)k, 0, 1, B * k);
+        send.o.skip0 = NO_SKIP; send.o.skip_g = 0;
+        send.ep = epi_store();
+        send.M = q > 0 ? B : 0; send.N = q * k; send.K = s;
+        return send;
+    };
+    const Product send = error_compression(delta, b.Dw);
 
     // dX = delta . L + dg_own . C: reduction index = [delta | dg_own] against [L ; C]
     Product dx{};
@@ -623,7 +669,7 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
     const GemmPlan plan_x{LD_KC, LD_KM, g.vec, false};
     if (g.all) {
         // the input gradient needs dg_own, which is the sum of what all ranks send: three launches
-        PH_TRY((launch_products<T, T>(plan_x, &send, 1, g.groups, st, "error compression")));
+        if (!b.send_done) PH_TRY((launch_products<T, T>(plan_x, &send, 1, g.groups, st, "error compression")));
         if (q > 0) {
             const int64_t per_slot = B * k;
             constexpr int RS_VEC = 16 / (int)sizeof(T);
@@ -660,6 +706,23 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
     Product dc{view_plain_t(b.dg_own, k, B * k), view_plain_t(b.X, s, B * s), view_plain(b.dCw, s, k * s), epi_store(),
                q > 0 ? k : 0, s, B};
     Product grads[2] = {dw, dc};
+    if (b.below_done) *b.below_done = false;
+    if constexpr (std::is_same<T, bf16_t>::value) {
+        if (b.below_Dw && b.dX && g.all && q > 0 && g.vec > 0) {
+            // The layer below starts its backward with an error compression that fills half of the device or less
+            // for a short while: it shares this layer's last launch when it leaves at least half of the compute
+            // units to the weight gradients from the start (they take over the rest as it finishes).
+            const Product below = error_compression(b.dX, b.below_Dw);
+            const int64_t head_tiles = tiles_of(below.M, below.N) * g.groups;
+            const int64_t tail_tiles = (tiles_of(dw.M, dw.N) + tiles_of(dc.M, dc.N)) * g.groups;
+            static const char *force = getenv("PHANTOM_TRIO");
+            if (head_tiles <= 128 && tail_tiles <= 256 && !(force && force[0] == '0')) {
+                PH_TRY(launch_trio(below, dw, dc, g.groups, g.vec, st, "weight + compressor gradients | error compression below"));
+                if (b.below_done) *b.below_done = true;
+                return PH_OK;
+            }
+        }
+    }
     // a lone weight-gradient product with few tiles may split its reduction; a pair never does
     return launch_products<T, float>(GemmPlan{LD_KM, LD_KM, g.vec, true}, grads, q > 0 ? 2 : 1, g.groups, st,
                                      "weight + compressor gradients", "weight gradients", "compressor gradient");
@@ -780,8 +843,12 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
     }
 
     void *dY = w.dYa, *dX = w.dYb;    // delta of the current layer / of the layer below
+    bool send_done = false;           // the current layer's error compression went out with the layer above
     for (int l = L - 1; l >= 0; --l) {
         BwdArgs b{};
+        b.send_done = send_done;
+        b.below_Dw = (g.all && q > 0 && l > 0) ? a.Dw[l - 1] : nullptr;
+        b.below_done = &send_done;
         b.dbias_zeroed = true;
         b.loss_tail = &loss_tail;
         b.dbias_ready = fused_dbias && (l < L - 1 || mse_in_update);
