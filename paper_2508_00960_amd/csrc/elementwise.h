@@ -31,21 +31,29 @@ struct LossTail {
     float *loss;
 };
 
-__device__ __forceinline__ void finish_loss(const LossTail &t)
+// lred: 256 floats of LDS that nothing else uses meanwhile
+__device__ __forceinline__ void finish_loss(const LossTail &t, float *lred)
 {
-    __shared__ float lred[256];
-    float acc = 0.f;
-    for (int i = threadIdx.x; i < t.n; i += 256) acc += t.partial[i];
-    lred[threadIdx.x] = acc;
+    // 256 threads do the work; a larger workgroup's other threads only keep the barriers company
+    const int me = threadIdx.x;
+    if (me < 256) {
+        float acc = 0.f;
+        for (int i = me; i < t.n; i += 256) acc += t.partial[i];
+        lred[me] = acc;
+    }
     __syncthreads();
     for (int w = 128; w > 0; w >>= 1) {
-        if ((int)threadIdx.x < w) lred[threadIdx.x] += lred[threadIdx.x + w];
+        if (me < w) lred[me] += lred[me + w];
         __syncthreads();
     }
-    if (threadIdx.x == 0) *t.loss = lred[0] * t.scale;
+    if (me == 0) *t.loss = lred[0] * t.scale;
 }
 
-__global__ __launch_bounds__(256) void loss_kernel(LossTail t) { finish_loss(t); }
+__global__ __launch_bounds__(256) void loss_kernel(LossTail t)
+{
+    __shared__ float lred[256];
+    finish_loss(t, lred);
+}
 
 // Column sums of delta [rows x cols] (Eq. (bpb): dLoss/db = sum over the batch of delta).  One workgroup
 // owns CSUM_COLS columns of one group and rows [chunk*rows_per_chunk, ...): 16-byte loads, row lanes x
@@ -96,7 +104,8 @@ __global__ __launch_bounds__(256) void colsum_kernel(const T *__restrict__ delta
             else unsafeAtomicAdd(out + (int64_t)g * cols + c, sum);
         }
     }
-    if (tail.partial && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) finish_loss(tail);      // uniform
+    __shared__ float lred[256];
+    if (tail.partial && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0) finish_loss(tail, lred);      // uniform
 }
 
 // In-memory Reduce-Scatter of Algorithm 1's backward: dg_own[i] = sum_{j != i} dG_send[j][slot of i on j].
@@ -145,7 +154,8 @@ __global__ __launch_bounds__(256) void reduce_scatter_kernel(const T *__restrict
         for (int g = 0; g < RS_LANES; ++g) sum += part[g][c];
         dg_own[(int64_t)i * per_slot + at] = from_f32<T>(sum);
     }
-    if (tail.partial && blockIdx.x == 0 && blockIdx.y == 0) finish_loss(tail);      // uniform; rider, see LossTail
+    __shared__ float lred[256];
+    if (tail.partial && blockIdx.x == 0 && blockIdx.y == 0) finish_loss(tail, lred);      // uniform; rider, see LossTail
 }
 
 // MSE output error (Section IV-B, "Local error at the output", Eq. (deltaL)):
@@ -230,20 +240,14 @@ struct SgdBatch {
     LossTail tail;       // rider for workgroup (0,0), see LossTail
 };
 
+// one tensor's update by workgroup `job` of `jobs` (all of the workgroup's `threads` threads)
 template <typename T>
-__global__ __launch_bounds__(256) void sgd_kernel(SgdBatch batch, float lr)
+__device__ __forceinline__ void sgd_tensor(const SgdTensor &t, float lr, int job, int jobs, int threads)
 {
-    // fixed-index copies selected by value: indexing the argument block with blockIdx.y would make
-    // every access a dependent load
-    SgdTensor t = batch.t[0];
-    if (blockIdx.y == 1) t = batch.t[1];
-    if (blockIdx.y == 2) t = batch.t[2];
-    if (blockIdx.y == 3) t = batch.t[3];
-    if (batch.tail.partial && blockIdx.x == 0 && blockIdx.y == 0) finish_loss(batch.tail);      // uniform
     typedef float F4 __attribute__((ext_vector_type(4)));
     typedef T T4 __attribute__((ext_vector_type(4)));
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int64_t i = (int64_t)job * threads + threadIdx.x;
+    const int64_t stride = (int64_t)jobs * threads;
     if ((t.count & 3) == 0) {                          // uniform
         for (const int64_t quads = t.count >> 2; i < quads; i += stride) {
             const F4 gr = ((const F4 *)t.grad)[i];
@@ -272,6 +276,30 @@ __global__ __launch_bounds__(256) void sgd_kernel(SgdBatch batch, float lr)
             ((T *)t.w)[i] = from_f32<T>(m);
         }
     }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void sgd_kernel(SgdBatch batch, float lr)
+{
+    // fixed-index copies selected by value: indexing the argument block with blockIdx.y would make
+    // every access a dependent load
+    SgdTensor t = batch.t[0];
+    if (blockIdx.y == 1) t = batch.t[1];
+    if (blockIdx.y == 2) t = batch.t[2];
+    if (blockIdx.y == 3) t = batch.t[3];
+    __shared__ float lred[256];
+    if (batch.tail.partial && blockIdx.x == 0 && blockIdx.y == 0) finish_loss(batch.tail, lred);      // uniform
+    sgd_tensor<T>(t, lr, blockIdx.x, gridDim.x, 256);
+}
+
+// The same update as a few workgroups of another launch (workgroup `job` of `jobs`): every tensor in turn.
+template <typename T>
+__device__ __forceinline__ void sgd_rider(const SgdBatch &batch, float lr, int job, int jobs, int threads, float *lred)
+{
+    if (batch.tail.partial && job == 0) finish_loss(batch.tail, lred);      // uniform
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (batch.t[i].count > 0) sgd_tensor<T>(batch.t[i], lr, job, jobs, threads);
 }
 
 __global__ __launch_bounds__(256) void fill_zero_kernel(float *__restrict__ dst, int64_t count)

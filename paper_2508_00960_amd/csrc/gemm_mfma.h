@@ -29,6 +29,7 @@
 // of tiles: neighbouring tiles share operand panels in that XCD's L2.
 #pragma once
 #include "common.h"
+#include "elementwise.h"    // SgdBatch, sgd_rider
 #include "gemm_generic.h"   // Epilogue, EPI_*
 #include "views.h"
 
@@ -905,34 +906,43 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
     mfma_workgroup<KA, KB, VA, VB, TOut, ATOMIC, DUAL, EPI>(P, wg);
 }
 
-// The end of one layer's backward pass and the start of the next one's in one launch (all ranks on the
-// device): the error compression of the layer below, which fills half of the device for a short while, and
-// the weight + compressor gradients of this layer, which need nothing that the first produces.  Three
-// products of two operand layouts and output types: `head` (input-gradient layout, storage type out) runs
-// in the workgroups [0, head_wg) so that it is dispatched first and frees its compute units early,
-// tail[0], tail[1] (weight-gradient layout, float out; tail[1] may be empty: total_wg = 0) follow from
-// tail_first, a multiple of 8.
-struct MfmaTrio {
+// The last launch of a layer's backward pass, the weight + compressor gradients (tail[0], tail[1]: weight-gradient
+// layout, float out; tail[1] may be empty: total_wg = 0), with up to two riders that need nothing it produces:
+//  - head, all ranks on the device: the error compression of the layer below (input-gradient layout, storage
+//    type out), which fills half of the device or less for a short while.  It runs in the workgroups
+//    [0, head_wg) so that it is dispatched first and frees its compute units early.
+//  - the SGD update of the layer above (sgd_wg workgroups from sgd_first on) on compute units that the
+//    products leave idle; its gradients sit in other buffers than the ones tail[] writes.
+// tail_first and sgd_first are multiples of 8; workgroups in the gaps do nothing.
+struct MfmaTailBatch {
     MfmaParams head;
     MfmaParams tail[2];
-    int head_wg;         // = head.total_wg
-    int tail_first;      // head_wg rounded up to a multiple of 8; the workgroups in between do nothing
-    int total_wg;
+    SgdBatch sgd;
+    float lr;
+    int head_wg;         // = head.total_wg (0: no head)
+    int tail_first;
+    int tail_wg;         // = tail[0].total_wg + tail[1].total_wg
+    int sgd_first;
+    int sgd_wg;          // 0: no update
 };
 
 template <int VEC>
-__global__ __launch_bounds__(512, 1) void gemm_mfma_trio_kernel(MfmaTrio trio)
+__global__ __launch_bounds__(512, 1) void gemm_mfma_tail_kernel(MfmaTailBatch tb)
 {
     const int id = blockIdx.x;
-    if (id < trio.tail_first) {                        // uniform
-        if (id >= trio.head_wg) return;
-        mfma_workgroup<LD_KC, LD_KM, VEC, VEC, __bf16, false, false, EPI_STORE>(trio.head, xcd_order(id, 0, trio.head_wg));
-    } else {
-        int wg = xcd_order(id, trio.tail_first, trio.total_wg - trio.tail_first);
-        const bool second = wg >= trio.tail[0].total_wg;
-        if (second) wg -= trio.tail[0].total_wg;
-        const MfmaParams P = pick_params(second, trio.tail[0], trio.tail[1]);
+    if (id < tb.tail_first) {                          // uniform, like every branch here
+        if (id >= tb.head_wg) return;
+        mfma_workgroup<LD_KC, LD_KM, VEC, VEC, __bf16, false, false, EPI_STORE>(tb.head, xcd_order(id, 0, tb.head_wg));
+    } else if (id < tb.sgd_first) {
+        if (id >= tb.tail_first + tb.tail_wg) return;
+        int wg = xcd_order(id, tb.tail_first, tb.tail_wg);
+        const bool second = wg >= tb.tail[0].total_wg;
+        if (second) wg -= tb.tail[0].total_wg;
+        const MfmaParams P = pick_params(second, tb.tail[0], tb.tail[1]);
         mfma_workgroup<LD_KM, LD_KM, VEC, VEC, float, false, false, EPI_STORE>(P, wg);
+    } else {
+        extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+        sgd_rider<__bf16>(tb.sgd, tb.lr, id - tb.sgd_first, tb.sgd_wg, MFMA_THREADS, (float *)smem_raw);
     }
 }
 

@@ -177,7 +177,9 @@ BwdWs carve_bwd(Arena &a, const Geo &g)
 struct StepWs {
     std::vector<void *> Y, A, G;
     void *dYa, *dYb, *dG_send, *dg_own;
-    float *dLw, *dCw, *dDw, *dbias, *mse_partial;   // dbias: [layers][groups, s], one block
+    float *dLw[2], *dCw[2], *dDw[2];                // two sets, used by alternate layers: a layer's update may still read
+                                                    //   its gradients while the layer below writes its own
+    float *dbias, *mse_partial;                     // dbias: [layers][groups, s], one block
     BwdWs bwd;
 };
 
@@ -196,9 +198,11 @@ StepWs carve_step(Arena &a, const Geo &g)
     w.dYb = a.take(act_bytes);
     w.dG_send = g.q > 0 ? a.take((size_t)g.groups * g.q * g.B * g.k * g.esz) : nullptr;
     w.dg_own = g.q > 0 ? a.take(gath_bytes) : nullptr;
-    w.dLw = (float *)a.take((size_t)g.groups * g.s * g.s * 4);
-    w.dCw = (float *)a.take((size_t)g.groups * g.k * g.s * 4 + 16);
-    w.dDw = (float *)a.take((size_t)g.groups * g.q * g.s * g.k * 4 + 16);
+    for (int set = 0; set < 2; ++set) {
+        w.dLw[set] = (float *)a.take((size_t)g.groups * g.s * g.s * 4);
+        w.dCw[set] = (float *)a.take((size_t)g.groups * g.k * g.s * 4 + 16);
+        w.dDw[set] = (float *)a.take((size_t)g.groups * g.q * g.s * g.k * 4 + 16);
+    }
     w.dbias = (float *)a.take((size_t)g.layers * g.groups * g.s * 4);
     w.mse_partial = (float *)a.take(MSE_BLOCKS * sizeof(float));
     w.bwd = carve_bwd(a, g);
@@ -365,12 +369,13 @@ ph_status launch_mfma(const GemmPlan &plan, const Product *prods, int count, int
     return fail(PH_ERR_UNSUPPORTED, "%s: operand layout, output type and epilogue are not built together", what);
 }
 
-// One launch for the error compression of one layer (head) and the weight + compressor gradients of the layer
-// above it (tail): see MfmaTrio.
+// The weight + compressor gradients (tail0, tail1; tail1 may be empty) with their riders in one launch: the
+// error compression of the layer below (head, may be NULL) and the SGD update of the layer above (sgd, may be
+// NULL, on sgd_wg workgroups): see MfmaTailBatch.
 template <int VEC>
-ph_status launch_trio_kernel(const MfmaTrio &trio, hipStream_t st, const char *what)
+ph_status launch_tail_kernel(const MfmaTailBatch &tb, unsigned total_wg, hipStream_t st, const char *what)
 {
-    auto kern = gemm_mfma_trio_kernel<VEC>;
+    auto kern = gemm_mfma_tail_kernel<VEC>;
     static thread_local bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, MFMA_LDS_BYTES);
@@ -378,29 +383,32 @@ ph_status launch_trio_kernel(const MfmaTrio &trio, hipStream_t st, const char *w
                                          hipGetErrorString(e));
         configured = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)trio.total_wg), dim3(MFMA_THREADS), MFMA_LDS_BYTES, st, trio);
+    hipLaunchKernelGGL(kern, dim3(total_wg), dim3(MFMA_THREADS), MFMA_LDS_BYTES, st, tb);
     return check_launch(what);
 }
 
-ph_status launch_trio(const Product &head, const Product &tail0, const Product &tail1, int groups, int vec, hipStream_t st,
-                      const char *what)
+ph_status launch_tail(const Product *head, const Product &tail0, const Product &tail1, const SgdBatch *sgd, float lr,
+                      int sgd_wg, int groups, int vec, hipStream_t st, const char *what)
 {
-    MfmaTrio trio{};
-    trio.head = mfma_params(head, groups, 1, false);
-    trio.tail[0] = mfma_params(tail0, groups, 1, false);
-    int tail_wg = trio.tail[0].total_wg;
+    MfmaTailBatch tb{};
+    if (head) tb.head = mfma_params(*head, groups, 1, false);
+    tb.head_wg = head ? tb.head.total_wg : 0;
+    tb.tail_first = (tb.head_wg + 7) & ~7;
+    tb.tail[0] = mfma_params(tail0, groups, 1, false);
+    tb.tail_wg = tb.tail[0].total_wg;
     if (tail1.M > 0 && tail1.N > 0) {
-        trio.tail[1] = mfma_params(tail1, groups, 1, false);
-        tail_wg += trio.tail[1].total_wg;
+        tb.tail[1] = mfma_params(tail1, groups, 1, false);
+        tb.tail_wg += tb.tail[1].total_wg;
     }
-    trio.head_wg = trio.head.total_wg;
-    trio.tail_first = (trio.head_wg + 7) & ~7;
-    trio.total_wg = trio.tail_first + tail_wg;
-    ProfScope prof(what, tail0.M, tail0.N, tail0.K, groups, st, head.M, head.N, head.K);
+    tb.sgd_first = (tb.tail_first + tb.tail_wg + 7) & ~7;
+    tb.sgd_wg = sgd ? sgd_wg : 0;
+    if (sgd) { tb.sgd = *sgd; tb.lr = lr; }
+    ProfScope prof(what, tail0.M, tail0.N, tail0.K, groups, st, head ? head->M : 0, head ? head->N : 0, head ? head->K : 0);
+    const unsigned total = (unsigned)(tb.sgd_first + tb.sgd_wg);
     switch (vec) {
-    case 8: return launch_trio_kernel<8>(trio, st, what);
-    case 4: return launch_trio_kernel<4>(trio, st, what);
-    default: return launch_trio_kernel<2>(trio, st, what);
+    case 8: return launch_tail_kernel<8>(tb, total, st, what);
+    case 4: return launch_tail_kernel<4>(tb, total, st, what);
+    default: return launch_tail_kernel<2>(tb, total, st, what);
     }
 }
 
@@ -585,6 +593,9 @@ struct BwdArgs {
     bool send_done;            // step only: this layer's error compression was launched by the layer above (below)
     const void *below_Dw;      // step only, all ranks: D of the layer below; its error compression (dX -> dG_send)
     bool *below_done;          //   may then ride with this layer's weight gradients; *below_done says whether it did
+    const SgdBatch *ride_sgd;  // step only: the update of the layer above, not launched yet; it may ride with this
+    float ride_lr;             //   layer's weight gradients on compute units they leave idle; *ride_sgd_done says
+    bool *ride_sgd_done;       //   whether it did
     LossTail *loss_tail;       // step only, last layer: the first memory-bound kernel of this backward finishes
                                //   the loss as a rider and clears loss_tail->partial; left alone if there is none
 };
@@ -707,18 +718,36 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
                q > 0 ? k : 0, s, B};
     Product grads[2] = {dw, dc};
     if (b.below_done) *b.below_done = false;
+    if (b.ride_sgd_done) *b.ride_sgd_done = false;
     if constexpr (std::is_same<T, bf16_t>::value) {
-        if (b.below_Dw && b.dX && g.all && q > 0 && g.vec > 0) {
-            // The layer below starts its backward with an error compression that fills half of the device or less
-            // for a short while: it shares this layer's last launch when it leaves at least half of the compute
-            // units to the weight gradients from the start (they take over the rest as it finishes).
-            const Product below = error_compression(b.dX, b.below_Dw);
-            const int64_t head_tiles = tiles_of(below.M, below.N) * g.groups;
-            const int64_t tail_tiles = (tiles_of(dw.M, dw.N) + tiles_of(dc.M, dc.N)) * g.groups;
-            static const char *force = getenv("PHANTOM_TRIO");
-            if (head_tiles <= 128 && tail_tiles <= 256 && !(force && force[0] == '0')) {
-                PH_TRY(launch_trio(below, dw, dc, g.groups, g.vec, st, "weight + compressor gradients | error compression below"));
-                if (b.below_done) *b.below_done = true;
+        const int64_t tail_tiles = (tiles_of(dw.M, dw.N) + tiles_of(dc.M, dc.N)) * g.groups;
+        if (g.vec > 0 && tail_tiles <= 256) {
+            // Riders of the weight-gradient launch (MfmaTailBatch).  The layer below starts its backward with an
+            // error compression that fills half of the device or less for a short while: it comes along when it
+            // leaves at least half of the compute units to the weight gradients from the start (they take over
+            // the rest as it finishes).  The update of the layer above comes along when at least a quarter of the
+            // compute units would otherwise be idle.  PHANTOM_TAIL=0 switches both off (for measurements).
+            static const char *force = getenv("PHANTOM_TAIL");
+            const bool allowed = !(force && force[0] == '0');
+            Product below{};
+            bool with_head = false;
+            int64_t used = tail_tiles;
+            if (allowed && b.below_Dw && b.dX && g.all && q > 0) {
+                below = error_compression(b.dX, b.below_Dw);
+                const int64_t head_tiles = tiles_of(below.M, below.N) * g.groups;
+                with_head = head_tiles <= 128;
+                if (with_head) used += (head_tiles + 7) & ~(int64_t)7;
+            }
+            const int64_t idle = 256 - ((used + 7) & ~(int64_t)7);
+            const bool with_sgd = allowed && b.ride_sgd && idle >= 64;
+            if (with_head || with_sgd) {
+                PH_TRY(launch_tail(with_head ? &below : nullptr, dw, dc, with_sgd ? b.ride_sgd : nullptr, b.ride_lr, (int)idle,
+                                   g.groups, g.vec, st,
+                                   with_head ? (with_sgd ? "weight + compressor gradients | error compression below | SGD above"
+                                                         : "weight + compressor gradients | error compression below")
+                                             : "weight + compressor gradients | SGD above"));
+                if (b.below_done) *b.below_done = with_head;
+                if (b.ride_sgd_done) *b.ride_sgd_done = with_sgd;
                 return PH_OK;
             }
         }
@@ -844,6 +873,14 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
 
     void *dY = w.dYa, *dX = w.dYb;    // delta of the current layer / of the layer below
     bool send_done = false;           // the current layer's error compression went out with the layer above
+    SgdBatch pending{};               // the update of the layer above, if it has not been launched yet
+    int64_t pending_elems = 0, pending_largest = 0;
+    bool have_pending = false;
+    auto launch_sgd = [&](const SgdBatch &batch, int tensors, int64_t largest, int64_t total) -> ph_status {
+        ProfScope prof("SGD update", 0, total, 0, 1, st);
+        hipLaunchKernelGGL((sgd_kernel<T>), dim3(blocks_for(largest, 256, 2048), (unsigned)tensors), dim3(256), 0, st, batch, a.lr);
+        return check_launch("SGD update");
+    };
     for (int l = L - 1; l >= 0; --l) {
         BwdArgs b{};
         b.send_done = send_done;
@@ -861,12 +898,18 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
         b.G = q ? (g.all ? w.G[l] : a.G[l]) : nullptr;
         b.dg_own = q ? (g.all ? w.dg_own : const_cast<void *>(a.dg_own[l])) : nullptr;
         b.dX = l > 0 ? dX : nullptr;
-        b.dLw = a.dLw ? a.dLw[l] : w.dLw;
-        b.dCw = q ? (a.dCw ? a.dCw[l] : w.dCw) : nullptr;
-        b.dDw = q ? (a.dDw ? a.dDw[l] : w.dDw) : nullptr;
+        b.dLw = a.dLw ? a.dLw[l] : w.dLw[l & 1];
+        b.dCw = q ? (a.dCw ? a.dCw[l] : w.dCw[l & 1]) : nullptr;
+        b.dDw = q ? (a.dDw ? a.dDw[l] : w.dDw[l & 1]) : nullptr;
         b.dbias = dbias_of(l);
         b.dG_send = w.dG_send;
+        bool sgd_rode = false;
+        b.ride_sgd = have_pending ? &pending : nullptr;
+        b.ride_lr = a.lr;
+        b.ride_sgd_done = &sgd_rode;
         PH_TRY(bwd_impl<T>(g, b, w.bwd, st));
+        if (have_pending && !sgd_rode) PH_TRY(launch_sgd(pending, 4, pending_largest, pending_elems));
+        have_pending = false;
 
         if (a.mode == PH_STEP_NO_UPDATE) {
             if (loss_tail.partial) {                   // no kernel of this layer's backward could carry the rider
@@ -898,9 +941,16 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
         if (tensors > 0) {
             batch.tail = loss_tail;                    // still set: no kernel of this layer's backward carried the rider
             loss_tail.partial = nullptr;
-            ProfScope prof("SGD update", 0, total, 0, 1, st);
-            hipLaunchKernelGGL((sgd_kernel<T>), dim3(blocks_for(largest, 256, 2048), (unsigned)tensors), dim3(256), 0, st, batch, a.lr);
-            PH_TRY(check_launch("SGD update"));
+            // The update may wait for the weight-gradient launch of the layer below and use the compute units
+            // that launch leaves idle (bwd_impl decides); the first layer's has nothing to wait for.
+            if (std::is_same<T, bf16_t>::value && g.vec > 0 && l > 0) {
+                pending = batch;
+                pending_elems = total;
+                pending_largest = largest;
+                have_pending = true;
+            } else {
+                PH_TRY(launch_sgd(batch, tensors, largest, total));
+            }
         }
         void *t = dY; dY = dX; dX = t;
     }
