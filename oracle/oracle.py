@@ -123,16 +123,17 @@ def compress(X, Cw):
 
 def layer_update(act, X, Lw, Dw, bias, G):
     """A = b + L y + sum_i D^(i,j) g^(i), Y = sigma(A) on one rank (Eq. (ylq))."""
-    B, s = X.shape
+    B, si = X.shape              # si inputs and so outputs of the layer on this rank (equal in the paper's text)
+    so = Lw.shape[0]
     q = 0 if Dw is None else Dw.shape[0]
     k = Dw.shape[2] if q else 0
     X_, pX = _c(X); Lw_, pL = _c(Lw); b_, pb = _c(bias)
     Dw_, pD = _c(Dw if q else None); G_, pG = _c(G if q else None)
     if q:
-        assert G_.shape == (q, B, k) and Dw_.shape == (q, s, k)
-    assert Lw_.shape == (s, s) and b_.shape == (s,)
-    A = np.empty((B, s)); Y = np.empty((B, s))
-    lib().pho_layer_update(_i(B), _i(s), _i(k), _i(q), ctypes.c_int(ACTS[act]),
+        assert G_.shape == (q, B, k) and Dw_.shape == (q, so, k)
+    assert Lw_.shape == (so, si) and b_.shape == (so,)
+    A = np.empty((B, so)); Y = np.empty((B, so))
+    lib().pho_layer_update(_i(B), _i(si), _i(so), _i(k), _i(q), ctypes.c_int(ACTS[act]),
                            pX, pL, pD, pb, pG, _vp(A), _vp(Y))
     return A, Y
 
@@ -168,16 +169,18 @@ def error_compress(Dw, delta):
 
 def layer_grads(delta, X, Lw, Cw, G, dg_own, need_dX=True):
     """dX (braces of Eq. (backprop)) and Eq. (bpb)-(bpD) once dg_own is known."""
-    B, s = X.shape
+    B, si = X.shape
+    so = Lw.shape[0]
     q = 0 if G is None else G.shape[0]
     k = Cw.shape[0] if q > 0 else 0
     d_, pd = _c(delta); X_, pX = _c(X); Lw_, pL = _c(Lw)
     Cw_, pC = _c(Cw if q else None); G_, pG = _c(G if q else None); h_, ph = _c(dg_own if q else None)
+    assert d_.shape == (B, so) and Lw_.shape == (so, si)
     if q:
-        assert G_.shape == (q, B, k) and h_.shape == (B, k) and Cw_.shape == (k, s)
-    dX = np.empty((B, s)) if need_dX else None
-    dLw = np.empty((s, s)); dCw = np.empty((k, s)); dDw = np.empty((q, s, k)); db = np.empty((s,))
-    lib().pho_layer_grads(_i(B), _i(s), _i(k), _i(q), pd, pX, pL, pC, pG, ph,
+        assert G_.shape == (q, B, k) and h_.shape == (B, k) and Cw_.shape == (k, si)
+    dX = np.empty((B, si)) if need_dX else None
+    dLw = np.empty((so, si)); dCw = np.empty((k, si)); dDw = np.empty((q, so, k)); db = np.empty((so,))
+    lib().pho_layer_grads(_i(B), _i(si), _i(so), _i(k), _i(q), pd, pX, pL, pC, pG, ph,
                           _vp(dX), _vp(dLw), _vp(dCw), _vp(dDw), _vp(db))
     return {"dX": dX, "dLw": dLw, "dCw": dCw if q else None, "dDw": dDw if q else None, "dbias": db}
 
@@ -207,8 +210,9 @@ def all_ranks_fwd(act, X, P, storage="f32"):
     Returns A, Y [p,B,s] and the gathered phantom layers G_full [p,B,k]
     (rank j reads every slot but its own).
     """
-    p, B, s = X.shape
-    A = np.empty((p, B, s)); Y = np.empty((p, B, s))
+    p, B, _ = X.shape
+    so = P["Lw"].shape[1]
+    A = np.empty((p, B, so)); Y = np.empty((p, B, so))
     if p == 1:
         A[0], Y[0] = layer_update(act, X[0], P["Lw"][0], None, P["bias"][0], None)
         return {"A": A, "Y": Y, "G_full": None}

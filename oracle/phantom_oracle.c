@@ -7,6 +7,13 @@
  * for ONE rank j and ONE layer.  Several ranks, several layers, the loss and
  * the update are put together from these calls by oracle/oracle.py.
  *
+ * Layer widths may differ (Section IV, first paragraph: widths n_l and phantom widths k_l per layer; the
+ * equations are then written for one width to keep them short).  Reading taken here: layer l maps
+ * n_{l-1} to n_l, rank j holds si = n_{l-1}/p inputs and so = n_l/p outputs of it, so L is [so, si], C is
+ * [k, si] (it compresses the layer's input), D^(i,j) is [so, k], b is [so].  Below, "s" in a shape
+ * stands for so where the tensor lives on the output side (A, Y, dY, delta, bias, rows of L and D) and
+ * for si on the input side (X, dX, columns of L and C).
+ *
  * Conventions (row-major, batch-major):
  *   X   [B, s]      y_{l-1}^(j)                 Lw  [s, s]      L_l^(j)
  *   Cw  [k, s]      C_l^(j)                     Dw  [q, s, k]   D_l^(i,j) for the q = p-1 peers i != j,
@@ -123,40 +130,40 @@ void pho_compress(int64_t B, int64_t s, int64_t k,
 
 /* (2) local update, decompression, remote update, bias and activation:
  *     A = b + L y + sum_{i != j} D^(i,j) g^(i),  Y = sigma(A).   q = 0 means p = 1: Dw, G unused. */
-void pho_layer_update(int64_t B, int64_t s, int64_t k, int64_t q, int act,
+void pho_layer_update(int64_t B, int64_t si, int64_t so, int64_t k, int64_t q, int act,
                       const double *X, const double *Lw, const double *Dw,
                       const double *bias, const double *G,
                       double *A, double *Y)
 {
 #pragma omp parallel for schedule(static)
     for (int64_t b = 0; b < B; ++b) {
-        const double *x = X + b * s;
-        for (int64_t o = 0; o < s; ++o) {
+        const double *x = X + b * si;
+        for (int64_t o = 0; o < so; ++o) {
             double z = 0.0;
             /* local update L^(j) y^(j) */
-            for (int64_t m = 0; m < s; ++m) z += Lw[o * s + m] * x[m];
+            for (int64_t m = 0; m < si; ++m) z += Lw[o * si + m] * x[m];
             /* decompression and remote update: sum_i D^(i,j) g^(i) */
             for (int64_t i = 0; i < q; ++i) {
-                const double *d = Dw + (i * s + o) * k;
+                const double *d = Dw + (i * so + o) * k;
                 const double *g = G + (i * B + b) * k;
                 double t = 0.0;
                 for (int64_t c = 0; c < k; ++c) t += d[c] * g[c];
                 z += t;
             }
             double a = bias[o] + z;
-            A[b * s + o] = a;
-            Y[b * s + o] = act_f(act, a);
+            A[b * so + o] = a;
+            Y[b * so + o] = act_f(act, a);
         }
     }
 }
 
-void pho_layer_fwd(int64_t B, int64_t s, int64_t k, int64_t q, int act,
+void pho_layer_fwd(int64_t B, int64_t si, int64_t so, int64_t k, int64_t q, int act,
                    const double *X, const double *Lw, const double *Cw, const double *Dw,
                    const double *bias, const double *G,
                    double *A, double *Y, double *g_own)
 {
-    if (q > 0) pho_compress(B, s, k, X, Cw, g_own);
-    pho_layer_update(B, s, k, q, act, X, Lw, Dw, bias, G, A, Y);
+    if (q > 0) pho_compress(B, si, k, X, Cw, g_own);
+    pho_layer_update(B, si, so, k, q, act, X, Lw, Dw, bias, G, A, Y);
 }
 
 /* Backward of one layer on one rank, in the three pieces the method has
@@ -206,7 +213,7 @@ void pho_error_compress(int64_t B, int64_t s, int64_t k, int64_t q,
  *     dCw     = sum_b dg_own x^T                              Eq. (bpC), its sum over ranks already in dg_own
  *     dX may be NULL.  q = 0: Cw, G, dg_own, dCw, dDw unused.
  */
-void pho_layer_grads(int64_t B, int64_t s, int64_t k, int64_t q,
+void pho_layer_grads(int64_t B, int64_t si, int64_t so, int64_t k, int64_t q,
                      const double *delta, const double *X,
                      const double *Lw, const double *Cw,
                      const double *G, const double *dg_own,
@@ -215,35 +222,35 @@ void pho_layer_grads(int64_t B, int64_t s, int64_t k, int64_t q,
     if (dX) {
 #pragma omp parallel for schedule(static)
         for (int64_t b = 0; b < B; ++b) {
-            const double *dl = delta + b * s;
-            double *dx = dX + b * s;
-            for (int64_t m = 0; m < s; ++m) dx[m] = 0.0;
-            for (int64_t o = 0; o < s; ++o) {
+            const double *dl = delta + b * so;
+            double *dx = dX + b * si;
+            for (int64_t m = 0; m < si; ++m) dx[m] = 0.0;
+            for (int64_t o = 0; o < so; ++o) {
                 double d = dl[o];
-                for (int64_t m = 0; m < s; ++m) dx[m] += Lw[o * s + m] * d;
+                for (int64_t m = 0; m < si; ++m) dx[m] += Lw[o * si + m] * d;
             }
             for (int64_t c = 0; c < (q > 0 ? k : 0); ++c) {
                 double h = dg_own[b * k + c];
-                for (int64_t m = 0; m < s; ++m) dx[m] += Cw[c * s + m] * h;
+                for (int64_t m = 0; m < si; ++m) dx[m] += Cw[c * si + m] * h;
             }
         }
     }
 
 #pragma omp parallel for schedule(static)
-    for (int64_t o = 0; o < s; ++o) {
+    for (int64_t o = 0; o < so; ++o) {
         double sb = 0.0;
-        double *gl = dLw + o * s;
-        for (int64_t m = 0; m < s; ++m) gl[m] = 0.0;
+        double *gl = dLw + o * si;
+        for (int64_t m = 0; m < si; ++m) gl[m] = 0.0;
         for (int64_t i = 0; i < q; ++i)
-            for (int64_t c = 0; c < k; ++c) dDw[(i * s + o) * k + c] = 0.0;
+            for (int64_t c = 0; c < k; ++c) dDw[(i * so + o) * k + c] = 0.0;
         for (int64_t b = 0; b < B; ++b) {
-            double d = delta[b * s + o];
+            double d = delta[b * so + o];
             sb += d;
-            const double *x = X + b * s;
-            for (int64_t m = 0; m < s; ++m) gl[m] += d * x[m];
+            const double *x = X + b * si;
+            for (int64_t m = 0; m < si; ++m) gl[m] += d * x[m];
             for (int64_t i = 0; i < q; ++i) {
                 const double *g = G + (i * B + b) * k;
-                double *gd = dDw + (i * s + o) * k;
+                double *gd = dDw + (i * so + o) * k;
                 for (int64_t c = 0; c < k; ++c) gd[c] += d * g[c];
             }
         }
@@ -253,25 +260,25 @@ void pho_layer_grads(int64_t B, int64_t s, int64_t k, int64_t q,
     if (q > 0) {
 #pragma omp parallel for schedule(static)
         for (int64_t c = 0; c < k; ++c) {
-            double *gc = dCw + c * s;
-            for (int64_t m = 0; m < s; ++m) gc[m] = 0.0;
+            double *gc = dCw + c * si;
+            for (int64_t m = 0; m < si; ++m) gc[m] = 0.0;
             for (int64_t b = 0; b < B; ++b) {
                 double h = dg_own[b * k + c];
-                const double *x = X + b * s;
-                for (int64_t m = 0; m < s; ++m) gc[m] += h * x[m];
+                const double *x = X + b * si;
+                for (int64_t m = 0; m < si; ++m) gc[m] += h * x[m];
             }
         }
     }
 }
 
-void pho_layer_bwd(int64_t B, int64_t s, int64_t k, int64_t q, int act, int round_operands,
+void pho_layer_bwd(int64_t B, int64_t si, int64_t so, int64_t k, int64_t q, int act, int round_operands,
                    const double *dY, const double *X, const double *A,
                    const double *Lw, const double *Cw, const double *Dw,
                    const double *G, const double *dg_own,
                    double *delta, double *dX, double *dLw, double *dCw, double *dDw,
                    double *dbias, double *dG_send)
 {
-    pho_delta(B, s, act, round_operands, dY, A, delta);
-    if (q > 0) pho_error_compress(B, s, k, q, Dw, delta, dG_send);
-    pho_layer_grads(B, s, k, q, delta, X, Lw, Cw, G, dg_own, dX, dLw, dCw, dDw, dbias);
+    pho_delta(B, so, act, round_operands, dY, A, delta);
+    if (q > 0) pho_error_compress(B, so, k, q, Dw, delta, dG_send);
+    pho_layer_grads(B, si, so, k, q, delta, X, Lw, Cw, G, dg_own, dX, dLw, dCw, dDw, dbias);
 }

@@ -13,8 +13,9 @@ values do not depend on the order in which tensors are requested.
 Distributions follow the workload recipe of the paper's experiments as far as
 it is stated (Section VI, "Data and Hardware": synthetic Gaussian data) and the
 default initialisation of a linear layer for the weights: U(-1/sqrt(fan_in),
-+1/sqrt(fan_in)) with fan_in = n/p for the local matrix, the compressor and the
-bias, and fan_in = k for the decompressors (shapes from Section IV-A).
++1/sqrt(fan_in)) with fan_in = n/p (the layer's input shard) for the local matrix,
+the compressor and the bias, and fan_in = k for the decompressors (shapes from
+Section IV-A).
 """
 from __future__ import annotations
 
@@ -110,6 +111,10 @@ class Problem:
 
     rank >= 0: one rank's share, peers' buffers are seeded inputs.
     rank == -1: all p ranks held together; every tensor gains a leading [p] axis.
+
+    widths, ks (optional): layer widths n_0 .. n_L (n_0 the network input, n_l the output of layer l)
+    and phantom widths k_1 .. k_L, for a network whose layers differ (Section IV, first paragraph);
+    empty = every width is n, every phantom width k.
     """
     n: int
     p: int
@@ -119,6 +124,13 @@ class Problem:
     act: str = "relu"          # 'identity' | 'relu' | 'gelu'
     dtype: str = "f32"         # 'f32' | 'bf16' (bf16 storage, fp32 accumulate)
     rank: int = 0
+    widths: tuple = ()
+    ks: tuple = ()
+
+    def __post_init__(self):
+        if self.widths:
+            assert len(self.widths) == self.layers + 1 and len(self.ks) == self.layers
+            assert all(w % self.p == 0 for w in self.widths)
 
     @property
     def s(self) -> int:
@@ -132,16 +144,26 @@ class Problem:
     def kc(self) -> int:
         return self.s + self.peers * self.k
 
+    def s_in(self, layer: int) -> int:
+        """Inputs of layer `layer` (0-based) held by one rank."""
+        return (self.widths[layer] if self.widths else self.n) // self.p
+
+    def s_out(self, layer: int) -> int:
+        return (self.widths[layer + 1] if self.widths else self.n) // self.p
+
+    def k_of(self, layer: int) -> int:
+        return self.ks[layer] if self.ks else self.k
+
 
 def layer_params(prob: Problem, layer: int, rank: int, seed: int) -> dict:
     """Weights of one rank for one layer, rounded to the storage type."""
-    s, k, q = prob.s, prob.k, prob.peers
-    bs, bk = 1.0 / math.sqrt(s), 1.0 / math.sqrt(max(k, 1))
+    si, so, k, q = prob.s_in(layer), prob.s_out(layer), prob.k_of(layer), prob.peers
+    bs, bk = 1.0 / math.sqrt(si), 1.0 / math.sqrt(max(k, 1))
     out = {
-        "Lw": uniform((s, s), -bs, bs, seed=seed, tensor="Lw", layer=layer, rank=rank),
-        "bias": uniform((s,), -bs, bs, seed=seed, tensor="bias", layer=layer, rank=rank),
-        "Cw": uniform((k, s), -bs, bs, seed=seed, tensor="Cw", layer=layer, rank=rank),
-        "Dw": uniform((q, s, k), -bk, bk, seed=seed, tensor="Dw", layer=layer, rank=rank),
+        "Lw": uniform((so, si), -bs, bs, seed=seed, tensor="Lw", layer=layer, rank=rank),
+        "bias": uniform((so,), -bs, bs, seed=seed, tensor="bias", layer=layer, rank=rank),
+        "Cw": uniform((k, si), -bs, bs, seed=seed, tensor="Cw", layer=layer, rank=rank),
+        "Dw": uniform((q, so, k), -bk, bk, seed=seed, tensor="Dw", layer=layer, rank=rank),
     }
     return {name: round_to_storage(v, prob.dtype) for name, v in out.items()}
 
@@ -152,13 +174,13 @@ def one_rank_layer_inputs(prob: Problem, layer: int, seed: int, *, with_backward
     X, G ~ N(0,1); dY, dg_own ~ N(0,1)/batch (the scale of an MSE output error
     averaged over the batch).
     """
-    B, s, k, q = prob.batch, prob.s, prob.k, prob.peers
+    B, k, q = prob.batch, prob.k_of(layer), prob.peers
     r = prob.rank
     d = layer_params(prob, layer, r, seed)
-    d["X"] = normal((B, s), seed=seed, tensor="X", layer=layer, rank=r)
+    d["X"] = normal((B, prob.s_in(layer)), seed=seed, tensor="X", layer=layer, rank=r)
     d["G"] = normal((q, B, k), seed=seed, tensor="G", layer=layer, rank=r)
     if with_backward:
-        d["dY"] = normal((B, s), seed=seed, tensor="dY", layer=layer, rank=r, scale=1.0 / B)
+        d["dY"] = normal((B, prob.s_out(layer)), seed=seed, tensor="dY", layer=layer, rank=r, scale=1.0 / B)
         d["dg_own"] = normal((B, k), seed=seed, tensor="dg_own", layer=layer, rank=r, scale=1.0 / B)
     for name in ("X", "G", "dY", "dg_own"):
         if name in d:
@@ -178,8 +200,9 @@ def network_io(prob: Problem, seed: int) -> tuple:
     In all-ranks mode the caller shards the columns: rank j owns columns
     j*s .. (j+1)*s-1.  In one-rank mode only that rank's columns are used.
     """
-    X0 = normal((prob.batch, prob.n), seed=seed, tensor="X", layer=-1, rank=0)
-    T = normal((prob.batch, prob.n), seed=seed, tensor="T", layer=-1, rank=0)
+    n_in, n_out = prob.s_in(0) * prob.p, prob.s_out(prob.layers - 1) * prob.p
+    X0 = normal((prob.batch, n_in), seed=seed, tensor="X", layer=-1, rank=0)
+    T = normal((prob.batch, n_out), seed=seed, tensor="T", layer=-1, rank=0)
     return round_to_storage(X0, prob.dtype), round_to_storage(T, prob.dtype)
 
 
@@ -193,16 +216,17 @@ def one_rank_step_inputs(prob: Problem, seed: int) -> dict:
     """Everything a multi-layer one-rank step needs: per-layer weights, seeded
     peer buffers G[l] and reduce-scatter results dg_own[l], the rank's columns
     of the network input and target."""
-    B, s, k, q, r = prob.batch, prob.s, prob.k, prob.peers, prob.rank
+    B, q, r = prob.batch, prob.peers, prob.rank
     layers = []
     for l in range(prob.layers):
+        k = prob.k_of(l)
         d = layer_params(prob, l, r, seed)
         d["G"] = round_to_storage(normal((q, B, k), seed=seed, tensor="G", layer=l, rank=r), prob.dtype)
         d["dg_own"] = round_to_storage(
             normal((B, k), seed=seed, tensor="dg_own", layer=l, rank=r, scale=1.0 / B), prob.dtype)
         layers.append(d)
-    X0 = round_to_storage(normal((B, s), seed=seed, tensor="X", layer=-1, rank=r), prob.dtype)
-    T = round_to_storage(normal((B, s), seed=seed, tensor="T", layer=-1, rank=r), prob.dtype)
+    X0 = round_to_storage(normal((B, prob.s_in(0)), seed=seed, tensor="X", layer=-1, rank=r), prob.dtype)
+    T = round_to_storage(normal((B, prob.s_out(prob.layers - 1)), seed=seed, tensor="T", layer=-1, rank=r), prob.dtype)
     return {"layers": layers, "X0": X0, "T": T}
 
 

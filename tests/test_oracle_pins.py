@@ -56,9 +56,9 @@ def _dense_weight(Lw, Cw, Dw):
 def _dense_reference(act, X0, T, layers, lr):
     """Loss, parameter gradients (autograd) and SGD-updated parameters of the dense-equivalent
     network.  X0, T: [p,B,s] shards; layers: stacked numpy weights per layer."""
-    p, B, s = X0.shape
-    x = _t(X0).permute(1, 0, 2).reshape(B, p * s)
-    t = _t(T).permute(1, 0, 2).reshape(B, p * s)
+    p, B, _ = X0.shape
+    x = _t(X0).permute(1, 0, 2).reshape(B, -1)
+    t = _t(T).permute(1, 0, 2).reshape(B, -1)
     leaves = []
     for P in layers:
         leaf = {name: _t(P[name], grad=True) for name in ("Lw", "Cw", "Dw", "bias") if P.get(name) is not None}
@@ -71,12 +71,12 @@ def _dense_reference(act, X0, T, layers, lr):
     loss = 0.5 * torch.sum((x - t) ** 2) / B
     loss.backward()
     grads = [{name: v.grad.numpy() for name, v in leaf.items()} for leaf in leaves]
-    y = x.detach().numpy().reshape(B, p, s).transpose(1, 0, 2)
+    y = x.detach().numpy().reshape(B, p, -1).transpose(1, 0, 2)
     return float(loss), grads, y
 
 
-def _problem(n, p, k, B, L, act):
-    return pin.Problem(n=n, p=p, k=k, batch=B, layers=L, act=act, dtype="f32", rank=-1)
+def _problem(n, p, k, B, L, act, widths=(), ks=()):
+    return pin.Problem(n=n, p=p, k=k, batch=B, layers=L, act=act, dtype="f32", rank=-1, widths=widths, ks=ks)
 
 
 def _close(a, b, tol=1e-11):
@@ -112,19 +112,26 @@ def test_p1_is_dense_layer(act):
 # P2: dense equivalence for any k, all ranks, several layers
 # ----------------------------------------------------------------------------
 
-@pytest.mark.parametrize("n,p,k,B,L,act", [
-    (12, 3, 2, 5, 2, "gelu"),
-    (12, 3, 2, 5, 3, "relu"),
-    (20, 4, 3, 6, 2, "identity"),
-    (16, 2, 8, 4, 2, "relu"),        # k = s
-    (30, 5, 1, 3, 1, "gelu"),        # a single ghost neuron
+@pytest.mark.parametrize("n,p,k,B,L,act,widths,ks", [
+    (12, 3, 2, 5, 2, "gelu", (), ()),
+    (12, 3, 2, 5, 3, "relu", (), ()),
+    (20, 4, 3, 6, 2, "identity", (), ()),
+    (16, 2, 8, 4, 2, "relu", (), ()),        # k = s
+    (30, 5, 1, 3, 1, "gelu", (), ()),        # a single ghost neuron
+    # layers of different widths and phantom widths (Section IV, first paragraph): 12 -> 21 -> 6 -> 15 over 3 ranks
+    (12, 3, 2, 5, 3, "gelu", (12, 21, 6, 15), (2, 3, 1)),
+    (8, 2, 1, 4, 2, "relu", (8, 20, 4), (4, 2)),
 ])
-def test_phantom_equals_structured_dense(n, p, k, B, L, act):
+def test_phantom_equals_structured_dense(n, p, k, B, L, act, widths, ks):
+    check_structured_dense(n, p, k, B, L, act, widths, ks)
+
+
+def check_structured_dense(n, p, k, B, L, act, widths=(), ks=()):
     """The phantom model is the dense model whose off-diagonal block (j,i) is D^(i,j) C^(i).
     torch autograd through that dense model gives the gradients of L, C, D and b directly.
     Pins: which D goes with which peer and which slot, that C^(i) is shared by all destinations,
     the gather and reduce-scatter index maps, the shapes of dD, the chaining over layers."""
-    prob = _problem(n, p, k, B, L, act)
+    prob = _problem(n, p, k, B, L, act, widths, ks)
     data = pin.all_rank_step_inputs(prob, seed=11)
     got = oracle.ffn_step(act, data["X0"], data["T"], data["layers"], lr=0.01, storage="f32", all_ranks=True)
     loss, grads, y = _dense_reference(act, data["X0"], data["T"], data["layers"], lr=0.01)
@@ -204,11 +211,15 @@ def test_parameter_count_matches_table_1():
 # P5: finite differences (does not rely on torch)
 # ----------------------------------------------------------------------------
 
-@pytest.mark.parametrize("act", ["gelu", "identity"])
-def test_gradients_match_central_differences(act):
+@pytest.mark.parametrize("act,widths,ks", [("gelu", (), ()), ("identity", (), ()), ("gelu", (12, 18, 6), (2, 3))])
+def test_gradients_match_central_differences(act, widths, ks):
+    check_central_differences(act, widths, ks)
+
+
+def check_central_differences(act, widths=(), ks=()):
     """Central differences of the oracle's own forward + loss, for every parameter tensor of every
     layer and for the network input.  Pins the whole backward, incl. multi-layer chaining."""
-    prob = _problem(n=12, p=3, k=2, B=3, L=2, act=act)
+    prob = _problem(n=12, p=3, k=2, B=3, L=2, act=act, widths=widths, ks=ks)
     data = pin.all_rank_step_inputs(prob, seed=7)
     layers = data["layers"]
 
