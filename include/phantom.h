@@ -56,7 +56,18 @@ typedef enum {
 typedef enum { PH_ACT_IDENTITY = 0, PH_ACT_RELU = 1, PH_ACT_GELU = 2 /* x*Phi(x), erf form */ } ph_act;
 typedef enum { PH_F32 = 0, PH_BF16 = 1 } ph_dtype;
 
-/* The problem as the paper states it: (n, p, k, batch, layers, activation). */
+/*
+ * The problem as the paper states it: (n, p, k, batch, layers, activation).
+ *
+ * Layers of different widths (Section IV, first paragraph: widths n_l and phantom widths k_l; the paper then
+ * writes one n and one k for brevity): `widths` and `ks`, HOST arrays read during each call, or both NULL for
+ * the uniform network.  widths[0 .. layers] = n_0 .. n_L (n_0 the network input, n_l the output of layer l,
+ * each a multiple of p); ks[0 .. layers-1] = k_1 .. k_L.  Layer l then has, per rank, si = n_{l-1}/p inputs
+ * and so = n_l/p outputs: Lw [so, si], Cw [k_l, si] (it compresses the layer's input), Dw [p-1, so, k_l],
+ * bias [so]; wherever a shape below says s, read si for the layer's input side (X, dX, columns of Lw and
+ * Cw) and so for its output side (Y, A, dY, bias, rows of Lw and Dw).  n and k are ignored when widths
+ * is given.  The single-layer calls use widths[0], widths[1], ks[0].
+ */
 typedef struct {
     int64_t n;        /* layer width; n % p == 0 */
     int64_t p;        /* ranks; p >= 1.  p == 1: a plain dense layer, no C, D, G */
@@ -66,6 +77,8 @@ typedef struct {
     int32_t act;      /* ph_act, same for every layer incl. the last (sigma_L in Eq. (deltaL)) */
     int32_t dtype;    /* ph_dtype */
     int32_t rank;     /* j in [0, p): one-rank mode.  -1: all p ranks on this GPU */
+    const int64_t *widths;   /* host, layers + 1 entries, or NULL */
+    const int64_t *ks;       /* host, layers entries, or NULL (required with widths when p > 1) */
 } ph_problem;
 
 /* Bytes of workspace that any of the three calls below needs for this problem (host pointer out). */

@@ -31,6 +31,7 @@ class PhProblem(ctypes.Structure):
     _fields_ = [
         ("n", ctypes.c_int64), ("p", ctypes.c_int64), ("k", ctypes.c_int64), ("batch", ctypes.c_int64),
         ("layers", ctypes.c_int32), ("act", ctypes.c_int32), ("dtype", ctypes.c_int32), ("rank", ctypes.c_int32),
+        ("widths", ctypes.POINTER(ctypes.c_int64)), ("ks", ctypes.POINTER(ctypes.c_int64)),
     ]
 
     @property
@@ -121,8 +122,16 @@ def last_error() -> str:
 
 
 def make_problem(n: int, p: int, k: int, batch: int, layers: int = 1, act: str = "relu", dtype: str = "f32",
-                 rank: int = 0) -> PhProblem:
-    return PhProblem(n, p, k, batch, layers, ACTS[act], DTYPES[dtype], rank)
+                 rank: int = 0, widths=(), ks=()) -> PhProblem:
+    """widths (n_0 .. n_L) and ks (k_1 .. k_L): layers of different widths; empty = every layer n and k."""
+    prob = PhProblem(n, p, k, batch, layers, ACTS[act], DTYPES[dtype], rank, None, None)
+    if widths:
+        prob._widths = (ctypes.c_int64 * len(widths))(*widths)      # kept alive by the struct object
+        prob.widths = ctypes.cast(prob._widths, ctypes.POINTER(ctypes.c_int64))
+        if ks:
+            prob._ks = (ctypes.c_int64 * len(ks))(*ks)
+            prob.ks = ctypes.cast(prob._ks, ctypes.POINTER(ctypes.c_int64))
+    return prob
 
 
 def _ptr(t) -> Optional[int]:

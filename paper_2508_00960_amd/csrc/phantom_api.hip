@@ -38,32 +38,48 @@ ph_status fail(ph_status st, const char *fmt, ...)
     return st;
 }
 
+#define PH_TRY(expr) do { ph_status st__ = (expr); if (st__ != PH_OK) return st__; } while (0)
+
+// One layer's shapes on this GPU.  si / so: inputs / outputs of the layer held by one rank (equal unless
+// the problem gives per-layer widths).
 struct Geo {
-    int64_t n, p, k, B, s, q, Kc;
+    int64_t p, k, B, si, so, q, Kc;
     int groups;       // ranks held on this GPU: 1 or p
     bool all;         // all-ranks mode
     int act, dtype, rank, layers;
     size_t esz;       // bytes per element of the storage type
-    int vec;          // bf16: widest vector (8, 4, 2 elements) dividing n/p and k; 0: shape-agnostic kernels only
+    int vec;          // bf16: widest vector (8, 4, 2 elements) dividing si, so and k; 0: shape-agnostic kernels only
 };
 
-ph_status make_geo(const ph_problem *pr, Geo &g)
+// Checks the problem and fills in the shapes of layer `layer` (0-based).
+ph_status make_geo(const ph_problem *pr, Geo &g, int layer = 0)
 {
     if (!pr) return fail(PH_ERR_INVALID_ARG, "problem is NULL");
     if (pr->p < 1) return fail(PH_ERR_INVALID_ARG, "p = %lld must be >= 1", (long long)pr->p);
-    if (pr->n < 1 || pr->n % pr->p) return fail(PH_ERR_INVALID_ARG, "n = %lld must be a positive multiple of p = %lld",
-                                                (long long)pr->n, (long long)pr->p);
     if (pr->batch < 1) return fail(PH_ERR_INVALID_ARG, "batch = %lld must be >= 1", (long long)pr->batch);
-    const int64_t s = pr->n / pr->p;
-    if (pr->p > 1 && (pr->k < 1 || pr->k > s))
-        return fail(PH_ERR_INVALID_ARG, "k = %lld must lie in [1, n/p = %lld]", (long long)pr->k, (long long)s);
     if (pr->act < PH_ACT_IDENTITY || pr->act > PH_ACT_GELU) return fail(PH_ERR_INVALID_ARG, "unknown activation %d", pr->act);
     if (pr->dtype != PH_F32 && pr->dtype != PH_BF16) return fail(PH_ERR_INVALID_ARG, "unknown dtype %d", pr->dtype);
     if (pr->rank < -1 || pr->rank >= pr->p) return fail(PH_ERR_INVALID_ARG, "rank = %d must lie in [-1, p)", pr->rank);
     if (pr->layers < 1) return fail(PH_ERR_INVALID_ARG, "layers = %d must be >= 1", pr->layers);
-    g.n = pr->n; g.p = pr->p; g.B = pr->batch; g.s = s; g.q = pr->p - 1;
-    g.k = g.q > 0 ? pr->k : 0;
-    g.Kc = s + g.q * g.k;
+    if (layer < 0 || layer >= pr->layers) return fail(PH_ERR_INVALID_ARG, "layer %d of %d", layer, pr->layers);
+    int64_t n_in = pr->n, n_out = pr->n, k = pr->k;
+    if (pr->widths) {
+        if (pr->p > 1 && !pr->ks) return fail(PH_ERR_INVALID_ARG, "widths without ks");
+        n_in = pr->widths[layer]; n_out = pr->widths[layer + 1];
+        if (pr->ks) k = pr->ks[layer];
+    } else if (pr->ks) {
+        return fail(PH_ERR_INVALID_ARG, "ks without widths");
+    }
+    if (n_in < 1 || n_in % pr->p || n_out < 1 || n_out % pr->p)
+        return fail(PH_ERR_INVALID_ARG, "layer %d: widths %lld -> %lld must be positive multiples of p = %lld", layer,
+                    (long long)n_in, (long long)n_out, (long long)pr->p);
+    const int64_t si = n_in / pr->p, so = n_out / pr->p;
+    if (pr->p > 1 && (k < 1 || k > std::max(si, so)))
+        return fail(PH_ERR_INVALID_ARG, "layer %d: k = %lld must lie in [1, n/p = %lld]", layer, (long long)k,
+                    (long long)std::max(si, so));
+    g.p = pr->p; g.B = pr->batch; g.si = si; g.so = so; g.q = pr->p - 1;
+    g.k = g.q > 0 ? k : 0;
+    g.Kc = si + g.q * g.k;
     g.all = pr->rank < 0;
     g.groups = g.all ? (int)pr->p : 1;
     g.act = pr->act; g.dtype = pr->dtype; g.rank = pr->rank; g.layers = pr->layers;
@@ -71,11 +87,21 @@ ph_status make_geo(const ph_problem *pr, Geo &g)
     g.vec = 0;
     if (pr->dtype == PH_BF16) {
         for (int v = 8; v >= 2 && !g.vec; v >>= 1)
-            if (s % v == 0 && (g.q == 0 || g.k % v == 0)) g.vec = v;
+            if (si % v == 0 && so % v == 0 && (g.q == 0 || g.k % v == 0)) g.vec = v;
     }
     // index arithmetic inside the kernels uses 32-bit row/column numbers and a 3-D grid
-    if (g.B > (1 << 22) || g.s > (1 << 22) || g.Kc > (1 << 24) || g.p > 65535)
+    if (g.B > (1 << 22) || si > (1 << 22) || so > (1 << 22) || g.Kc > (1 << 24) || so + g.q * g.k > (1 << 24) || g.p > 65535)
         return fail(PH_ERR_UNSUPPORTED, "problem too large for 32-bit tile indices (batch, n/p <= 2^22, n/p+(p-1)k <= 2^24)");
+    return PH_OK;
+}
+
+// every layer's shapes (a uniform problem: `layers` copies of the same)
+ph_status make_geos(const ph_problem *pr, std::vector<Geo> &geos)
+{
+    Geo first;
+    PH_TRY(make_geo(pr, first, 0));
+    geos.assign((size_t)pr->layers, first);
+    for (int l = 1; l < pr->layers; ++l) PH_TRY(make_geo(pr, geos[(size_t)l], l));
     return PH_OK;
 }
 
@@ -90,7 +116,6 @@ ph_status optional(const void *p, const char *name)
     if (p && ((uintptr_t)p & 15)) return fail(PH_ERR_INVALID_ARG, "%s is not 16-byte aligned", name);
     return PH_OK;
 }
-#define PH_TRY(expr) do { ph_status st__ = (expr); if (st__ != PH_OK) return st__; } while (0)
 
 ph_status check_launch(const char *what)
 {
@@ -164,13 +189,13 @@ struct Arena {
 constexpr int MSE_BLOCKS = 1024;
 
 struct BwdWs {
-    void *delta;        // [groups, B, s] storage type
+    void *delta;        // [groups, B, so] storage type
 };
 
 BwdWs carve_bwd(Arena &a, const Geo &g)
 {
     BwdWs w;
-    w.delta = a.take((size_t)g.groups * g.B * g.s * g.esz);
+    w.delta = a.take((size_t)g.groups * g.B * g.so * g.esz);
     return w;
 }
 
@@ -179,33 +204,46 @@ struct StepWs {
     void *dYa, *dYb, *dG_send, *dg_own;
     float *dLw[2], *dCw[2], *dDw[2];                // two sets, used by alternate layers: a layer's update may still read
                                                     //   its gradients while the layer below writes its own
-    float *dbias, *mse_partial;                     // dbias: [layers][groups, s], one block
+    float *dbias, *mse_partial;                     // dbias: one block, layer l's [groups, so_l] at dbias_at[l]
+    std::vector<int64_t> dbias_at;                  // float offsets into dbias; dbias_at[layers] = the block's length
     BwdWs bwd;
 };
 
-StepWs carve_step(Arena &a, const Geo &g)
+// geos: every layer's shapes.  Buffers that are reused from layer to layer take the largest layer's size.
+StepWs carve_step(Arena &a, const std::vector<Geo> &geos)
 {
     StepWs w;
-    const size_t act_bytes = (size_t)g.groups * g.B * g.s * g.esz;
-    const size_t gath_bytes = (size_t)g.groups * g.B * g.k * g.esz;   // all-ranks: [p,B,k]; one-rank: [B,k]
-    for (int l = 0; l < g.layers; ++l) {
+    const Geo &g0 = geos[0];
+    size_t act_max = 0, k_max = 0, lw_max = 0, cw_max = 0, dw_max = 0;
+    int64_t dbias_total = 0;
+    for (const Geo &g : geos) {
+        const size_t act_bytes = (size_t)g.groups * g.B * g.so * g.esz;
         w.Y.push_back(a.take(act_bytes));
         // GELU keeps per layer: fp32 storage, the pre-activation; bf16 storage, sigma'(pre-activation) in fp16
-        w.A.push_back(g.act == PH_ACT_GELU ? a.take(g.esz == 2 ? act_bytes : (size_t)g.groups * g.B * g.s * sizeof(float)) : nullptr);
-        w.G.push_back(g.q > 0 ? a.take(gath_bytes) : nullptr);
+        w.A.push_back(g.act == PH_ACT_GELU ? a.take(g.esz == 2 ? act_bytes : (size_t)g.groups * g.B * g.so * sizeof(float)) : nullptr);
+        w.G.push_back(g.q > 0 ? a.take((size_t)g.groups * g.B * g.k * g.esz) : nullptr);   // all-ranks: [p,B,k]; one-rank: [B,k]
+        act_max = std::max(act_max, (size_t)std::max(g.si, g.so));
+        k_max = std::max(k_max, (size_t)g.k);
+        lw_max = std::max(lw_max, (size_t)(g.so * g.si));
+        cw_max = std::max(cw_max, (size_t)(g.k * g.si));
+        dw_max = std::max(dw_max, (size_t)(g.q * g.so * g.k));
+        w.dbias_at.push_back(dbias_total);
+        dbias_total += (int64_t)g.groups * g.so;
     }
-    w.dYa = a.take(act_bytes);
-    w.dYb = a.take(act_bytes);
-    w.dG_send = g.q > 0 ? a.take((size_t)g.groups * g.q * g.B * g.k * g.esz) : nullptr;
-    w.dg_own = g.q > 0 ? a.take(gath_bytes) : nullptr;
+    w.dbias_at.push_back(dbias_total);
+    const size_t groups = (size_t)g0.groups, B = (size_t)g0.B;
+    w.dYa = a.take(groups * B * act_max * g0.esz);
+    w.dYb = a.take(groups * B * act_max * g0.esz);
+    w.dG_send = g0.q > 0 ? a.take(groups * g0.q * B * k_max * g0.esz) : nullptr;
+    w.dg_own = g0.q > 0 ? a.take(groups * B * k_max * g0.esz) : nullptr;
     for (int set = 0; set < 2; ++set) {
-        w.dLw[set] = (float *)a.take((size_t)g.groups * g.s * g.s * 4);
-        w.dCw[set] = (float *)a.take((size_t)g.groups * g.k * g.s * 4 + 16);
-        w.dDw[set] = (float *)a.take((size_t)g.groups * g.q * g.s * g.k * 4 + 16);
+        w.dLw[set] = (float *)a.take(groups * lw_max * 4);
+        w.dCw[set] = (float *)a.take(groups * cw_max * 4 + 16);
+        w.dDw[set] = (float *)a.take(groups * dw_max * 4 + 16);
     }
-    w.dbias = (float *)a.take((size_t)g.layers * g.groups * g.s * 4);
+    w.dbias = (float *)a.take((size_t)dbias_total * 4);
     w.mse_partial = (float *)a.take(MSE_BLOCKS * sizeof(float));
-    w.bwd = carve_bwd(a, g);
+    w.bwd.delta = a.take(groups * B * act_max * g0.esz);
     return w;
 }
 
@@ -506,53 +544,53 @@ struct OutputError {
 // update)?  Same conditions as in fwd_impl.
 bool thin_compression_first(const Geo &g)
 {
-    if (g.dtype != PH_BF16 || g.q == 0 || g.k > THIN_MAX_N || g.s % 16 != 0 || g.vec == 0) return false;
+    if (g.dtype != PH_BF16 || g.q == 0 || g.k > THIN_MAX_N || g.si % 16 != 0 || g.vec == 0) return false;
     if (g.all) return true;
-    const int64_t tiles_both = (tiles_of(g.B, g.s) + tiles_of(g.B, g.k)) * g.groups;
+    const int64_t tiles_both = (tiles_of(g.B, g.so) + tiles_of(g.B, g.k)) * g.groups;
     return tiles_both > 256;
 }
 
 template <typename T>
 ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
 {
-    const int64_t B = g.B, s = g.s, k = g.k, q = g.q;
+    const int64_t B = g.B, si = g.si, so = g.so, k = g.k, q = g.q;
     const GemmPlan plan{LD_KC, LD_KC, g.vec, false};
-    // compression g = C y: [B, s] x [k, s]^T -> [B, k]
-    Product compress{view_plain(f.X, s, B * s), view_plain(f.Cw, s, k * s), view_plain(f.g_own, k, B * k), epi_store(),
-                     q > 0 ? B : 0, k, s};
+    // compression g = C y: [B, si] x [k, si]^T -> [B, k]
+    Product compress{view_plain(f.X, si, B * si), view_plain(f.Cw, si, k * si), view_plain(f.g_own, k, B * k), epi_store(),
+                     q > 0 ? B : 0, k, si};
     // local update + decompression + remote update + bias + activation: one product over the
     // concatenated reduction index [y | g_1 .. g_{p-1}] . [L | D_1 .. D_{p-1}]^T
     const void *gathered = g.all ? f.g_own : f.G;
     Product update{};
-    update.a = q > 0 ? view_rowseg(f.X, s, (int)s, B * s, gathered, (int)k, B * k, 0, g.all ? 0 : NO_SKIP, g.all ? 1 : 0)
-                     : view_plain(f.X, s, B * s);
-    update.b = q > 0 ? view_rowseg(f.Lw, s, (int)s, s * s, f.Dw, (int)k, s * k, q * s * k) : view_plain(f.Lw, s, s * s);
-    update.o = view_plain(f.Y, s, B * s);
-    update.ep.mode = EPI_BIAS_ACT; update.ep.act = g.act; update.ep.bias = f.bias; update.ep.bias_g = s;
-    update.ep.aux = f.A_save; update.ep.aux_ld = s; update.ep.aux_g = B * s; update.ep.aux_f32 = f.a_f32; update.ep.aux_deriv = f.a_deriv;
-    update.M = B; update.N = s; update.K = g.Kc;
+    update.a = q > 0 ? view_rowseg(f.X, si, (int)si, B * si, gathered, (int)k, B * k, 0, g.all ? 0 : NO_SKIP, g.all ? 1 : 0)
+                     : view_plain(f.X, si, B * si);
+    update.b = q > 0 ? view_rowseg(f.Lw, si, (int)si, so * si, f.Dw, (int)k, so * k, q * so * k) : view_plain(f.Lw, si, so * si);
+    update.o = view_plain(f.Y, so, B * so);
+    update.ep.mode = EPI_BIAS_ACT; update.ep.act = g.act; update.ep.bias = f.bias; update.ep.bias_g = so;
+    update.ep.aux = f.A_save; update.ep.aux_ld = so; update.ep.aux_g = B * so; update.ep.aux_f32 = f.a_f32; update.ep.aux_deriv = f.a_deriv;
+    update.M = B; update.N = so; update.K = g.Kc;
     float *clear_at = nullptr;
     int64_t clear_count = 0;
     if (f.mse) {
         if (!thin_compression_first(g)) return fail(PH_ERR_LAUNCH, "output error in the update needs the thin compression launch");
         update.ep.mse_target = f.mse->target; update.ep.mse_delta = f.mse->delta; update.ep.mse_partial = f.mse->partial;
         update.ep.mse_inv_b = f.mse->inv_b;
-        update.ep.colsum = f.mse->dbias; update.ep.colsum_g = s;
+        update.ep.colsum = f.mse->dbias; update.ep.colsum_g = so;
         clear_at = f.mse->clear_at; clear_count = f.mse->clear_count;
     }
     // A compression with few phantom neurons has a kernel of its own (32 rows per workgroup instead of 128)
     bool thin = false;
-    if constexpr (std::is_same<T, bf16_t>::value) thin = q > 0 && k <= THIN_MAX_N && s % 16 == 0 && g.vec > 0;
+    if constexpr (std::is_same<T, bf16_t>::value) thin = q > 0 && k <= THIN_MAX_N && si % 16 == 0 && g.vec > 0;
     auto launch_thin = [&]() -> ph_status {
         if constexpr (std::is_same<T, bf16_t>::value) {
-            ProfScope prof("compression", B, k, s, g.groups, st);
+            ProfScope prof("compression", B, k, si, g.groups, st);
             dim3 grid((unsigned)((B + THIN_ROWS - 1) / THIN_ROWS), (unsigned)g.groups);
             if (k <= 32)
                 hipLaunchKernelGGL((thin_product_kernel<1>), grid, dim3(256), 0, st, (const __bf16 *)f.X, (const __bf16 *)f.Cw,
-                                   (__bf16 *)f.g_own, (int)B, (int)k, (int)s, B * s, k * s, B * k, clear_at, clear_count);
+                                   (__bf16 *)f.g_own, (int)B, (int)k, (int)si, B * si, k * si, B * k, clear_at, clear_count);
             else
                 hipLaunchKernelGGL((thin_product_kernel<2>), grid, dim3(256), 0, st, (const __bf16 *)f.X, (const __bf16 *)f.Cw,
-                                   (__bf16 *)f.g_own, (int)B, (int)k, (int)s, B * s, k * s, B * k, clear_at, clear_count);
+                                   (__bf16 *)f.g_own, (int)B, (int)k, (int)si, B * si, k * si, B * k, clear_at, clear_count);
             return check_launch("compression");
         }
         return PH_OK;
@@ -565,7 +603,7 @@ ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
     }
     // one rank: the peers' g are inputs, so the rank's own compression runs beside the update when the two
     // fit the device together
-    const int64_t tiles_both = (tiles_of(B, s) + tiles_of(B, k)) * g.groups;
+    const int64_t tiles_both = (tiles_of(B, so) + tiles_of(B, k)) * g.groups;
     if (thin && tiles_both > 256) {
         PH_TRY(launch_thin());
         return launch_products<T, T>(plan, &update, 1, g.groups, st, "layer update");
@@ -592,6 +630,7 @@ struct BwdArgs {
     bool dbias_zeroed;         // step only: dbias is zero on entry
     bool send_done;            // step only: this layer's error compression was launched by the layer above (below)
     const void *below_Dw;      // step only, all ranks: D of the layer below; its error compression (dX -> dG_send)
+    const Geo *below_g;        //   (that layer's shapes)
     bool *below_done;          //   may then ride with this layer's weight gradients; *below_done says whether it did
     const SgdBatch *ride_sgd;  // step only: the update of the layer above, not launched yet; it may ride with this
     float ride_lr;             //   layer's weight gradients on compute units they leave idle; *ride_sgd_done says
@@ -603,8 +642,8 @@ struct BwdArgs {
 template <typename T>
 ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t st)
 {
-    const int64_t B = g.B, s = g.s, k = g.k, q = g.q;
-    const int64_t act_count = (int64_t)g.groups * B * s;
+    const int64_t B = g.B, si = g.si, so = g.so, k = g.k, q = g.q;
+    const int64_t act_count = (int64_t)g.groups * B * so;
 
     // local error delta = dY * sigma'
     const void *delta = b.delta_ready;
@@ -625,57 +664,58 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
 
     // bias gradient: column sums of delta
     {
-        const int strips = (int)((s + CSUM_COLS - 1) / CSUM_COLS);
+        const int strips = (int)((so + CSUM_COLS - 1) / CSUM_COLS);
         // enough workgroups to pull the whole tensor at memory speed: split the rows when the strips are few
         int chunks = (int)std::max<int64_t>(1, std::min<int64_t>(256 / ((int64_t)strips * g.groups), B / 128));
         if (g.dtype == PH_F32) chunks = 1;      // the fp32 path keeps a fixed summation order
         const int rows_per_chunk = (int)((B + chunks - 1) / chunks);
         chunks = (int)((B + rows_per_chunk - 1) / rows_per_chunk);
         if (chunks > 1 && !b.dbias_zeroed && !b.dbias_ready) {
-            ProfScope prof("clear bias gradient", 0, (int64_t)g.groups * s, 0, 1, st);
-            hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks_for((int64_t)g.groups * s)), dim3(256), 0, st, b.dbias,
-                               (int64_t)g.groups * s);
+            ProfScope prof("clear bias gradient", 0, (int64_t)g.groups * so, 0, 1, st);
+            hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks_for((int64_t)g.groups * so)), dim3(256), 0, st, b.dbias,
+                               (int64_t)g.groups * so);
             PH_TRY(check_launch("clear bias gradient"));
         }
         if (!b.dbias_ready) {
             dim3 grid((unsigned)strips, (unsigned)g.groups, (unsigned)chunks);
             ProfScope prof("bias gradient", 0, act_count, 0, 1, st);
-            hipLaunchKernelGGL((colsum_kernel<T>), grid, dim3(256), 0, st, (const T *)delta, b.dbias, (int)B, (int)s,
+            hipLaunchKernelGGL((colsum_kernel<T>), grid, dim3(256), 0, st, (const T *)delta, b.dbias, (int)B, (int)so,
                                rows_per_chunk, take_tail());
             PH_TRY(check_launch("bias gradient"));
         }
     }
 
-    // error compression: dG_send[i] = delta . D_i   ([B, s] x [s, k] for every peer, one product over N = q*k)
-    auto error_compression = [&](const void *dl, const void *Dw) {
+    // error compression: dG_send[i] = delta . D_i   ([B, so] x [so, k] for every peer, one product over N = q*k);
+    // w, kk: the output width and phantom width of the layer whose delta and D these are
+    auto error_compression = [&](const void *dl, const void *Dw, int64_t w_out, int64_t kk) {
         Product send{};
-        send.a = view_plain(dl, s, B * s);
-        send.b.p0 = nullptr; send.b.p1 = const_cast<void *>(Dw); send.b.g0 = 0; send.b.g1 = q * s * k;
-        send.b.r = axis_seg(0, (int)k, 0, 1, s * k); send.b.c = axis_plain(0, k);
+        send.a = view_plain(dl, w_out, B * w_out);
+        send.b.p0 = nullptr; send.b.p1 = const_cast<void *>(Dw); send.b.g0 = 0; send.b.g1 = q * w_out * kk;
+        send.b.r = axis_seg(0, (int)kk, 0, 1, w_out * kk); send.b.c = axis_plain(0, kk);
         send.b.skip0 = NO_SKIP; send.b.skip_g = 0;
-        send.o.p0 = nullptr; send.o.p1 = b.dG_send; send.o.g0 = 0; send.o.g1 = q * B * k;
-        send.o.r = axis_plain(0, k); send.o.c = axis_seg(0, (int)k, 0, 1, B * k);
+        send.o.p0 = nullptr; send.o.p1 = b.dG_send; send.o.g0 = 0; send.o.g1 = q * B * kk;
+        send.o.r = axis_plain(0, kk); send.o.c = axis_seg(0, (int)kk, 0, 1, B * kk);
         send.o.skip0 = NO_SKIP; send.o.skip_g = 0;
         send.ep = epi_store();
-        send.M = q > 0 ? B : 0; send.N = q * k; send.K = s;
+        send.M = q > 0 ? B : 0; send.N = q * kk; send.K = w_out;
         return send;
     };
-    const Product send = error_compression(delta, b.Dw);
+    const Product send = error_compression(delta, b.Dw, so, k);
 
     // dX = delta . L + dg_own . C: reduction index = [delta | dg_own] against [L ; C]
     Product dx{};
-    dx.a = q > 0 ? view_rowseg(delta, s, (int)s, B * s, b.dg_own, (int)k, 0, B * k) : view_plain(delta, s, B * s);
-    dx.b = q > 0 ? view_colstack(b.Lw, s, (int)s, s * s, b.Cw, s, (int)k, k * s) : view_plain_t(b.Lw, s, s * s);
-    dx.o = view_plain(b.dX, s, B * s);
+    dx.a = q > 0 ? view_rowseg(delta, so, (int)so, B * so, b.dg_own, (int)k, 0, B * k) : view_plain(delta, so, B * so);
+    dx.b = q > 0 ? view_colstack(b.Lw, si, (int)so, so * si, b.Cw, si, (int)k, k * si) : view_plain_t(b.Lw, si, so * si);
+    dx.o = view_plain(b.dX, si, B * si);
     dx.ep = epi_store();
     if (b.dx_S && g.act != PH_ACT_IDENTITY) {
-        dx.ep.mode = EPI_DACT; dx.ep.act = g.act; dx.ep.aux = const_cast<void *>(b.dx_S); dx.ep.aux_ld = s;
-        dx.ep.aux_g = B * s; dx.ep.aux_f32 = b.dx_S_f32; dx.ep.aux_deriv = b.dx_S_deriv;
+        dx.ep.mode = EPI_DACT; dx.ep.act = g.act; dx.ep.aux = const_cast<void *>(b.dx_S); dx.ep.aux_ld = si;
+        dx.ep.aux_g = B * si; dx.ep.aux_f32 = b.dx_S_f32; dx.ep.aux_deriv = b.dx_S_deriv;
     } else if (b.dx_colsum) {
         dx.ep.mode = EPI_DACT; dx.ep.act = g.act; dx.ep.aux = nullptr;      // identity: column sums only
     }
-    dx.ep.colsum = b.dx_colsum; dx.ep.colsum_g = s;
-    dx.M = b.dX ? B : 0; dx.N = s; dx.K = s + k;
+    dx.ep.colsum = b.dx_colsum; dx.ep.colsum_g = si;
+    dx.M = b.dX ? B : 0; dx.N = si; dx.K = so + k;
 
     const GemmPlan plan_x{LD_KC, LD_KM, g.vec, false};
     if (g.all) {
@@ -705,17 +745,17 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
 
     // weight gradients: [dL | dD_1 .. dD_{p-1}] = delta^T . [X | G_1 .. G_{p-1}], and dC = dg_own^T . X beside it
     Product dw{};
-    dw.a = view_plain_t(delta, s, B * s);
-    dw.b = q > 0 ? view_rowseg_t(b.X, s, (int)s, B * s, b.G, (int)k, B * k, 0, g.all ? 0 : NO_SKIP, g.all ? 1 : 0)
-                 : view_plain_t(b.X, s, B * s);
-    dw.o.p0 = b.dLw; dw.o.p1 = b.dDw; dw.o.g0 = s * s; dw.o.g1 = q * s * k;
-    dw.o.r = axis_plain(s, k);
-    dw.o.c = q > 0 ? axis_seg((int)s, (int)k, 1, 1, s * k) : axis_plain(1, 0);
+    dw.a = view_plain_t(delta, so, B * so);
+    dw.b = q > 0 ? view_rowseg_t(b.X, si, (int)si, B * si, b.G, (int)k, B * k, 0, g.all ? 0 : NO_SKIP, g.all ? 1 : 0)
+                 : view_plain_t(b.X, si, B * si);
+    dw.o.p0 = b.dLw; dw.o.p1 = b.dDw; dw.o.g0 = so * si; dw.o.g1 = q * so * k;
+    dw.o.r = axis_plain(si, k);
+    dw.o.c = q > 0 ? axis_seg((int)si, (int)k, 1, 1, so * k) : axis_plain(1, 0);
     dw.o.skip0 = NO_SKIP; dw.o.skip_g = 0;
     dw.ep = epi_store();
-    dw.M = s; dw.N = g.Kc; dw.K = B;
-    Product dc{view_plain_t(b.dg_own, k, B * k), view_plain_t(b.X, s, B * s), view_plain(b.dCw, s, k * s), epi_store(),
-               q > 0 ? k : 0, s, B};
+    dw.M = so; dw.N = g.Kc; dw.K = B;
+    Product dc{view_plain_t(b.dg_own, k, B * k), view_plain_t(b.X, si, B * si), view_plain(b.dCw, si, k * si), epi_store(),
+               q > 0 ? k : 0, si, B};
     Product grads[2] = {dw, dc};
     if (b.below_done) *b.below_done = false;
     if (b.ride_sgd_done) *b.ride_sgd_done = false;
@@ -732,8 +772,10 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
             Product below{};
             bool with_head = false;
             int64_t used = tail_tiles;
-            if (allowed && b.below_Dw && b.dX && g.all && q > 0) {
-                below = error_compression(b.dX, b.below_Dw);
+            int vec = g.vec;
+            if (allowed && b.below_Dw && b.below_g && b.below_g->vec > 0 && b.dX && g.all && q > 0) {
+                below = error_compression(b.dX, b.below_Dw, b.below_g->so, b.below_g->k);
+                vec = std::min(vec, b.below_g->vec);
                 const int64_t head_tiles = tiles_of(below.M, below.N) * g.groups;
                 with_head = head_tiles <= 128;
                 if (with_head) used += (head_tiles + 7) & ~(int64_t)7;
@@ -742,7 +784,7 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
             const bool with_sgd = allowed && b.ride_sgd && idle >= 64;
             if (with_head || with_sgd) {
                 PH_TRY(launch_tail(with_head ? &below : nullptr, dw, dc, with_sgd ? b.ride_sgd : nullptr, b.ride_lr, (int)idle,
-                                   g.groups, g.vec, st,
+                                   g.groups, vec, st,
                                    with_head ? (with_sgd ? "weight + compressor gradients | error compression below | SGD above"
                                                          : "weight + compressor gradients | error compression below")
                                              : "weight + compressor gradients | SGD above"));
@@ -791,11 +833,12 @@ ph_status check_ws(void *ws, size_t have, size_t want)
 }
 
 template <typename T>
-ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStream_t st)
+ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const StepWs &w, hipStream_t st)
 {
+    const Geo &g = geos.back();       // the last layer; what does not depend on the layer is read from it
     const int L = g.layers;
-    const int64_t B = g.B, s = g.s, k = g.k, q = g.q;
-    const int64_t act_count = (int64_t)g.groups * B * s;
+    const int64_t B = g.B, q = g.q;
+    const int64_t act_count = (int64_t)g.groups * B * g.so;      // elements of the network output
 
     // What the backward pass needs of a layer's pre-activation A is sigma'(A) alone.  ReLU reads it off the
     // layer's output.  GELU in bf16 storage has the forward epilogue, which evaluates erf and exp for
@@ -811,24 +854,24 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
     // for the whole step: the caller's buffers by launches of their own, the workspace's (one block) by a
     // kernel that runs anyway.
     const bool train = a.mode != PH_STEP_FORWARD;
-    const bool fused_dbias = std::is_same<T, bf16_t>::value && g.vec > 0;
-    const int64_t bias_count = (int64_t)g.groups * s;
-    auto dbias_of = [&](int l) { return a.dbias ? a.dbias[l] : w.dbias + (int64_t)l * bias_count; };
+    auto on_mfma = [&](int l) { return std::is_same<T, bf16_t>::value && geos[(size_t)l].vec > 0; };
+    auto dbias_of = [&](int l) { return a.dbias ? a.dbias[l] : w.dbias + w.dbias_at[(size_t)l]; };
     if (train && a.dbias) {
         for (int l = 0; l < L; ++l) {
+            const int64_t bias_count = (int64_t)g.groups * geos[(size_t)l].so;
             hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks_for(bias_count)), dim3(256), 0, st, a.dbias[l], bias_count);
             PH_TRY(check_launch("clear bias gradients"));
         }
     }
     float *clear_at = a.dbias ? nullptr : w.dbias;
-    const int64_t clear_count = a.dbias ? 0 : bias_count * L;
+    const int64_t clear_count = a.dbias ? 0 : w.dbias_at[(size_t)L];
 
     // The output error of the MSE loss (Eq. (deltaL)) is elementwise in the last layer's output, so on the MFMA
     // path that layer's update forms it in its epilogue, together with the last bias gradient and one partial
     // sum of the loss per tile: two launches less than a kernel for the error and one for the column sums.
     // The buffers it adds into are cleared by the compression launch right before it, hence the conditions.
-    const int64_t out_tiles = tiles_of(B, s) * g.groups;
-    const bool mse_in_update = train && fused_dbias && thin_compression_first(g) && out_tiles <= MSE_BLOCKS;
+    const int64_t out_tiles = tiles_of(B, g.so) * g.groups;
+    const bool mse_in_update = train && on_mfma(L - 1) && thin_compression_first(g) && out_tiles <= MSE_BLOCKS;
     OutputError oe{a.T, w.dYa, w.mse_partial, 1.0f / (float)B, dbias_of(L - 1), clear_at, clear_count};
 
     // forward through every layer; y_l stays in the storage type between layers
@@ -839,7 +882,7 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
         FwdArgs f{in, a.Lw[l], q ? a.Cw[l] : nullptr, q ? a.Dw[l] : nullptr, a.bias[l],
                   (q && !g.all) ? a.G[l] : nullptr, w.Y[l], w.G[l], w.A[l], !save_deriv, save_deriv,
                   (mse_in_update && l == L - 1) ? &oe : nullptr};
-        PH_TRY(fwd_impl<T>(g, f, st));
+        PH_TRY(fwd_impl<T>(geos[(size_t)l], f, st));
         in = w.Y[l];
     }
     if (a.Y_out) {
@@ -885,11 +928,13 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
         BwdArgs b{};
         b.send_done = send_done;
         b.below_Dw = (g.all && q > 0 && l > 0) ? a.Dw[l - 1] : nullptr;
+        b.below_g = l > 0 ? &geos[(size_t)l - 1] : nullptr;
         b.below_done = &send_done;
         b.dbias_zeroed = true;
         b.loss_tail = &loss_tail;
-        b.dbias_ready = fused_dbias && (l < L - 1 || mse_in_update);
-        b.dx_colsum = (fused_dbias && l > 0) ? dbias_of(l - 1) : nullptr;
+        // the layer's bias gradient is there already if the product that wrote its delta took the column sums
+        b.dbias_ready = l < L - 1 ? on_mfma(l + 1) : mse_in_update;
+        b.dx_colsum = (on_mfma(l) && l > 0) ? dbias_of(l - 1) : nullptr;
         b.delta_ready = dY; b.X = inputs[l];
         b.dx_S = l > 0 ? (g.act == PH_ACT_GELU ? w.A[l - 1] : w.Y[l - 1]) : nullptr;
         b.dx_S_f32 = gelu && !save_deriv;
@@ -907,7 +952,9 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
         b.ride_sgd = have_pending ? &pending : nullptr;
         b.ride_lr = a.lr;
         b.ride_sgd_done = &sgd_rode;
-        PH_TRY(bwd_impl<T>(g, b, w.bwd, st));
+        const Geo &gl = geos[(size_t)l];
+        const int64_t si = gl.si, so = gl.so, k = gl.k;
+        PH_TRY(bwd_impl<T>(gl, b, w.bwd, st));
         if (have_pending && !sgd_rode) PH_TRY(launch_sgd(pending, 4, pending_largest, pending_elems));
         have_pending = false;
 
@@ -924,10 +971,10 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
         // SGD on this layer: nothing later in the backward pass reads its weights
         struct Upd { void *w; float *master; const float *grad; int64_t count; };
         Upd upd[4] = {
-            {a.Lw[l], a.Lw_master ? a.Lw_master[l] : nullptr, b.dLw, (int64_t)g.groups * s * s},
-            {a.bias[l], a.bias_master ? a.bias_master[l] : nullptr, b.dbias, (int64_t)g.groups * s},
-            {q ? a.Cw[l] : nullptr, (q && a.Cw_master) ? a.Cw_master[l] : nullptr, b.dCw, (int64_t)g.groups * k * s},
-            {q ? a.Dw[l] : nullptr, (q && a.Dw_master) ? a.Dw_master[l] : nullptr, b.dDw, (int64_t)g.groups * q * s * k},
+            {a.Lw[l], a.Lw_master ? a.Lw_master[l] : nullptr, b.dLw, (int64_t)g.groups * so * si},
+            {a.bias[l], a.bias_master ? a.bias_master[l] : nullptr, b.dbias, (int64_t)g.groups * so},
+            {q ? a.Cw[l] : nullptr, (q && a.Cw_master) ? a.Cw_master[l] : nullptr, b.dCw, (int64_t)g.groups * k * si},
+            {q ? a.Dw[l] : nullptr, (q && a.Dw_master) ? a.Dw_master[l] : nullptr, b.dDw, (int64_t)g.groups * q * so * k},
         };
         SgdBatch batch{};
         int tensors = 0;
@@ -943,7 +990,7 @@ ph_status step_impl(const Geo &g, const ph_step_args &a, const StepWs &w, hipStr
             loss_tail.partial = nullptr;
             // The update may wait for the weight-gradient launch of the layer below and use the compute units
             // that launch leaves idle (bwd_impl decides); the first layer's has nothing to wait for.
-            if (std::is_same<T, bf16_t>::value && g.vec > 0 && l > 0) {
+            if (l > 0 && on_mfma(l - 1)) {
                 pending = batch;
                 pending_elems = total;
                 pending_largest = largest;
@@ -972,7 +1019,7 @@ ph_status check_ptr_array(const void *const *arr, int L, const char *name)
 
 extern "C" {
 
-int32_t phantom_abi_version(void) { return 1; }
+int32_t phantom_abi_version(void) { return 2; }
 
 ph_status phantom_profile_begin(int32_t max_launches)
 {
@@ -1029,11 +1076,11 @@ const char *phantom_last_error(void) { return g_err.c_str(); }
 
 ph_status phantom_workspace_bytes(const ph_problem *prob, size_t *bytes)
 {
-    Geo g;
-    PH_TRY(make_geo(prob, g));
+    std::vector<Geo> geos;
+    PH_TRY(make_geos(prob, geos));
     if (!bytes) return fail(PH_ERR_INVALID_ARG, "bytes is NULL");
     Arena a{nullptr, 0};
-    carve_step(a, g);          // the step's layout contains the backward's; the forward needs none
+    carve_step(a, geos);       // the step's layout contains the backward's; the forward needs none
     *bytes = a.used + 256;
     return PH_OK;
 }
@@ -1072,8 +1119,9 @@ ph_status phantom_layer_bwd(const ph_problem *prob, const void *dY, const void *
 ph_status phantom_ffn_step(const ph_problem *prob, const ph_step_args *args, void *workspace, size_t workspace_bytes,
                            void *hip_stream)
 {
-    Geo g;
-    PH_TRY(make_geo(prob, g));
+    std::vector<Geo> geos;
+    PH_TRY(make_geos(prob, geos));
+    const Geo &g = geos[0];
     if (!args) return fail(PH_ERR_INVALID_ARG, "args is NULL");
     const int L = g.layers;
     if (args->mode < PH_STEP_TRAIN || args->mode > PH_STEP_NO_UPDATE) return fail(PH_ERR_INVALID_ARG, "unknown step mode %d", args->mode);
@@ -1108,12 +1156,12 @@ ph_status phantom_ffn_step(const ph_problem *prob, const ph_step_args *args, voi
         if (g.q > 0 && args->dDw) PH_TRY(check_ptr_array((const void *const *)args->dDw, L, "dDw"));
     }
     Arena sizing{nullptr, 0};
-    carve_step(sizing, g);
+    carve_step(sizing, geos);
     PH_TRY(check_ws(workspace, workspace_bytes, sizing.used));
     Arena a{(char *)workspace, 0};
-    StepWs w = carve_step(a, g);
+    StepWs w = carve_step(a, geos);
     hipStream_t st = (hipStream_t)hip_stream;
-    return g.dtype == PH_F32 ? step_impl<float>(g, *args, w, st) : step_impl<bf16_t>(g, *args, w, st);
+    return g.dtype == PH_F32 ? step_impl<float>(geos, *args, w, st) : step_impl<bf16_t>(geos, *args, w, st);
 }
 
 }  // extern "C"

@@ -24,23 +24,26 @@ def test_library_exports_every_declared_symbol():
             "phantom_last_error"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
-    assert ph.abi_version() == 1
+    assert ph.abi_version() == 2
 
 
 def test_struct_layout_matches_header():
-    assert ctypes.sizeof(ph.PhProblem) == 4 * 8 + 4 * 4
+    assert ctypes.sizeof(ph.PhProblem) == 4 * 8 + 4 * 4 + 2 * 8
     from paper_2508_00960_amd.binding import PhStepArgs
     assert ctypes.sizeof(PhStepArgs) == 18 * 8 + 8
 
 
 @pytest.mark.parametrize("kwargs,fragment", [
-    (dict(n=255, p=4, k=8, batch=32), "multiple of p"),
+    (dict(n=255, p=4, k=8, batch=32), "multiples of p"),
     (dict(n=256, p=0, k=8, batch=32), "p ="),
     (dict(n=256, p=4, k=0, batch=32), "k ="),
     (dict(n=256, p=4, k=65, batch=32), "k ="),
     (dict(n=256, p=4, k=8, batch=0), "batch"),
     (dict(n=256, p=4, k=8, batch=32, rank=4), "rank"),
     (dict(n=256, p=4, k=8, batch=32, layers=0), "layers"),
+    (dict(n=256, p=4, k=8, batch=32, layers=2, widths=(256, 130, 64), ks=(8, 8)), "multiples of p"),
+    (dict(n=256, p=4, k=8, batch=32, layers=2, widths=(256, 128, 64), ks=(8, 33)), "k ="),
+    (dict(n=256, p=4, k=8, batch=32, layers=2, widths=(256, 128, 64)), "widths without ks"),
 ])
 def test_bad_problems_are_rejected(kwargs, fragment):
     prob = ph.make_problem(**kwargs)

@@ -19,7 +19,8 @@ pytestmark = pytest.mark.gpu
 
 
 def _prob_c(prob: pin.Problem):
-    return ph.make_problem(prob.n, prob.p, prob.k, prob.batch, prob.layers, prob.act, prob.dtype, prob.rank)
+    return ph.make_problem(prob.n, prob.p, prob.k, prob.batch, prob.layers, prob.act, prob.dtype, prob.rank,
+                           widths=prob.widths, ks=prob.ks)
 
 
 # ----------------------------------------------------------------------------
@@ -50,7 +51,7 @@ ONE_RANK_CASES = [
 def run_layer_one_rank(prob: pin.Problem, seed: int):
     d = pin.one_rank_layer_inputs(prob, 0, seed)
     dt, q = prob.dtype, prob.peers
-    B, s, k = prob.batch, prob.s, prob.k
+    B, si, so, k = prob.batch, prob.s_in(0), prob.s_out(0), prob.k_of(0)
     pc = _prob_c(prob)
     ws = workspace(ph.workspace_bytes(pc))
     has = q > 0
@@ -61,7 +62,7 @@ def run_layer_one_rank(prob: pin.Problem, seed: int):
     Cw = to_gpu(d["Cw"], dt) if has else None
     Dw = to_gpu(d["Dw"], dt) if has else None
     G = to_gpu(d["G"], dt) if has else None
-    Y, A = empty((B, s), dt), empty((B, s), dt)
+    Y, A = empty((B, so), dt), empty((B, so), dt)
     g_own = empty((B, k), dt) if has else None
     ph.layer_fwd(pc, X, Lw, Cw, Dw, bias, G, Y, g_own, A, ws)
     torch.cuda.synchronize()
@@ -76,10 +77,10 @@ def run_layer_one_rank(prob: pin.Problem, seed: int):
                              storage=dt)
     dY, A_gpu = to_gpu(d["dY"], dt), to_gpu(A_in, dt)
     dg_own = to_gpu(d["dg_own"], dt) if has else None
-    dX = empty((B, s), dt)
-    dLw, dbias = empty_f32((s, s)), empty_f32((s,))
-    dCw = empty_f32((k, s)) if has else None
-    dDw = empty_f32((q, s, k)) if has else None
+    dX = empty((B, si), dt)
+    dLw, dbias = empty_f32((so, si)), empty_f32((so,))
+    dCw = empty_f32((k, si)) if has else None
+    dDw = empty_f32((q, so, k)) if has else None
     dG_send = empty((q, B, k), dt) if has else None
     ph.layer_bwd(pc, dY, X, A_gpu, Lw, Cw, Dw, G, dg_own, dX, dLw, dCw, dDw, dbias, dG_send, ws)
     torch.cuda.synchronize()
@@ -93,7 +94,7 @@ def run_layer_one_rank(prob: pin.Problem, seed: int):
     if prob.act == "relu":
         # the backward accepts the layer output in place of the pre-activation
         Y_in = to_gpu(pin.round_to_storage(np.maximum(A_in, 0.0), dt), dt)
-        dX2 = empty((B, s), dt)
+        dX2 = empty((B, si), dt)
         ph.layer_bwd(pc, dY, X, Y_in, Lw, Cw, Dw, G, dg_own, dX2, dLw, dCw, dDw, dbias, dG_send, ws)
         torch.cuda.synchronize()
         assert torch.equal(dX, dX2)
@@ -104,6 +105,23 @@ def run_layer_one_rank(prob: pin.Problem, seed: int):
 def test_layer_one_rank(n, p, k, B, act, dtype, rank):
     prob = pin.Problem(n=n, p=p, k=k, batch=B, layers=1, act=act, dtype=dtype, rank=rank)
     print(f"case one-rank n={n} p={p} k={k} B={B} {act} {dtype} rank={rank}", flush=True)
+    run_layer_one_rank(prob, seed=1)
+
+
+# a layer whose input and output widths differ (Section IV, first paragraph): n_in, n_out, p, k, B, act, dtype, rank
+RECTANGULAR_CASES = [
+    (96, 160, 4, 5, 37, "gelu", "f32", 2),
+    (1024, 512, 4, 16, 200, "relu", "bf16", 1),        # narrowing: shard 256 -> 128
+    (528, 1056, 4, 24, 300, "gelu", "bf16", 3),        # widening, shards 132 -> 264: ragged in every tile dimension
+    (2048, 1024, 8, 32, 4100, "gelu", "bf16", 0),      # long batch
+    (1032, 520, 4, 6, 260, "relu", "bf16", 2),         # shards 258 -> 130, k = 6: 4-byte vectors
+]
+
+
+@pytest.mark.parametrize("n_in,n_out,p,k,B,act,dtype,rank", RECTANGULAR_CASES)
+def test_rectangular_layer_one_rank(n_in, n_out, p, k, B, act, dtype, rank):
+    print(f"case one-rank {n_in}->{n_out} p={p} k={k} B={B} {act} {dtype} rank={rank}", flush=True)
+    prob = pin.Problem(n=n_in, p=p, k=k, batch=B, layers=1, act=act, dtype=dtype, rank=rank, widths=(n_in, n_out), ks=(k,))
     run_layer_one_rank(prob, seed=1)
 
 
@@ -148,8 +166,23 @@ ALL_RANK_CASES = [
 @pytest.mark.parametrize("n,p,k,B,act,dtype", ALL_RANK_CASES)
 def test_layer_all_ranks(n, p, k, B, act, dtype):
     print(f"case all-ranks n={n} p={p} k={k} B={B} {act} {dtype}", flush=True)
-    prob = pin.Problem(n=n, p=p, k=k, batch=B, layers=1, act=act, dtype=dtype, rank=-1)
-    dt, s, q = dtype, prob.s, prob.peers
+    run_layer_all_ranks(pin.Problem(n=n, p=p, k=k, batch=B, layers=1, act=act, dtype=dtype, rank=-1))
+
+
+@pytest.mark.parametrize("n_in,n_out,p,k,B,act,dtype", [
+    (96, 160, 4, 5, 37, "gelu", "f32"),
+    (1024, 2048, 8, 16, 136, "relu", "bf16"),
+    (1584, 792, 6, 10, 70, "gelu", "bf16"),
+])
+def test_rectangular_layer_all_ranks(n_in, n_out, p, k, B, act, dtype):
+    print(f"case all-ranks {n_in}->{n_out} p={p} k={k} B={B} {act} {dtype}", flush=True)
+    run_layer_all_ranks(pin.Problem(n=n_in, p=p, k=k, batch=B, layers=1, act=act, dtype=dtype, rank=-1,
+                                    widths=(n_in, n_out), ks=(k,)))
+
+
+def run_layer_all_ranks(prob):
+    p, B, k, act, dtype = prob.p, prob.batch, prob.k_of(0), prob.act, prob.dtype
+    dt, si, so, q = dtype, prob.s_in(0), prob.s_out(0), prob.peers
     P = pin.all_rank_params(prob, 0, seed=2)
     X0, T = pin.network_io(prob, seed=2)
     Xn = pin.shard_columns(X0, p)
@@ -162,7 +195,7 @@ def test_layer_all_ranks(n, p, k, B, act, dtype):
     X, Lw, bias = to_gpu(Xn, dt), to_gpu(P["Lw"], dt), to_gpu(P["bias"], dt)
     Cw = to_gpu(P["Cw"], dt) if has else None
     Dw = to_gpu(P["Dw"], dt) if has else None
-    Y, A = empty((p, B, s), dt), empty((p, B, s), dt)
+    Y, A = empty((p, B, so), dt), empty((p, B, so), dt)
     G_full = empty((p, B, k), dt) if has else None
     ph.layer_fwd(pc, X, Lw, Cw, Dw, bias, None, Y, G_full, A, ws)
     torch.cuda.synchronize()
@@ -175,10 +208,10 @@ def test_layer_all_ranks(n, p, k, B, act, dtype):
     b_ref = oracle.all_ranks_bwd(act, dYn, Xn, A_in, P, f_ref["G_full"], dt)
     dY, A_gpu = to_gpu(dYn, dt), to_gpu(A_in, dt)
     G_in = to_gpu(f_ref["G_full"], dt) if has else None
-    dX = empty((p, B, s), dt)
-    dLw, dbias = empty_f32((p, s, s)), empty_f32((p, s))
-    dCw = empty_f32((p, k, s)) if has else None
-    dDw = empty_f32((p, q, s, k)) if has else None
+    dX = empty((p, B, si), dt)
+    dLw, dbias = empty_f32((p, so, si)), empty_f32((p, so))
+    dCw = empty_f32((p, k, si)) if has else None
+    dDw = empty_f32((p, q, so, k)) if has else None
     dG_send = empty((p, q, B, k), dt) if has else None
     dg_own = empty((p, B, k), dt) if has else None
     ph.layer_bwd(pc, dY, X, A_gpu, Lw, Cw, Dw, G_in, dg_own, dX, dLw, dCw, dDw, dbias, dG_send, ws)
@@ -215,7 +248,7 @@ def run_step(prob: pin.Problem, seed: int, lr: float, with_grads: bool = True, w
     G = [to_gpu(P["G"], dt) for P in data["layers"]] if (has and not all_ranks) else None
     dg = [to_gpu(P["dg_own"], dt) for P in data["layers"]] if (has and not all_ranks) else None
     X0, T = to_gpu(data["X0"], dt), to_gpu(data["T"], dt)
-    Y_out = empty(data["X0"].shape, dt)
+    Y_out = empty(data["T"].shape, dt)
     loss = empty_f32((4,))
     ph.ffn_step(pc, X0, T, W["Lw"], W.get("Cw"), W.get("Dw"), W["bias"],
                 Lw_master=M.get("Lw"), Cw_master=M.get("Cw"), Dw_master=M.get("Dw"), bias_master=M.get("bias"),
@@ -297,6 +330,23 @@ def test_step_without_gradient_outputs(n, p, k, B, L, act, rank):
                 moved = (M[nm][l].double().cpu().numpy() - old) / -lr
                 assert_close(f"d{nm}[{l}] (from the update, {call})", torch.from_numpy(moved), ref["grads"][l]["d" + nm], "bf16")
                 assert torch.equal(W[nm][l], M[nm][l].to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("widths,ks,p,B,act,dtype,rank", [
+    ((288, 160, 96, 224), (5, 3, 7), 4, 37, "gelu", "f32", -1),
+    ((288, 160, 96), (5, 3), 4, 37, "identity", "f32", 2),
+    ((1024, 2048, 512, 1024), (16, 32, 8), 8, 136, "gelu", "bf16", -1),     # all ranks: thin compression, fused output error, riders
+    ((2048, 1024, 3072), (32, 16), 16, 200, "gelu", "bf16", 0),             # one rank
+    ((1032, 520, 1032), (6, 2), 4, 70, "identity", "bf16", 3),              # 4-byte vectors
+    ((1056, 528, 1056), (24, 8), 8, 72, "gelu", "bf16", -1),                # shards 132, 66, 132: 4-byte vectors in the middle
+])
+def test_step_layers_of_different_widths(widths, ks, p, B, act, dtype, rank):
+    """Section IV, first paragraph: widths n_l and phantom widths k_l per layer."""
+    print(f"case step widths={widths} ks={ks} p={p} B={B} {act} {dtype} rank={rank}", flush=True)
+    prob = pin.Problem(n=widths[0], p=p, k=ks[0], batch=B, layers=len(ks), act=act, dtype=dtype, rank=rank,
+                       widths=widths, ks=ks)
+    out = run_step(prob, seed=4, lr=0.05)
+    check_step(prob, *out, 0.05)
 
 
 def test_training_several_steps_fp32():
