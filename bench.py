@@ -39,23 +39,37 @@ WORKLOADS = {
     "a16": (8192, 16, 32, 1024, 4, "relu", "bf16", -1, "no_update", 0.0),
     "a32": (8192, 32, 16, 1024, 4, "relu", "bf16", -1, "no_update", 0.0),
     "a64": (16384, 64, 8, 512, 4, "relu", "bf16", -1, "no_update", 0.0),
+    # layers of different widths and phantom widths (Section IV, first paragraph): two more entries, the widths
+    # n_0 .. n_L and k_1 .. k_L; here configuration 2 with every other layer twice as wide
+    "w4": (4096, 8, 32, 1024, 4, "relu", "bf16", -1, "no_update", 0.0, (4096, 8192, 4096, 8192, 4096), (32, 64, 32, 64)),
 }
 
 
-def flops_per_step(n, p, k, B, L, mode, groups):
-    s = n // p
-    per = B * s * (s + (p * k if p > 1 else 0))      # multiply-adds of one forward, one rank, one layer
+def layer_shapes(n, p, k, L, widths=(), ks=()):
+    """(si, so, k) of every layer: inputs and outputs held by one rank, phantom width."""
+    widths = widths or (n,) * (L + 1)
+    ks = ks or (k,) * L
+    return [(widths[l] // p, widths[l + 1] // p, ks[l]) for l in range(L)]
+
+
+def flops_per_step(shapes, p, B, mode, groups):
+    q = p - 1
+    # multiply-adds of one forward on one rank (Section IV-A): local update, decompression, compression
+    per = sum(B * (so * si + q * so * k + (k * si if q else 0)) for si, so, k in shapes)
     passes = 1 if mode == "forward" else 3           # backward costs twice the forward (Section IV-B)
-    return 2.0 * per * passes * L * groups
+    return 2.0 * per * passes * groups
 
 
-def bytes_per_step(n, p, k, B, L, mode, groups, e):
+def bytes_per_step(shapes, p, B, mode, groups, e):
     """Algorithmic bytes: every input and weight read once, every output written once, storage type."""
-    s, q = n // p, p - 1
-    W = s * s + (p * s * k if p > 1 else 0) + s
-    fwd = e * (2 * B * s + q * k * B + (B * k if q else 0) + W)
-    bwd = e * (4 * B * s + 2 * q * k * B + (B * k if q else 0) + 2 * W)
-    return float((fwd if mode == "forward" else fwd + bwd) * L * groups)
+    q = p - 1
+    total = 0
+    for si, so, k in shapes:
+        W = so * si + q * so * k + (k * si if q else 0) + so
+        fwd = e * (B * si + B * so + q * k * B + (B * k if q else 0) + W)
+        bwd = e * (2 * B * si + 2 * B * so + 2 * q * k * B + (B * k if q else 0) + 2 * W)
+        total += fwd if mode == "forward" else fwd + bwd
+    return float(total * groups)
 
 
 class Bench:
@@ -68,15 +82,19 @@ class Bench:
         import phantom_inputs as pin
         from helpers import empty, empty_f32, to_gpu, to_gpu_f32, workspace
 
-        n, p, k, B, L, act, dt, rank, mode, lr = WORKLOADS[name] if isinstance(name, str) else name
-        self.cfg = dict(n=n, p=p, k=k, batch=B, layers=L, act=act, dtype=dt, rank=rank, mode=mode, lr=lr)
+        spec = WORKLOADS[name] if isinstance(name, str) else name
+        n, p, k, B, L, act, dt, rank, mode, lr = spec[:10]
+        widths, ks = (spec[10], spec[11]) if len(spec) > 10 else ((), ())
+        self.cfg = dict(n=n, p=p, k=k, batch=B, layers=L, act=act, dtype=dt, rank=rank, mode=mode, lr=lr,
+                        widths=tuple(widths), ks=tuple(ks))
+        self.shapes = layer_shapes(n, p, k, L, widths, ks)
         self.ph, self.torch = ph, torch
-        self.prob = pin.Problem(n=n, p=p, k=k, batch=B, layers=L, act=act, dtype=dt, rank=rank)
-        self.pc = ph.make_problem(n, p, k, B, L, act, dt, rank)
+        self.prob = pin.Problem(n=n, p=p, k=k, batch=B, layers=L, act=act, dtype=dt, rank=rank, widths=tuple(widths), ks=tuple(ks))
+        self.pc = ph.make_problem(n, p, k, B, L, act, dt, rank, widths=tuple(widths), ks=tuple(ks))
         self.groups = p if rank < 0 else 1
         self.mode, self.lr = mode, lr
         self.ws = workspace(ph.workspace_bytes(self.pc))
-        s, q = n // p, p - 1
+        q = p - 1
         has = q > 0
         tdt = torch.float32 if dt == "f32" else torch.bfloat16
         lead = (p,) if rank < 0 else ()
@@ -95,20 +113,23 @@ class Bench:
                 return ((torch.rand(shape, device="cuda", generator=gen) * 2 - 1) * bound).to(tdt)
             def nrm(shape, scale=1.0):
                 return (torch.randn(shape, device="cuda", generator=gen) * scale).to(tdt)
-            shapes = {"Lw": (lead + (s, s), s ** -0.5), "bias": (lead + (s,), s ** -0.5)}
-            if has:
-                shapes["Cw"] = (lead + (k, s), s ** -0.5)
-                shapes["Dw"] = (lead + (q, s, k), k ** -0.5)
-            self.W = {nm: [uni(*shapes[nm]) for _ in range(L)] for nm in names}
-            self.G = [nrm((q, B, k)) for _ in range(L)] if (has and rank >= 0) else None
-            self.dg = [nrm((B, k), 1.0 / B) for _ in range(L)] if (has and rank >= 0) else None
-            self.X0, self.T = nrm(lead + (B, s)), nrm(lead + (B, s))
+            def layer_weights(si, so, kl):
+                shapes = {"Lw": (lead + (so, si), si ** -0.5), "bias": (lead + (so,), si ** -0.5)}
+                if has:
+                    shapes["Cw"] = (lead + (kl, si), si ** -0.5)
+                    shapes["Dw"] = (lead + (q, so, kl), kl ** -0.5)
+                return {nm: uni(*shapes[nm]) for nm in names}
+            per_layer = [layer_weights(*sh) for sh in self.shapes]
+            self.W = {nm: [d[nm] for d in per_layer] for nm in names}
+            self.G = [nrm((q, B, kl)) for _, _, kl in self.shapes] if (has and rank >= 0) else None
+            self.dg = [nrm((B, kl), 1.0 / B) for _, _, kl in self.shapes] if (has and rank >= 0) else None
+            self.X0, self.T = nrm(lead + (B, self.shapes[0][0])), nrm(lead + (B, self.shapes[-1][1]))
         self.M = None
         if dt == "bf16" and mode == "train":
             self.M = {nm: [w.float() for w in self.W[nm]] for nm in names}
         self.loss = empty_f32((4,))
-        self.flops = flops_per_step(n, p, k, B, L, mode, self.groups)
-        self.bytes = bytes_per_step(n, p, k, B, L, mode, self.groups, 4 if dt == "f32" else 2)
+        self.flops = flops_per_step(self.shapes, p, B, mode, self.groups)
+        self.bytes = bytes_per_step(self.shapes, p, B, mode, self.groups, 4 if dt == "f32" else 2)
 
     def step(self):
         W, M = self.W, self.M or {}
@@ -179,11 +200,15 @@ def kernel_table(entries, steps, esize):
         if e["K"] > 0:
             out_e = 4 if "gradients" in e["name"] or e["name"] == "compressor gradient" else esize
             flops, byts = 0.0, 0.0
-            for M, N, K in ((e["M"], e["N"], e["K"]), (e.get("M2", 0), e.get("N2", 0), e.get("K2", 0))):
+            # the third product of a launch is the error compression riding with the weight gradients: storage type out
+            for M, N, K, oe in ((e["M"], e["N"], e["K"], out_e), (e.get("M2", 0), e.get("N2", 0), e.get("K2", 0), out_e),
+                                (e.get("M3", 0), e.get("N3", 0), e.get("K3", 0), esize)):
                 flops += 2.0 * M * N * K * e["groups"]
-                byts += (esize * (M + N) * K + out_e * M * N) * e["groups"]
+                byts += (esize * (M + N) * K + oe * M * N) * e["groups"]
             if e.get("K2", 0):
                 row.update(M2=e["M2"], N2=e["N2"], K2=e["K2"])
+            if e.get("K3", 0):
+                row.update(M3=e["M3"], N3=e["N3"], K3=e["K3"])
             row.update(tflops=round(flops / avg_us * 1e-6, 2), gbs=round(byts / avg_us * 1e-3, 1),
                        flops=flops, bytes=byts)
         out.append(row)
@@ -214,7 +239,7 @@ def cpu_baseline(bench, sample_batch):
     from oracle import oracle
     c = bench.cfg
     prob = pin.Problem(n=c["n"], p=c["p"], k=c["k"], batch=sample_batch, layers=c["layers"], act=c["act"],
-                       dtype=c["dtype"], rank=c["rank"])
+                       dtype=c["dtype"], rank=c["rank"], widths=c["widths"], ks=c["ks"])
     all_ranks = c["rank"] < 0
     data = pin.all_rank_step_inputs(prob, 0) if all_ranks else pin.one_rank_step_inputs(prob, 0)
     def once():
@@ -230,7 +255,7 @@ def cpu_baseline(bench, sample_batch):
         once()
         reps += 1
     dt = (time.perf_counter() - t0) / reps
-    fl = flops_per_step(c["n"], c["p"], c["k"], sample_batch, c["layers"], c["mode"], bench.groups)
+    fl = flops_per_step(bench.shapes, c["p"], sample_batch, c["mode"], bench.groups)
     return {"value": fl / dt * 1e-12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
             "seconds": round(dt, 2), "passes": reps, "samples_per_s": sample_batch / dt,
             "sample": f"same workload with batch {sample_batch} of {c['batch']} (all layers, fp64), "
@@ -299,7 +324,8 @@ def main():
                                f"{'all ranks emulated on the GPU' if c['rank'] < 0 else 'rank %d with seeded peer buffers' % c['rank']}, "
                                f"step = {c['mode']}",
                    "launch": how, "n": c["n"], "p": c["p"], "k": c["k"], "global_batch": c["batch"],
-                   "layers": c["layers"], "activation": c["act"]},
+                   "layers": c["layers"], "activation": c["act"],
+                   **({"widths": list(c["widths"]), "ks": list(c["ks"])} if c["widths"] else {})},
         "samples_per_s": c["batch"] / ms * 1e3,
         "ms_per_step_eager": ms_eager,
         "pct_mfma_peak": 100.0 * tflops / MFMA_PEAK_TFLOPS,
@@ -312,7 +338,8 @@ def main():
 
     if not args.no_dense:
         # equal-width dense (tensor-parallel-equivalent) network through the same kernels: p = 1
-        d = Bench((c["n"], 1, 0, c["batch"], c["layers"], c["act"], c["dtype"], 0, c["mode"], c["lr"]), seeded=False)
+        d = Bench((c["n"], 1, 0, c["batch"], c["layers"], c["act"], c["dtype"], 0, c["mode"], c["lr"],
+                   c["widths"], ()), seeded=False)
         dms, dhow = d.time_steps(max(10, args.steps // 4), 5, graph=not args.no_graph)
         out["dense_equal_width"] = {"ms_per_step": dms, "tflops": d.flops / dms * 1e-9, "launch": dhow,
                                     "flop_per_step": d.flops, "phantom_speedup": dms / ms}

@@ -193,12 +193,13 @@ const char *phantom_last_error(void);
  * launches of a kernel that does nothing, reported as the entry named "(empty launch)".
  */
 typedef struct {
-    char name[40];
+    char name[64];
     int64_t M, N, K;
     int32_t groups;
     int32_t calls;
     double total_ms;
-    int64_t M2, N2, K2;   /* a launch that carries two products side by side: the second one's shape, else 0 */
+    int64_t M2, N2, K2;   /* a launch that carries two or three products side by side: the second one's shape */
+    int64_t M3, N3, K3;   /*   and the third one's, else 0 */
 } ph_profile_entry;
 
 ph_status phantom_profile_begin(int32_t max_launches);

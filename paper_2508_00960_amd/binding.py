@@ -56,9 +56,10 @@ class PhStepArgs(ctypes.Structure):
 
 class PhProfileEntry(ctypes.Structure):
     _fields_ = [
-        ("name", ctypes.c_char * 40), ("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
+        ("name", ctypes.c_char * 64), ("M", ctypes.c_int64), ("N", ctypes.c_int64), ("K", ctypes.c_int64),
         ("groups", ctypes.c_int32), ("calls", ctypes.c_int32), ("total_ms", ctypes.c_double),
         ("M2", ctypes.c_int64), ("N2", ctypes.c_int64), ("K2", ctypes.c_int64),
+        ("M3", ctypes.c_int64), ("N3", ctypes.c_int64), ("K3", ctypes.c_int64),
     ]
 
 
@@ -109,7 +110,7 @@ def profile_end(capacity: int = 256):
     count = ctypes.c_int32(0)
     _check(load().phantom_profile_end(entries, capacity, ctypes.byref(count)))
     return [dict(name=e.name.decode(), M=e.M, N=e.N, K=e.K, groups=e.groups, calls=e.calls, total_ms=e.total_ms,
-                 M2=e.M2, N2=e.N2, K2=e.K2)
+                 M2=e.M2, N2=e.N2, K2=e.K2, M3=e.M3, N3=e.N3, K3=e.K3)
             for e in entries[:count.value]]
 
 

@@ -129,7 +129,8 @@ struct ProfRec {
     const char *name;
     int64_t M, N, K;
     int groups;
-    int64_t M2, N2, K2;   // second product of a paired launch (0 if none)
+    int64_t M2, N2, K2;   // second and third product of a launch that carries several (0 if none)
+    int64_t M3, N3, K3;
 };
 struct Profiler {
     bool on = false;
@@ -147,7 +148,7 @@ struct ProfScope {
     hipStream_t st;
     long idx = -1;
     ProfScope(const char *name, int64_t M, int64_t N, int64_t K, int groups, hipStream_t s, int64_t M2 = 0,
-              int64_t N2 = 0, int64_t K2 = 0) : st(s)
+              int64_t N2 = 0, int64_t K2 = 0, int64_t M3 = 0, int64_t N3 = 0, int64_t K3 = 0) : st(s)
     {
         if (!g_prof.on) return;
         if (!g_prof.calibrated) {
@@ -157,7 +158,7 @@ struct ProfScope {
             g_prof.calibrated = true;
             for (int i = 0; i < PROF_CALIBRATION_LAUNCHES && g_prof.recs.size() < g_prof.cap; ++i) {
                 const long at = (long)g_prof.recs.size();
-                g_prof.recs.push_back(ProfRec{PROF_EMPTY_NAME, 0, 0, 0, 1, 0, 0, 0});
+                g_prof.recs.push_back(ProfRec{PROF_EMPTY_NAME, 0, 0, 0, 1, 0, 0, 0, 0, 0, 0});
                 (void)hipEventRecord(g_prof.ev[2 * at], st);
                 hipLaunchKernelGGL(fill_zero_kernel, dim3(256), dim3(256), 0, st, (float *)nullptr, (int64_t)0);
                 (void)hipEventRecord(g_prof.ev[2 * at + 1], st);
@@ -165,7 +166,7 @@ struct ProfScope {
         }
         if (g_prof.recs.size() >= g_prof.cap) return;
         idx = (long)g_prof.recs.size();
-        g_prof.recs.push_back(ProfRec{name, M, N, K, groups, M2, N2, K2});
+        g_prof.recs.push_back(ProfRec{name, M, N, K, groups, M2, N2, K2, M3, N3, K3});
         (void)hipEventRecord(g_prof.ev[2 * idx], st);
     }
     ~ProfScope()
@@ -441,7 +442,9 @@ ph_status launch_tail(const Product *head, const Product &tail0, const Product &
     tb.sgd_first = (tb.tail_first + tb.tail_wg + 7) & ~7;
     tb.sgd_wg = sgd ? sgd_wg : 0;
     if (sgd) { tb.sgd = *sgd; tb.lr = lr; }
-    ProfScope prof(what, tail0.M, tail0.N, tail0.K, groups, st, head ? head->M : 0, head ? head->N : 0, head ? head->K : 0);
+    const bool two = tail1.M > 0 && tail1.N > 0;
+    ProfScope prof(what, tail0.M, tail0.N, tail0.K, groups, st, two ? tail1.M : 0, two ? tail1.N : 0, two ? tail1.K : 0,
+                   head ? head->M : 0, head ? head->N : 0, head ? head->K : 0);
     const unsigned total = (unsigned)(tb.sgd_first + tb.sgd_wg);
     switch (vec) {
     case 8: return launch_tail_kernel<8>(tb, total, st, what);
@@ -785,7 +788,7 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
             if (with_head || with_sgd) {
                 PH_TRY(launch_tail(with_head ? &below : nullptr, dw, dc, with_sgd ? b.ride_sgd : nullptr, b.ride_lr, (int)idle,
                                    g.groups, vec, st,
-                                   with_head ? (with_sgd ? "weight + compressor gradients | error compression below | SGD above"
+                                   with_head ? (with_sgd ? "weight + compressor gradients | error compr. below | SGD above"
                                                          : "weight + compressor gradients | error compression below")
                                              : "weight + compressor gradients | SGD above"));
                 if (b.below_done) *b.below_done = with_head;
@@ -1055,7 +1058,8 @@ ph_status phantom_profile_end(ph_profile_entry *entries, int32_t capacity, int32
         for (int32_t j = 0; j < used && at < 0; ++j)
             if (!strncmp(entries[j].name, r.name, sizeof entries[j].name - 1) && entries[j].M == r.M &&
                 entries[j].N == r.N && entries[j].K == r.K && entries[j].groups == r.groups && entries[j].M2 == r.M2 &&
-                entries[j].N2 == r.N2 && entries[j].K2 == r.K2)
+                entries[j].N2 == r.N2 && entries[j].K2 == r.K2 && entries[j].M3 == r.M3 && entries[j].N3 == r.N3 &&
+                entries[j].K3 == r.K3)
                 at = j;
         if (at < 0) {
             if (used >= capacity) continue;
@@ -1064,6 +1068,7 @@ ph_status phantom_profile_end(ph_profile_entry *entries, int32_t capacity, int32
             strncpy(entries[at].name, r.name, sizeof entries[at].name - 1);
             entries[at].M = r.M; entries[at].N = r.N; entries[at].K = r.K; entries[at].groups = r.groups;
             entries[at].M2 = r.M2; entries[at].N2 = r.N2; entries[at].K2 = r.K2;
+            entries[at].M3 = r.M3; entries[at].N3 = r.N3; entries[at].K3 = r.K3;
         }
         entries[at].calls += 1;
         entries[at].total_ms += ms;

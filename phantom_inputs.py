@@ -129,7 +129,7 @@ class Problem:
 
     def __post_init__(self):
         if self.widths:
-            assert len(self.widths) == self.layers + 1 and len(self.ks) == self.layers
+            assert len(self.widths) == self.layers + 1 and (self.p == 1 or len(self.ks) == self.layers)
             assert all(w % self.p == 0 for w in self.widths)
 
     @property
