@@ -31,6 +31,7 @@
 #include "common.h"
 #include "elementwise.h"    // SgdBatch, sgd_rider
 #include "gemm_generic.h"   // Epilogue, EPI_*
+#include "thin_product.h"   // thin_workgroup
 #include "views.h"
 
 namespace phantom {
@@ -943,6 +944,37 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_tail_kernel(MfmaTailBatch tb
     } else {
         extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
         sgd_rider<__bf16>(tb.sgd, tb.lr, id - tb.sgd_first, tb.sgd_wg, MFMA_THREADS, (float *)smem_raw);
+    }
+}
+
+// One rank's forward of a layer in one launch: the thin compression g = C y (see thin_product.h) and the layer
+// update, which in one-rank mode do not depend on each other (the peers' g are inputs).  The compression's
+// workgroups come first (32 rows each, all 8 wavefronts splitting the reduction range), so they are
+// dispatched first and the update takes over their compute units as they finish.
+struct MfmaFwdBatch {
+    MfmaParams update;
+    const __bf16 *X, *C;     // compression operands: X [M, K] per group, C [N, K] per group
+    __bf16 *G;               // [M, N] per group
+    int M, N, K;
+    int64_t x_g, c_g, o_g;
+    int thin_per_group;      // workgroups of the compression per group = ceil(M / 32)
+    int thin_wg;             // = thin_per_group * groups
+    int update_first;        // thin_wg rounded up to a multiple of 8; the workgroups in between do nothing
+};
+
+template <int VEC, bool DUAL>
+__global__ __launch_bounds__(512, 1) void gemm_mfma_fwd_kernel(MfmaFwdBatch fb)
+{
+    const int id = blockIdx.x;
+    if (id < fb.update_first) {                        // uniform
+        if (id >= fb.thin_wg) return;
+        extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+        const int grp = id / fb.thin_per_group, m0 = (id - grp * fb.thin_per_group) * THIN_ROWS;
+        if (fb.N <= 32) thin_workgroup<1, 8>(fb.X, fb.C, fb.G, fb.M, fb.N, fb.K, fb.x_g, fb.c_g, fb.o_g, m0, grp, (float *)smem_raw);
+        else thin_workgroup<2, 8>(fb.X, fb.C, fb.G, fb.M, fb.N, fb.K, fb.x_g, fb.c_g, fb.o_g, m0, grp, (float *)smem_raw);
+    } else {
+        mfma_workgroup<LD_KC, LD_KC, VEC, VEC, __bf16, false, DUAL, EPI_BIAS_ACT>(
+            fb.update, xcd_order(id, fb.update_first, fb.update.total_wg));
     }
 }
 

@@ -453,6 +453,44 @@ ph_status launch_tail(const Product *head, const Product &tail0, const Product &
     }
 }
 
+// One rank's thin compression and layer update in one launch: see MfmaFwdBatch.
+template <int VEC, bool DUAL>
+ph_status launch_fwd_kernel(const MfmaFwdBatch &fb, unsigned total_wg, hipStream_t st, const char *what)
+{
+    auto kern = gemm_mfma_fwd_kernel<VEC, DUAL>;
+    static thread_local bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, MFMA_LDS_BYTES);
+        if (e != hipSuccess) return fail(PH_ERR_LAUNCH, "%s: cannot reserve %d bytes of LDS: %s", what, MFMA_LDS_BYTES,
+                                         hipGetErrorString(e));
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(total_wg), dim3(MFMA_THREADS), MFMA_LDS_BYTES, st, fb);
+    return check_launch(what);
+}
+
+ph_status launch_fwd_pair(const Product &update, const Product &compress, int groups, int vec, hipStream_t st, const char *what)
+{
+    const int64_t tiles = tiles_of(update.M, update.N) * groups;
+    if (tiles * 8 > 0x7fffffff) return fail(PH_ERR_UNSUPPORTED, "%s: too many tiles", what);
+    const bool dual = tiles > 256;                     // as for a launch of the update alone
+    MfmaFwdBatch fb{};
+    fb.update = mfma_params(update, groups, 1, dual);
+    fb.X = (const __bf16 *)compress.a.p0; fb.C = (const __bf16 *)compress.b.p0; fb.G = (__bf16 *)compress.o.p0;
+    fb.M = (int)compress.M; fb.N = (int)compress.N; fb.K = (int)compress.K;
+    fb.x_g = compress.a.g0; fb.c_g = compress.b.g0; fb.o_g = compress.o.g0;
+    fb.thin_per_group = (int)((compress.M + THIN_ROWS - 1) / THIN_ROWS);
+    fb.thin_wg = fb.thin_per_group * groups;
+    fb.update_first = (fb.thin_wg + 7) & ~7;
+    const unsigned total = (unsigned)(fb.update_first + fb.update.total_wg);
+    ProfScope prof(what, update.M, update.N, update.K, groups, st, compress.M, compress.N, compress.K);
+    switch (vec) {
+    case 8: return dual ? launch_fwd_kernel<8, true>(fb, total, st, what) : launch_fwd_kernel<8, false>(fb, total, st, what);
+    case 4: return dual ? launch_fwd_kernel<4, true>(fb, total, st, what) : launch_fwd_kernel<4, false>(fb, total, st, what);
+    default: return dual ? launch_fwd_kernel<2, true>(fb, total, st, what) : launch_fwd_kernel<2, false>(fb, total, st, what);
+    }
+}
+
 // Runs one product, or two independent ones of the same kind (names: `what` for the pair on the
 // matrix cores, `what` / `what2` when they run as separate launches of the shape-agnostic kernel).
 template <typename TIn, typename TOut>
@@ -608,6 +646,12 @@ ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
     // fit the device together
     const int64_t tiles_both = (tiles_of(B, so) + tiles_of(B, k)) * g.groups;
     if (thin && tiles_both > 256) {
+        if constexpr (std::is_same<T, bf16_t>::value) {
+            // one launch; the output error in the update's epilogue needs the compression's clear to come first
+            static const char *force = getenv("PHANTOM_FWD_PAIR");
+            if (!f.mse && !(force && force[0] == '0'))
+                return launch_fwd_pair(update, compress, g.groups, g.vec, st, "layer update + thin compression");
+        }
         PH_TRY(launch_thin());
         return launch_products<T, T>(plan, &update, 1, g.groups, st, "layer update");
     }

@@ -18,29 +18,22 @@ constexpr int THIN_MAX_N = 64;
 typedef __bf16 thin_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float thin_f32x16 __attribute__((ext_vector_type(16)));
 
-// NF = number of 32-wide column blocks (1: N <= 32, 2: N <= 64).  K is a multiple of 16.
-// x_g, c_g, o_g: element offsets per group (blockIdx.y).
-// Rider: the kernel also clears zero_count floats at `zero` (buffers that later launches of a training step
-// add into; the compression is the launch before the first of them).
-template <int NF>
-__global__ __launch_bounds__(256) void thin_product_kernel(const __bf16 *__restrict__ X, const __bf16 *__restrict__ C,
-                                                          __bf16 *__restrict__ G, int M, int N, int K,
-                                                          int64_t x_g, int64_t c_g, int64_t o_g,
-                                                          float *__restrict__ zero, int64_t zero_count)
+// One workgroup's share: rows [m0, m0 + 32) of group grp.  NF = number of 32-wide column blocks (1: N <= 32,
+// 2: N <= 64); WAVES wavefronts split the K / 16 reduction chunks (K is a multiple of 16); part: WAVES * NF * 1024
+// floats of LDS.  x_g, c_g, o_g: element offsets per group.
+template <int NF, int WAVES>
+__device__ __forceinline__ void thin_workgroup(const __bf16 *__restrict__ X, const __bf16 *__restrict__ C,
+                                               __bf16 *__restrict__ G, int M, int N, int K, int64_t x_g, int64_t c_g,
+                                               int64_t o_g, int m0, int grp, float *part)
 {
-    for (int64_t z = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x; z < zero_count;
-         z += (int64_t)gridDim.x * gridDim.y * 256)
-        zero[z] = 0.f;
-    __shared__ float part[4][NF][16][64];              // [wavefront][column block][accumulator][lane]
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int grp = blockIdx.y;
-    const int m0 = blockIdx.x * THIN_ROWS;
     const __bf16 *x = X + grp * x_g, *c = C + grp * c_g;
     __bf16 *out = G + grp * o_g;
+    auto part_at = [part](int w, int f, int e, int l) -> float & { return part[((w * NF + f) * 16 + e) * 64 + l]; };
 
     // this wavefront's share of the K / 16 reduction chunks
     const int chunks = K >> 4;
-    const int c_lo = (int)((int64_t)chunks * wave / 4), c_hi = (int)((int64_t)chunks * (wave + 1) / 4);
+    const int c_lo = (int)((int64_t)chunks * wave / WAVES), c_hi = (int)((int64_t)chunks * (wave + 1) / WAVES);
     // MFMA operand of a lane: row (lane & 31), 8 consecutive reduction indices starting at 8 * (lane >> 5).
     // Rows past the end read the last row; what they produce is never stored.
     const int half = (lane >> 5) * 8;
@@ -79,18 +72,36 @@ __global__ __launch_bounds__(256) void thin_product_kernel(const __bf16 *__restr
 #pragma unroll
     for (int f = 0; f < NF; ++f)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) part[wave][f][e][lane] = acc[f][e];
+        for (int e = 0; e < 16; ++e) part_at(wave, f, e, lane) = acc[f][e];
     __syncthreads();
 
     // accumulator e of lane l in column block f is element (row 8*(e/4) + 4*(l>>5) + e%4, column 32*f + (l&31))
-    for (int o = threadIdx.x; o < THIN_ROWS * NF * 32; o += 256) {
+    for (int o = threadIdx.x; o < THIN_ROWS * NF * 32; o += WAVES * 64) {
         const int row = o / (NF * 32), col = o - row * (NF * 32);
         const int m = m0 + row;
         if (m >= M || col >= N) continue;
         const int f = col >> 5, e = (row >> 3) * 4 + (row & 3), l = (col & 31) + 32 * ((row >> 2) & 1);
-        const float sum = (part[0][f][e][l] + part[1][f][e][l]) + (part[2][f][e][l] + part[3][f][e][l]);
+        float sum = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) sum += part_at(w, f, e, l);
         out[(int64_t)m * N + col] = (__bf16)sum;
     }
+}
+
+// The kernel: workgroup (x, y) = rows [32 x, 32 x + 32) of group y, 256 threads.
+// Rider: the kernel also clears zero_count floats at `zero` (buffers that later launches of a training step
+// add into; the compression is the launch before the first of them).
+template <int NF>
+__global__ __launch_bounds__(256) void thin_product_kernel(const __bf16 *__restrict__ X, const __bf16 *__restrict__ C,
+                                                          __bf16 *__restrict__ G, int M, int N, int K,
+                                                          int64_t x_g, int64_t c_g, int64_t o_g,
+                                                          float *__restrict__ zero, int64_t zero_count)
+{
+    for (int64_t z = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x; z < zero_count;
+         z += (int64_t)gridDim.x * gridDim.y * 256)
+        zero[z] = 0.f;
+    __shared__ float part[4 * NF * 16 * 64];           // [wavefront][column block][accumulator][lane]
+    thin_workgroup<NF, 4>(X, C, G, M, N, K, x_g, c_g, o_g, blockIdx.x * THIN_ROWS, blockIdx.y, part);
 }
 
 }  // namespace phantom
