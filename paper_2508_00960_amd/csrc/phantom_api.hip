@@ -570,7 +570,8 @@ struct FwdArgs {
 };
 
 // What the last layer's update needs to leave the output error of the MSE loss behind (Epilogue::mse_*), and
-// the buffers the compression launch before it clears on its way (they are added into from then on).
+// the buffers a thin compression launch before it clears on its way (they are added into from then on;
+// clear_count = 0: the caller has cleared them).
 struct OutputError {
     const void *target;      // [groups, B, s] storage type
     void *delta;             // [groups, B, s] storage type
@@ -581,14 +582,11 @@ struct OutputError {
     int64_t clear_count;
 };
 
-// Does the forward of this geometry run its compression as the thin kernel in a launch of its own (before the
-// update)?  Same conditions as in fwd_impl.
-bool thin_compression_first(const Geo &g)
+// Does the forward of this geometry run its compression as the thin kernel in a launch of its own before the
+// update?  (All ranks on the device, and the conditions of the thin kernel as in fwd_impl.)
+bool thin_launch_before_update(const Geo &g)
 {
-    if (g.dtype != PH_BF16 || g.q == 0 || g.k > THIN_MAX_N || g.si % 16 != 0 || g.vec == 0) return false;
-    if (g.all) return true;
-    const int64_t tiles_both = (tiles_of(g.B, g.so) + tiles_of(g.B, g.k)) * g.groups;
-    return tiles_both > 256;
+    return g.all && g.dtype == PH_BF16 && g.q > 0 && g.k <= THIN_MAX_N && g.si % 16 == 0 && g.vec > 0;
 }
 
 template <typename T>
@@ -613,7 +611,6 @@ ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
     float *clear_at = nullptr;
     int64_t clear_count = 0;
     if (f.mse) {
-        if (!thin_compression_first(g)) return fail(PH_ERR_LAUNCH, "output error in the update needs the thin compression launch");
         update.ep.mse_target = f.mse->target; update.ep.mse_delta = f.mse->delta; update.ep.mse_partial = f.mse->partial;
         update.ep.mse_inv_b = f.mse->inv_b;
         update.ep.colsum = f.mse->dbias; update.ep.colsum_g = so;
@@ -647,9 +644,8 @@ ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
     const int64_t tiles_both = (tiles_of(B, so) + tiles_of(B, k)) * g.groups;
     if (thin && tiles_both > 256) {
         if constexpr (std::is_same<T, bf16_t>::value) {
-            // one launch; the output error in the update's epilogue needs the compression's clear to come first
-            static const char *force = getenv("PHANTOM_FWD_PAIR");
-            if (!f.mse && !(force && force[0] == '0'))
+            static const char *force = getenv("PHANTOM_FWD_PAIR");     // =0: two launches (for measurements)
+            if (!(force && force[0] == '0'))
                 return launch_fwd_pair(update, compress, g.groups, g.vec, st, "layer update + thin compression");
         }
         PH_TRY(launch_thin());
@@ -829,12 +825,17 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
             }
             const int64_t idle = 256 - ((used + 7) & ~(int64_t)7);
             const bool with_sgd = allowed && b.ride_sgd && idle >= 64;
-            if (with_head || with_sgd) {
-                PH_TRY(launch_tail(with_head ? &below : nullptr, dw, dc, with_sgd ? b.ride_sgd : nullptr, b.ride_lr, (int)idle,
-                                   g.groups, vec, st,
+            // a loss that no kernel has finished yet (and no update to carry it): one more workgroup does it
+            const bool with_loss = allowed && !with_sgd && !b.ride_sgd && b.loss_tail && b.loss_tail->partial;
+            if (with_head || with_sgd || with_loss) {
+                SgdBatch loss_only{};
+                if (with_loss) loss_only.tail = take_tail();
+                PH_TRY(launch_tail(with_head ? &below : nullptr, dw, dc, with_sgd ? b.ride_sgd : with_loss ? &loss_only : nullptr,
+                                   b.ride_lr, with_sgd ? (int)idle : 1, g.groups, vec, st,
                                    with_head ? (with_sgd ? "weight + compressor gradients | error compr. below | SGD above"
                                                          : "weight + compressor gradients | error compression below")
-                                             : "weight + compressor gradients | SGD above"));
+                                             : with_sgd ? "weight + compressor gradients | SGD above"
+                                                        : "weight + compressor gradients | loss"));
                 if (b.below_done) *b.below_done = with_head;
                 if (b.ride_sgd_done) *b.ride_sgd_done = with_sgd;
                 return PH_OK;
@@ -916,10 +917,18 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
     // The output error of the MSE loss (Eq. (deltaL)) is elementwise in the last layer's output, so on the MFMA
     // path that layer's update forms it in its epilogue, together with the last bias gradient and one partial
     // sum of the loss per tile: two launches less than a kernel for the error and one for the column sums.
-    // The buffers it adds into are cleared by the compression launch right before it, hence the conditions.
+    // The buffers it adds into have to be clear by then: the thin compression launch right before it does that
+    // on its way where there is one, else a launch of its own at the start of the step.
     const int64_t out_tiles = tiles_of(B, g.so) * g.groups;
-    const bool mse_in_update = train && on_mfma(L - 1) && thin_compression_first(g) && out_tiles <= MSE_BLOCKS;
-    OutputError oe{a.T, w.dYa, w.mse_partial, 1.0f / (float)B, dbias_of(L - 1), clear_at, clear_count};
+    const bool mse_in_update = train && on_mfma(L - 1) && out_tiles <= MSE_BLOCKS;
+    const bool clear_in_compression = mse_in_update && thin_launch_before_update(g);
+    if (mse_in_update && !clear_in_compression && clear_count > 0) {
+        ProfScope prof("clear bias gradients", 0, clear_count, 0, 1, st);
+        hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks_for(clear_count)), dim3(256), 0, st, clear_at, clear_count);
+        PH_TRY(check_launch("clear bias gradients"));
+    }
+    OutputError oe{a.T, w.dYa, w.mse_partial, 1.0f / (float)B, dbias_of(L - 1), clear_in_compression ? clear_at : nullptr,
+                   clear_in_compression ? clear_count : 0};
 
     // forward through every layer; y_l stays in the storage type between layers
     const void *in = a.X0;
