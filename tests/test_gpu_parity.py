@@ -45,6 +45,8 @@ ONE_RANK_CASES = [
     (1536, 4, 16, 520, "identity", "bf16", 3),    # shard 384 = 3 tiles
     (2048, 8, 32, 4100, "gelu", "bf16", 0),       # few tiles, long batch (65 reduction steps in the weight gradients)
     (1032, 4, 6, 3000, "relu", "bf16", 1),        # the same with 4-byte vectors and ragged tiles
+    (256, 1, 0, 4100, "relu", "bf16", 0),         # p = 1, 4 tiles, 65 reduction steps: weight gradients in split pieces (atomic adds)
+    (520, 1, 0, 2100, "gelu", "bf16", 0),         # the same, ragged tiles (shard 520)
 ]
 
 

@@ -26,7 +26,7 @@ def _pins():
         ("structured dense, layers of different widths",
          lambda: pins.check_structured_dense(12, 3, 2, 5, 3, "gelu", (12, 21, 6, 15), (2, 3, 1))),
         ("identity compressor", pins.test_identity_compressor_reproduces_dense_layer),
-        ("one rank vs all ranks", lambda: pins.test_one_rank_reproduces_its_share_of_all_ranks("f32")),
+        ("one rank vs all ranks", lambda: pins.check_one_rank_vs_all_ranks("f32")),
         ("central differences", lambda: pins.check_central_differences("gelu")),
         ("concatenated operands", pins.test_concatenated_operands_give_the_same_layer),
     ]

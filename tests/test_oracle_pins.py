@@ -163,11 +163,16 @@ def test_identity_compressor_reproduces_dense_layer():
 # P3: the emulation boundary: one rank fed with the buffers of an all-ranks run
 # ----------------------------------------------------------------------------
 
-@pytest.mark.parametrize("storage", ["f32", "bf16"])
-def test_one_rank_reproduces_its_share_of_all_ranks(storage):
+@pytest.mark.parametrize("storage,widths", [("f32", ()), ("bf16", ()), ("f32", (24, 40))])
+def test_one_rank_reproduces_its_share_of_all_ranks(storage, widths):
+    check_one_rank_vs_all_ranks(storage, widths)
+
+
+def check_one_rank_vs_all_ranks(storage, widths=()):
     """Feeding rank j the gathered buffer (minus its slot) and its reduce-scatter result from an
     all-ranks run reproduces that rank's outputs exactly (same code, same order of sums)."""
-    prob = pin.Problem(n=24, p=4, k=3, batch=5, layers=1, act="gelu", dtype=storage, rank=-1)
+    prob = pin.Problem(n=24, p=4, k=3, batch=5, layers=1, act="gelu", dtype=storage, rank=-1, widths=widths,
+                       ks=(3,) if widths else ())
     P = pin.all_rank_params(prob, 0, seed=2)
     X0, T = pin.network_io(prob, seed=2)
     X = pin.shard_columns(X0, prob.p)
