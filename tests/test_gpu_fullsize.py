@@ -144,3 +144,36 @@ def test_config2_all_ranks_full_size_layer_by_layer():
     for l in range(L):
         for nm in names:
             robust(f"d{nm}[{l}]", to_np(Gd[nm][l]), ref["grads"][l]["d" + nm])
+
+
+def test_config4_training_step_full_size():
+    """n=16384, p=16 (shard 1024), k=64, batch 4096, GELU, bf16, rank 0 with seeded peer buffers, SGD: the
+    launches bench.py times for configuration 4 (thin compression and update in one launch, input gradient +
+    error compression on two tiles per workgroup, weight gradients with the update of the layer above
+    riding along).  Two layers element by element; the full eight layers in the Frobenius norm (stored
+    bf16 activations of any two implementations drift apart with depth, see the configuration-2 test),
+    the loss to 1e-3, gradients and updated master weights of every layer."""
+    import test_gpu_parity as parity
+    print("case c4 training step, 2 layers", flush=True)
+    prob = pin.Problem(n=16384, p=16, k=64, batch=4096, layers=2, act="gelu", dtype="bf16", rank=0)
+    out = parity.run_step(prob, seed=0, lr=1e-3)
+    parity.check_step(prob, *out, 1e-3)
+
+    print("case c4 training step, 8 layers", flush=True)
+    prob = pin.Problem(n=16384, p=16, k=64, batch=4096, layers=8, act="gelu", dtype="bf16", rank=0)
+    lr = 1e-3
+    data, ref, W, M, Gd, Y_out, loss = parity.run_step(prob, seed=0, lr=lr)
+    assert abs(loss - ref["loss"]) <= 1e-3 * abs(ref["loss"])
+
+    def robust(name, got, want):
+        fro = float(np.linalg.norm(got - want) / np.linalg.norm(want))
+        rms = float(np.sqrt(np.mean(want * want)))
+        off = float(np.mean(np.abs(got - want) > 2e-2 * np.maximum(np.abs(want), rms)))
+        assert fro <= 2e-2 and off <= 5e-2, f"{name}: Frobenius error {fro:.2e}, fraction beyond the bar {off:.2e}"
+
+    robust("Y_L", to_np(Y_out), ref["forward"]["Y"][-1])
+    for l in range(prob.layers):
+        for nm in W:
+            robust(f"d{nm}[{l}]", to_np(Gd[nm][l]), ref["grads"][l]["d" + nm])
+            robust(f"{nm}_master[{l}]", to_np(M[nm][l]), ref["layers"][l][nm])
+            assert torch.equal(W[nm][l], M[nm][l].to(torch.bfloat16))
