@@ -177,3 +177,34 @@ def test_config4_training_step_full_size():
             robust(f"d{nm}[{l}]", to_np(Gd[nm][l]), ref["grads"][l]["d" + nm])
             robust(f"{nm}_master[{l}]", to_np(M[nm][l]), ref["layers"][l][nm])
             assert torch.equal(W[nm][l], M[nm][l].to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("k", [16, 64, 256])
+def test_config5_forward_six_layers_full_size(k):
+    """n=8192, p=8 (shard 1024), batch 8192, 6 layers, ReLU, bf16, rank 0, forward only, as bench.py runs it:
+    the network output in the Frobenius norm (six bf16 layers deep, see the configuration-2 test), and the
+    first layer's output element by element on its first 512 rows."""
+    print(f"case c5 forward, 6 layers, k={k}", flush=True)
+    prob = pin.Problem(n=8192, p=8, k=k, batch=8192, layers=6, act="relu", dtype="bf16", rank=0)
+    data = pin.one_rank_step_inputs(prob, seed=2)
+    fw = oracle.ffn_forward("relu", data["X0"], data["layers"], "bf16", all_ranks=False)
+    pc = _prob_c(prob)
+    ws = workspace(ph.workspace_bytes(pc))
+    W = {nm: [to_gpu(P[nm], "bf16") for P in data["layers"]] for nm in ("Lw", "Cw", "Dw", "bias")}
+    G = [to_gpu(P["G"], "bf16") for P in data["layers"]]
+    X0 = to_gpu(data["X0"], "bf16")
+    Y_out = empty(data["X0"].shape, "bf16")
+    ph.ffn_step(pc, X0, None, W["Lw"], W["Cw"], W["Dw"], W["bias"], G=G, Y_out=Y_out, mode="forward", workspace=ws)
+    torch.cuda.synchronize()
+    got, want = to_np(Y_out), fw["Y"][-1]
+    fro = float(np.linalg.norm(got - want) / np.linalg.norm(want))
+    rms = float(np.sqrt(np.mean(want * want)))
+    off = float(np.mean(np.abs(got - want) > 2e-2 * np.maximum(np.abs(want), rms)))
+    assert fro <= 2e-2 and off <= 5e-2, f"Y_L: Frobenius error {fro:.2e}, fraction beyond the bar {off:.2e}"
+    # one layer deep the element-wise bar holds: the same launch on a one-layer problem
+    p1 = ph.make_problem(prob.n, prob.p, k, prob.batch, 1, "relu", "bf16", 0)
+    Y1 = empty(data["X0"].shape, "bf16")
+    ph.ffn_step(p1, X0, None, W["Lw"][:1], W["Cw"][:1], W["Dw"][:1], W["bias"][:1], G=G[:1], Y_out=Y1, mode="forward",
+                workspace=ws)
+    torch.cuda.synchronize()
+    assert_close("Y_1 (first 512 rows)", Y1[:512], fw["Y"][0][:512], "bf16")
