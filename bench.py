@@ -292,6 +292,22 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # what a plain device-to-device copy reaches on this machine (1 GiB read + 1 GiB written per pass): the measured
+    # companion of the published HBM peak that the roofline below is priced against
+    src = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device="cuda").fill_(1.0)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 10 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) * 1e-9
+    del src, dst
+
     b = Bench(args.workload)
     c = b.cfg
     ms, how = b.time_steps(args.steps, args.warmup, graph=not args.no_graph)
@@ -333,6 +349,7 @@ def main():
         "algorithmic_flop_per_step": b.flops, "algorithmic_bytes_per_step": b.bytes,
         "roofline": roof,
         "empty_launch_us": round(event_overhead_us, 3),
+        "measured_copy_gbs": round(copy_gbs, 1),
         "kernels": [{k_: v for k_, v in r.items() if k_ not in ("flops", "bytes")} for r in table],
     }
 
