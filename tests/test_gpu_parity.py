@@ -234,7 +234,7 @@ def relu_margin(fw):
     return min(float(np.min(np.abs(A)) / np.sqrt(np.mean(A * A))) for A in fw["A"])
 
 
-def run_step(prob: pin.Problem, seed: int, lr: float, with_grads: bool = True, ws=None):
+def run_step(prob: pin.Problem, seed: int, lr: float, with_grads: bool = True, ws=None, mode: str = "train"):
     dt, L, q = prob.dtype, prob.layers, prob.peers
     all_ranks = prob.rank < 0
     data = pin.all_rank_step_inputs(prob, seed) if all_ranks else pin.one_rank_step_inputs(prob, seed)
@@ -255,7 +255,7 @@ def run_step(prob: pin.Problem, seed: int, lr: float, with_grads: bool = True, w
     ph.ffn_step(pc, X0, T, W["Lw"], W.get("Cw"), W.get("Dw"), W["bias"],
                 Lw_master=M.get("Lw"), Cw_master=M.get("Cw"), Dw_master=M.get("Dw"), bias_master=M.get("bias"),
                 G=G, dg_own=dg, dLw=Gd.get("Lw"), dCw=Gd.get("Cw"), dDw=Gd.get("Dw"), dbias=Gd.get("bias"),
-                Y_out=Y_out, loss=loss, lr=lr, workspace=ws)
+                Y_out=Y_out, loss=loss, lr=lr, mode=mode, workspace=ws)
     torch.cuda.synchronize()
     return data, ref, W, M, Gd, Y_out, float(loss[0])
 
@@ -349,6 +349,25 @@ def test_step_layers_of_different_widths(widths, ks, p, B, act, dtype, rank):
                        widths=widths, ks=ks)
     out = run_step(prob, seed=4, lr=0.05)
     check_step(prob, *out, 0.05)
+
+
+@pytest.mark.parametrize("n,p,k,B,L,dtype,rank", [
+    (2048, 16, 16, 300, 2, "bf16", 3),       # one rank: nothing but the weight-gradient launch can finish the loss
+    (1024, 8, 16, 136, 2, "bf16", -1),       # all ranks: the reduce-scatter does
+    (512, 1, 0, 200, 2, "bf16", 0),          # a dense stack
+    (288, 4, 5, 37, 2, "f32", 1),
+])
+def test_step_without_update(n, p, k, B, L, dtype, rank):
+    """mode no_update: loss and gradients as in a training step, the weights left as they were."""
+    print(f"case step/no update n={n} p={p} k={k} B={B} L={L} {dtype} rank={rank}", flush=True)
+    prob = pin.Problem(n=n, p=p, k=k, batch=B, layers=L, act="gelu", dtype=dtype, rank=rank)
+    data, ref, W, M, Gd, Y_out, loss = run_step(prob, seed=6, lr=0.05, mode="no_update")
+    assert_close("Y_L", Y_out, ref["forward"]["Y"][-1], dtype)
+    assert abs(loss - ref["loss"]) <= (1e-5 if dtype == "f32" else 2e-2) * abs(ref["loss"]), (loss, ref["loss"])
+    for l in range(L):
+        for nm in W:
+            assert_close(f"d{nm}[{l}]", Gd[nm][l], ref["grads"][l]["d" + nm], dtype)
+            assert torch.equal(W[nm][l], to_gpu(data["layers"][l][nm], dtype)), f"{nm}[{l}] changed"
 
 
 def test_training_several_steps_fp32():
