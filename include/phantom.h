@@ -172,7 +172,10 @@ typedef struct {
  * backward through every layer (Eq. (backprop), (bpb)-(bpD)) and a plain SGD
  * update.  Between layers, y_l and delta_l = dLoss/dz_l are kept in the storage
  * type; delta_l is formed as (L^T delta + C^T dg_own) * sigma_l' and rounded once,
- * as Eq. (backprop) writes it (dLoss/dy_l itself is never stored).
+ * as Eq. (backprop) writes it (dLoss/dy_l itself is never stored).  With PH_BF16 and
+ * GELU the sigma_l' factor is kept between forward and backward in IEEE half
+ * precision (11 significant bits); with PH_F32 the pre-activation is kept in float.
+ * The workspace need not be cleared by the caller and holds nothing between calls.
  */
 ph_status phantom_ffn_step(const ph_problem *prob, const ph_step_args *args,
                            void *workspace, size_t workspace_bytes, void *hip_stream);
