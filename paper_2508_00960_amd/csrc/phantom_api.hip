@@ -624,10 +624,10 @@ ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
             ProfScope prof("compression", B, k, si, g.groups, st);
             dim3 grid((unsigned)((B + THIN_ROWS - 1) / THIN_ROWS), (unsigned)g.groups);
             if (k <= 32)
-                hipLaunchKernelGGL((thin_product_kernel<1>), grid, dim3(256), 0, st, (const __bf16 *)f.X, (const __bf16 *)f.Cw,
+                hipLaunchKernelGGL((thin_product_kernel<1>), grid, dim3(THIN_WAVES * 64), 0, st, (const __bf16 *)f.X, (const __bf16 *)f.Cw,
                                    (__bf16 *)f.g_own, (int)B, (int)k, (int)si, B * si, k * si, B * k, clear_at, clear_count);
             else
-                hipLaunchKernelGGL((thin_product_kernel<2>), grid, dim3(256), 0, st, (const __bf16 *)f.X, (const __bf16 *)f.Cw,
+                hipLaunchKernelGGL((thin_product_kernel<2>), grid, dim3(THIN_WAVES * 64), 0, st, (const __bf16 *)f.X, (const __bf16 *)f.Cw,
                                    (__bf16 *)f.g_own, (int)B, (int)k, (int)si, B * si, k * si, B * k, clear_at, clear_count);
             return check_launch("compression");
         }

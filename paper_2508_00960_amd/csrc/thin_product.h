@@ -14,6 +14,7 @@ namespace phantom {
 
 constexpr int THIN_ROWS = 32;       // rows of X per workgroup
 constexpr int THIN_MAX_N = 64;
+constexpr int THIN_WAVES = 8;       // wavefronts per workgroup of the stand-alone kernel
 
 typedef __bf16 thin_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float thin_f32x16 __attribute__((ext_vector_type(16)));
@@ -88,20 +89,21 @@ __device__ __forceinline__ void thin_workgroup(const __bf16 *__restrict__ X, con
     }
 }
 
-// The kernel: workgroup (x, y) = rows [32 x, 32 x + 32) of group y, 256 threads.
+// The kernel: workgroup (x, y) = rows [32 x, 32 x + 32) of group y, THIN_WAVES wavefronts.
 // Rider: the kernel also clears zero_count floats at `zero` (buffers that later launches of a training step
 // add into; the compression is the launch before the first of them).
 template <int NF>
-__global__ __launch_bounds__(256) void thin_product_kernel(const __bf16 *__restrict__ X, const __bf16 *__restrict__ C,
+__global__ __launch_bounds__(THIN_WAVES * 64) void thin_product_kernel(const __bf16 *__restrict__ X, const __bf16 *__restrict__ C,
                                                           __bf16 *__restrict__ G, int M, int N, int K,
                                                           int64_t x_g, int64_t c_g, int64_t o_g,
                                                           float *__restrict__ zero, int64_t zero_count)
 {
-    for (int64_t z = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x; z < zero_count;
-         z += (int64_t)gridDim.x * gridDim.y * 256)
+    constexpr int THREADS = THIN_WAVES * 64;
+    for (int64_t z = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * THREADS + threadIdx.x; z < zero_count;
+         z += (int64_t)gridDim.x * gridDim.y * THREADS)
         zero[z] = 0.f;
-    __shared__ float part[4 * NF * 16 * 64];           // [wavefront][column block][accumulator][lane]
-    thin_workgroup<NF, 4>(X, C, G, M, N, K, x_g, c_g, o_g, blockIdx.x * THIN_ROWS, blockIdx.y, part);
+    __shared__ float part[THIN_WAVES * NF * 16 * 64];  // [wavefront][column block][accumulator][lane]
+    thin_workgroup<NF, THIN_WAVES>(X, C, G, M, N, K, x_g, c_g, o_g, blockIdx.x * THIN_ROWS, blockIdx.y, part);
 }
 
 }  // namespace phantom
