@@ -3,7 +3,7 @@
 //
 // As a tile of the general product it has few workgroups (one per 128 rows: 64 for an 8192-row batch)
 // and every one of them walks the whole reduction range, so three quarters of the device wait for
-// 14 us.  Here a workgroup owns 32 rows and all n; its four wavefronts split the reduction range and
+// 14 us.  Here a workgroup owns 32 rows and all n; its eight wavefronts split the reduction range and
 // feed the MFMAs straight from global memory (a lane's operand is 16 contiguous bytes of one row; the
 // four 16-byte pieces of a 128-byte line are used by consecutive steps of the same wavefront, from L1),
 // then add their partial sums through LDS.  C (k x s, at most 128 KB) is read by every workgroup, from L2.
