@@ -27,6 +27,12 @@
 //
 // Workgroup ids are re-mapped so that the ids an XCD receives (id mod 8) form a contiguous range
 // of tiles: neighbouring tiles share operand panels in that XCD's L2.
+//
+// Kernels in this file, all built on mfma_workgroup (one workgroup's work on one product):
+//   gemm_mfma_kernel       one product, or two of the same operand layout and output type
+//   gemm_mfma_tail_kernel  weight + compressor gradients with riders of other layouts (the error compression of
+//                          the layer below, the SGD update of the layer above)
+//   gemm_mfma_fwd_kernel   a rank's thin compression and layer update
 #pragma once
 #include "common.h"
 #include "elementwise.h"    // SgdBatch, sgd_rider
