@@ -121,7 +121,12 @@ __global__ __launch_bounds__(256) void reduce_scatter_kernel(const T *__restrict
                                                             int p, int64_t per_slot, LossTail tail)
 {
     typedef T TV __attribute__((ext_vector_type(VEC)));
-    __shared__ float part[RS_LANES][32 * VEC + 1];
+    // part[lane][u * 40 + ev]: element u of vector ev.  A wavefront writes 32 consecutive words per sender lane, its
+    // two sender lanes 32 banks apart; the 64 threads of a wavefront read 8 u-rows x 8 vectors, and the rows start
+    // 40 words = 8 banks mod 64 apart in a permuted order (with rows of 32 * VEC + 1 words indexed [ev * VEC + u]
+    // the writes met each bank four times: SQ_LDS_BANK_CONFLICT 448 cycles per workgroup, now 64)
+    constexpr int RS_U_PITCH = 40, RS_LANE_PITCH = VEC * RS_U_PITCH + 32;
+    __shared__ float part[RS_LANES * RS_LANE_PITCH];
     const int ev = threadIdx.x & 31, lane = threadIdx.x >> 5;
     const int64_t e = ((int64_t)blockIdx.x * 32 + ev) * VEC;
     const int i = blockIdx.y;
@@ -143,7 +148,7 @@ __global__ __launch_bounds__(256) void reduce_scatter_kernel(const T *__restrict
         }
     }
 #pragma unroll
-    for (int u = 0; u < VEC; ++u) part[lane][ev * VEC + u] = acc[u];
+    for (int u = 0; u < VEC; ++u) part[lane * RS_LANE_PITCH + u * RS_U_PITCH + ev] = acc[u];
     __syncthreads();
     // 256 threads, 32 * VEC elements: thread t finishes elements t, t + 256, ...
     for (int c = threadIdx.x; c < 32 * VEC; c += 256) {
@@ -151,7 +156,7 @@ __global__ __launch_bounds__(256) void reduce_scatter_kernel(const T *__restrict
         if (at >= per_slot) continue;
         float sum = 0.f;
 #pragma unroll
-        for (int g = 0; g < RS_LANES; ++g) sum += part[g][c];
+        for (int g = 0; g < RS_LANES; ++g) sum += part[g * RS_LANE_PITCH + (c % VEC) * RS_U_PITCH + c / VEC];
         dg_own[(int64_t)i * per_slot + at] = from_f32<T>(sum);
     }
     __shared__ float lred[256];
