@@ -67,6 +67,11 @@ typedef enum { PH_F32 = 0, PH_BF16 = 1 } ph_dtype;
  * bias [so]; wherever a shape below says s, read si for the layer's input side (X, dX, columns of Lw and
  * Cw) and so for its output side (Y, A, dY, bias, rows of Lw and Dw).  n and k are ignored when widths
  * is given.  The single-layer calls use widths[0], widths[1], ks[0].
+ *
+ * Size limits (PH_ERR_UNSUPPORTED beyond them): batch and every n_l/p at most 2^22, n_l/p + (p-1) k_l at most
+ * 2^24, p at most 65535.  A bf16 problem in which one rank's share of a tensor ([B, n_l/p] activations, the
+ * [p-1 or p, B, k] gathered buffer, a weight block) has more than 2^31 - 1 elements runs on the slower
+ * shape-agnostic kernels (as one whose n_l/p or k_l is odd does); results are the same.
  */
 typedef struct {
     int64_t n;        /* layer width; n % p == 0 */

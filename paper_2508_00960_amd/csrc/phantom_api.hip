@@ -89,6 +89,14 @@ ph_status make_geo(const ph_problem *pr, Geo &g, int layer = 0)
         for (int v = 8; v >= 2 && !g.vec; v >>= 1)
             if (si % v == 0 && so % v == 0 && (g.q == 0 || g.k % v == 0)) g.vec = v;
     }
+    // The matrix-core kernels address an operand with 32-bit element offsets inside one rank's share of a tensor:
+    // a problem with a larger tensor goes through the shape-agnostic kernels (64-bit offsets) like one whose widths
+    // allow no vector loads.
+    {
+        const int64_t wide = std::max(si, so), slots = g.all ? g.p : g.q;
+        const int64_t largest = std::max({g.B * wide, slots * g.B * g.k, so * si, slots * so * g.k, g.k * si});
+        if (largest > 0x7fffffff) g.vec = 0;
+    }
     // index arithmetic inside the kernels uses 32-bit row/column numbers and a 3-D grid
     if (g.B > (1 << 22) || si > (1 << 22) || so > (1 << 22) || g.Kc > (1 << 24) || so + g.q * g.k > (1 << 24) || g.p > 65535)
         return fail(PH_ERR_UNSUPPORTED, "problem too large for 32-bit tile indices (batch, n/p <= 2^22, n/p+(p-1)k <= 2^24)");

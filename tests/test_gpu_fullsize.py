@@ -208,3 +208,28 @@ def test_config5_forward_six_layers_full_size(k):
                 workspace=ws)
     torch.cuda.synchronize()
     assert_close("Y_1 (first 512 rows)", Y1[:512], fw["Y"][0][:512], "bf16")
+
+
+def test_tensor_beyond_32_bit_offsets_forward_sampled_rows():
+    """A dense layer (p = 1) 1032 -> 8 on 2^21 + 4096 batch rows: the input has more than 2^31 elements, past what
+    the matrix-core kernels address, so the call takes the kernels with 64-bit offsets.  The input is drawn on the
+    device (17 GB as float64 on the host otherwise); rows sampled from the whole range, the last rows among
+    them, go to the oracle."""
+    print("case 32-bit offsets: B = 2^21 + 4096, 1032 -> 8, p = 1, bf16", flush=True)
+    B, si, so = 2**21 + 4096, 1032, 8
+    assert B * si > 2**31
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    X = torch.randn((B, si), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    rng = np.random.default_rng(5)
+    Lw = pin.round_to_storage(rng.standard_normal((so, si)) / np.sqrt(si), "bf16")
+    bias = pin.round_to_storage(0.1 * rng.standard_normal(so), "bf16")
+    pc = ph.make_problem(si, 1, 0, B, 1, "gelu", "bf16", 0, widths=(si, so), ks=())
+    ws = workspace(ph.workspace_bytes(pc))
+    Y, A = empty((B, so), "bf16"), empty((B, so), "bf16")
+    ph.layer_fwd(pc, X, to_gpu(Lw, "bf16"), None, None, to_gpu(bias, "bf16"), None, Y, None, A, ws)
+    torch.cuda.synchronize()
+    idx = np.unique(np.concatenate([np.arange(4), np.arange(B - 64, B), rng.choice(B, 192, replace=False)]))
+    sel = torch.from_numpy(idx).cuda()
+    f = oracle.layer_fwd("gelu", X[sel].to(torch.float64).cpu().numpy(), Lw, None, None, bias, None)
+    assert_close("Y", Y[sel], f["Y"], "bf16")
+    assert_close("A_save", A[sel], f["A"], "bf16")
