@@ -96,6 +96,9 @@ ph_status make_geo(const ph_problem *pr, Geo &g, int layer = 0)
         const int64_t wide = std::max(si, so), slots = g.all ? g.p : g.q;
         const int64_t largest = std::max({g.B * wide, slots * g.B * g.k, so * si, slots * so * g.k, g.k * si});
         if (largest > 0x7fffffff) g.vec = 0;
+        // they also divide a position among the peers' segments by k with a multiply (Axis::magic), exact while
+        // position * k < 2^32
+        if (g.q * g.k * g.k >= (int64_t)1 << 32) g.vec = 0;
     }
     // index arithmetic inside the kernels uses 32-bit row/column numbers and a 3-D grid
     if (g.B > (1 << 22) || si > (1 << 22) || so > (1 << 22) || g.Kc > (1 << 24) || so + g.q * g.k > (1 << 24) || g.p > 65535)
