@@ -3,7 +3,10 @@
 Every function has the name and argument order of its C entry point in
 include/phantom.h.  Tensor arguments are torch tensors on the GPU (their
 data_ptr() is passed), None (NULL), or plain integers (raw addresses, used by
-the host-only argument-validation tests).  Nothing is computed here.
+the host-only argument-validation tests).  A tensor is checked against the
+problem's shapes before the call (device memory, contiguous, element size, at
+least as many elements as the argument has): the library sees an address only.
+Nothing is computed here.
 """
 from __future__ import annotations
 
@@ -143,6 +146,49 @@ def _ptr(t) -> Optional[int]:
     return t.data_ptr()
 
 
+def _layer_shape(prob: PhProblem, layer: int):
+    """(si, so, k) of one layer per rank: inputs, outputs, phantom width."""
+    if prob.widths:
+        si, so = prob.widths[layer] // prob.p, prob.widths[layer + 1] // prob.p
+        k = prob.ks[layer] if prob.ks else prob.k
+    else:
+        si = so = prob.n // prob.p
+        k = prob.k
+    return si, so, (k if prob.p > 1 else 0)
+
+
+def _expect(name: str, t, elems: int, elem_bytes: int) -> None:
+    """A tensor handed over for `name` must live on the GPU, be contiguous and hold at least `elems` elements of
+    `elem_bytes` bytes: the library sees an address only and would read or write past a shorter buffer.  Raw
+    addresses and None pass through (the library checks for NULL where an argument is required)."""
+    if t is None or isinstance(t, int) or elems <= 0:
+        return
+    if not t.is_cuda:
+        raise ValueError(f"{name}: tensor is on {t.device}, the library needs device memory")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: tensor is not contiguous")
+    if t.element_size() != elem_bytes:
+        raise ValueError(f"{name}: elements of {t.element_size()} bytes, {elem_bytes} expected ({t.dtype})")
+    if t.numel() < elems:
+        raise ValueError(f"{name}: {t.numel()} elements, the problem needs {elems}")
+
+
+def _check_layer_tensors(prob: PhProblem, layer: int, named: dict) -> None:
+    """named: argument name -> (tensor, kind); kind says which of the layer's shapes the argument has."""
+    si, so, k = _layer_shape(prob, layer)
+    B, q = prob.batch, prob.p - 1
+    groups = prob.p if prob.rank < 0 else 1
+    esz = 2 if prob.dtype == DTYPES["bf16"] else 4
+    counts = {
+        "in": groups * B * si, "out": groups * B * so, "L": groups * so * si, "C": groups * k * si,
+        "D": groups * q * so * k, "b": groups * so, "g": groups * B * k, "send": groups * q * B * k,
+        "gathered": (prob.p if prob.rank < 0 else q) * B * k, "scalar": 1,
+    }
+    for name, (t, kind) in named.items():
+        grad = kind.endswith("32")                      # gradients, master weights, the loss: float
+        _expect(name, t, counts[kind[:-2] if grad else kind], 4 if grad else esz)
+
+
 def _nbytes(t) -> int:
     if t is None:
         return 0
@@ -182,6 +228,9 @@ def workspace_bytes(prob: PhProblem) -> int:
 
 def layer_fwd(prob, X, Lw, Cw, Dw, bias, G, Y, g_own, A_save, workspace=None, stream=None):
     wp, wb = _ws(workspace)
+    _check_layer_tensors(prob, 0, {"X": (X, "in"), "Lw": (Lw, "L"), "Cw": (Cw, "C"), "Dw": (Dw, "D"), "bias": (bias, "b"),
+                                   "G": (G if prob.rank >= 0 else None, "gathered"), "Y": (Y, "out"),
+                                   "g_own": (g_own, "g"), "A_save": (A_save, "out")})
     _check(load().phantom_layer_fwd(ctypes.byref(prob), _ptr(X), _ptr(Lw), _ptr(Cw), _ptr(Dw), _ptr(bias), _ptr(G),
                                     _ptr(Y), _ptr(g_own), _ptr(A_save), wp, wb, _stream(stream)))
 
@@ -189,6 +238,10 @@ def layer_fwd(prob, X, Lw, Cw, Dw, bias, G, Y, g_own, A_save, workspace=None, st
 def layer_bwd(prob, dY, X, A_or_Y, Lw, Cw, Dw, G, dg_own, dX, dLw, dCw, dDw, dbias, dG_send, workspace=None,
               stream=None):
     wp, wb = _ws(workspace)
+    _check_layer_tensors(prob, 0, {"dY": (dY, "out"), "X": (X, "in"), "A_or_Y": (A_or_Y, "out"), "Lw": (Lw, "L"),
+                                   "Cw": (Cw, "C"), "Dw": (Dw, "D"), "G": (G, "gathered"), "dg_own": (dg_own, "g"),
+                                   "dX": (dX, "in"), "dLw": (dLw, "L32"), "dCw": (dCw, "C32"), "dDw": (dDw, "D32"),
+                                   "dbias": (dbias, "b32"), "dG_send": (dG_send, "send")})
     _check(load().phantom_layer_bwd(ctypes.byref(prob), _ptr(dY), _ptr(X), _ptr(A_or_Y), _ptr(Lw), _ptr(Cw), _ptr(Dw),
                                     _ptr(G), _ptr(dg_own), _ptr(dX), _ptr(dLw), _ptr(dCw), _ptr(dDw), _ptr(dbias),
                                     _ptr(dG_send), wp, wb, _stream(stream)))
@@ -209,6 +262,19 @@ def ffn_step(prob, X0, T, Lw, Cw, Dw, bias, *, Lw_master=None, Cw_master=None, D
     """phantom_ffn_step; per-layer arguments are sequences of prob.layers tensors (or None)."""
     L = prob.layers
     keep = []
+    kinds = {"Lw": "L", "Cw": "C", "Dw": "D", "bias": "b", "Lw_master": "L32", "Cw_master": "C32", "Dw_master": "D32",
+             "bias_master": "b32", "G": "gathered", "dg_own": "g", "dLw": "L32", "dCw": "C32", "dDw": "D32", "dbias": "b32"}
+    per_layer = {"Lw": Lw, "Cw": Cw, "Dw": Dw, "bias": bias, "Lw_master": Lw_master, "Cw_master": Cw_master,
+                 "Dw_master": Dw_master, "bias_master": bias_master, "G": G, "dg_own": dg_own, "dLw": dLw, "dCw": dCw,
+                 "dDw": dDw, "dbias": dbias}
+    for layer in range(L):
+        named = {f"{name}[{layer}]": (val[layer], kinds[name]) for name, val in per_layer.items()
+                 if val is not None and len(val) == L and not (prob.rank < 0 and name in ("G", "dg_own"))}
+        if layer == 0:
+            named["X0"] = (X0, "in")
+        if layer == L - 1:
+            named.update({"T": (T, "out"), "Y_out": (Y_out, "out"), "loss": (loss, "scalar32")})
+        _check_layer_tensors(prob, layer, named)
     args = PhStepArgs()
     args.X0, args.T, args.Y_out, args.loss = _ptr(X0), _ptr(T), _ptr(Y_out), _ptr(loss)
     for name, val in (("Lw", Lw), ("Cw", Cw), ("Dw", Dw), ("bias", bias), ("Lw_master", Lw_master),

@@ -96,3 +96,12 @@ def test_workspace_grows_with_the_problem():
     small = ph.workspace_bytes(ph.make_problem(256, 4, 8, 32, layers=2))
     big = ph.workspace_bytes(ph.make_problem(4096, 8, 32, 1024, layers=4, dtype="bf16", rank=-1))
     assert 0 < small < big
+
+
+def test_binding_refuses_host_tensors():
+    """The library gets addresses only: the binding stops a tensor that is not device memory before the call."""
+    import torch
+    prob = ph.make_problem(256, 4, 8, 32)
+    ok = 0x1000
+    with pytest.raises(ValueError, match="X: tensor is on cpu"):
+        ph.layer_fwd(prob, torch.zeros(32, 64), ok, ok, ok, ok, ok, ok, ok, None)

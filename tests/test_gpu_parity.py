@@ -414,3 +414,22 @@ def test_step_forward_only():
                 mode="forward", workspace=ws)
     torch.cuda.synchronize()
     assert_close("Y_L", Y_out, fw["Y"][-1], "bf16")
+
+
+def test_binding_refuses_short_and_mistyped_tensors():
+    """A buffer shorter than the problem's shape, of the wrong element size or not contiguous never reaches the library."""
+    prob = ph.make_problem(256, 4, 8, 32, dtype="bf16")
+    B, s, k, q = 32, 64, 8, 3
+    X, Lw, Cw, Dw = empty((B, s), "bf16"), empty((s, s), "bf16"), empty((k, s), "bf16"), empty((q, s, k), "bf16")
+    bias, G, Y, g_own = empty((s,), "bf16"), empty((q, B, k), "bf16"), empty((B, s), "bf16"), empty((B, k), "bf16")
+    ws = workspace(ph.workspace_bytes(prob))
+    with pytest.raises(ValueError, match="Y: 1984 elements, the problem needs 2048"):
+        ph.layer_fwd(prob, X, Lw, Cw, Dw, bias, G, empty((B - 1, s), "bf16"), g_own, None, ws)
+    with pytest.raises(ValueError, match="Lw: elements of 4 bytes, 2 expected"):
+        ph.layer_fwd(prob, X, empty((s, s), "f32"), Cw, Dw, bias, G, Y, g_own, None, ws)
+    with pytest.raises(ValueError, match="X: tensor is not contiguous"):
+        ph.layer_fwd(prob, empty((s, B), "bf16").t(), Lw, Cw, Dw, bias, G, Y, g_own, None, ws)
+    with pytest.raises(ValueError, match=r"dLw\[1\]: elements of 2 bytes, 4 expected"):
+        two = ph.make_problem(256, 4, 8, 32, layers=2, dtype="bf16")
+        ph.ffn_step(two, X, Y, [Lw, Lw], [Cw, Cw], [Dw, Dw], [bias, bias], G=[G, G], dg_own=[g_own, g_own],
+                    dLw=[empty_f32((s, s)), Lw], mode="no_update", workspace=ws)
