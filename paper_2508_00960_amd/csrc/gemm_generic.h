@@ -68,7 +68,10 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(View va, View vb, Vie
         rb[i] = locate(vb.r, n < N ? n : 0, skip_b);
     }
 
-    float acc[4][4] = {};
+    // Three levels of partial sums (16 terms, 16 of those, the rest): a single running fp32 sum over a reduction
+    // range of several thousand (a weight gradient over the batch) drifts past 1e-5 of the result.
+    float acc[4][4] = {}, mid[4][4] = {};
+    int steps_in_mid = 0;
     for (int k0 = 0; k0 < K; k0 += GK) {
         const int kk = k0 + lk;
         const bool kin = kk < K;
@@ -89,6 +92,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(View va, View vb, Vie
             Bs[lk][lr + 16 * i] = bv;
         }
         __syncthreads();
+        float part[4][4] = {};
 #pragma unroll
         for (int q = 0; q < GK; ++q) {
             float av[4], bv[4];
@@ -97,10 +101,23 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(View va, View vb, Vie
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(av[i], bv[j], acc[i][j]);
+                for (int j = 0; j < 4; ++j) part[i][j] = fmaf(av[i], bv[j], part[i][j]);
         }
+        const bool flush = ++steps_in_mid == 16;       // uniform
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                mid[i][j] += part[i][j];
+                if (flush) { acc[i][j] += mid[i][j]; mid[i][j] = 0.f; }
+            }
+        if (flush) steps_in_mid = 0;
         __syncthreads();
     }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] += mid[i][j];
 
     TOut *o0 = (TOut *)vo.p0 + g * vo.g0, *o1 = (TOut *)vo.p1 + g * vo.g1;
     const int skip_o = vo.skip0 + g * vo.skip_g;
