@@ -834,10 +834,24 @@ __device__ __forceinline__ void mfma_workgroup(const MfmaParams &P, int wg)
     if (regular) {                                                  // uniform (in DUAL for both teams alike)
         const int c_last = kfirst + (my_steps - 1) * KS;            // start of the tile processed first
         auto c_of = [c_last](int i) { return c_last - i * KS; };    // tile processed in step i (i < my_steps)
-        if (my_steps > 0) PH_FETCH(0, c_of(0));
-        if (my_steps > 1) PH_FETCH(1, c_of(1));
-        if (my_steps > 0) PH_STORE(0, 0, c_of(0));
-        if (my_steps > 2) PH_FETCH(0, c_of(2));
+        // only that first tile needs the careful loader (clamped indices, zeroed tail: some 30 vector instructions
+        // per fetch and operand); a full one and the two tiles behind it take the loop's own addressing
+#define PH_FETCH_FAST(set, c0) do { \
+        const FastStep fa_ = fast_step_addr<KA, VA>(sa, (c0)), fb_ = fast_step_addr<KB, VB>(sb, (c0)); \
+        fast_fetch<KA, VA, 1, 0, SA::NV>(fa_, a_off0, a_off1, ra##set); \
+        fast_fetch<KB, VB, BP, 0, SB::NV>(fb_, b_off0, b_off1, rb##set); } while (0)
+        const bool ragged_first = my_steps > 0 && c_of(0) + KT > k_end;     // the same for the whole team
+        if (ragged_first) PH_FETCH(0, c_of(0));
+        else if (my_steps > 0) PH_FETCH_FAST(0, c_of(0));
+        if (my_steps > 1) PH_FETCH_FAST(1, c_of(1));
+        if (ragged_first) {
+            PH_STORE(0, 0, c_of(0));
+        } else if (my_steps > 0) {
+            stage_store<KA, VA, false>(sa, ra0, s0a, 0);
+            stage_store<KB, VB, false, BP>(sb, rb0, s0b, 0);
+        }
+        if (my_steps > 2) PH_FETCH_FAST(0, c_of(2));
+#undef PH_FETCH_FAST
         __syncthreads();
         PH_PHASE(2);
         // step i multiplies LDS stage i%2; on entry tile i+1 sits in register set (i+1)%2 and is moved to the other
