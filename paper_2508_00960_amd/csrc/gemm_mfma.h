@@ -932,6 +932,9 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
 //  - head, all ranks on the device: the error compression of the layer below (input-gradient layout, storage
 //    type out), which fills half of the device or less for a short while.  It runs in the workgroups
 //    [0, head_wg) so that it is dispatched first and frees its compute units early.
+//    One rank, first layer (no input gradient to share a launch with): the layer's own error compression.  Nothing
+//    waits for it, so with more workgroups than compute units it goes out last (rotate) and fills in behind the
+//    longer weight-gradient workgroups.
 //  - the SGD update of the layer above (sgd_wg workgroups from sgd_first on) on compute units that the
 //    products leave idle; its gradients sit in other buffers than the ones tail[] writes.
 // tail_first and sgd_first are multiples of 8; workgroups in the gaps do nothing.
@@ -945,12 +948,15 @@ struct MfmaTailBatch {
     int tail_wg;         // = tail[0].total_wg + tail[1].total_wg
     int sgd_first;
     int sgd_wg;          // 0: no update
+    int rotate;          // workgroup b does the work of number (b + rotate) mod the grid size: rotate = tail_first
+                         //   sends the head's workgroups out last instead of first
 };
 
 template <int VEC>
 __global__ __launch_bounds__(512, 1) void gemm_mfma_tail_kernel(MfmaTailBatch tb)
 {
-    const int id = blockIdx.x;
+    int id = (int)blockIdx.x + tb.rotate;
+    if (id >= (int)gridDim.x) id -= (int)gridDim.x;
     if (id < tb.tail_first) {                          // uniform, like every branch here
         if (id >= tb.head_wg) return;
         mfma_workgroup<LD_KC, LD_KM, VEC, VEC, __bf16, false, false, EPI_STORE>(tb.head, xcd_order(id, 0, tb.head_wg));

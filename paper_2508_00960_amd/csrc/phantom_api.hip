@@ -438,7 +438,7 @@ ph_status launch_tail_kernel(const MfmaTailBatch &tb, unsigned total_wg, hipStre
 }
 
 ph_status launch_tail(const Product *head, const Product &tail0, const Product &tail1, const SgdBatch *sgd, float lr,
-                      int sgd_wg, int groups, int vec, hipStream_t st, const char *what)
+                      int sgd_wg, int groups, int vec, hipStream_t st, const char *what, bool head_last = false)
 {
     MfmaTailBatch tb{};
     if (head) tb.head = mfma_params(*head, groups, 1, false);
@@ -457,6 +457,7 @@ ph_status launch_tail(const Product *head, const Product &tail0, const Product &
     ProfScope prof(what, tail0.M, tail0.N, tail0.K, groups, st, two ? tail1.M : 0, two ? tail1.N : 0, two ? tail1.K : 0,
                    head ? head->M : 0, head ? head->N : 0, head ? head->K : 0);
     const unsigned total = (unsigned)(tb.sgd_first + tb.sgd_wg);
+    tb.rotate = (head && head_last) ? tb.tail_first : 0;
     switch (vec) {
     case 8: return launch_tail_kernel<8>(tb, total, st, what);
     case 4: return launch_tail_kernel<4>(tb, total, st, what);
@@ -771,6 +772,28 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
     dx.ep.colsum = b.dx_colsum; dx.ep.colsum_g = si;
     dx.M = b.dX ? B : 0; dx.N = si; dx.K = so + k;
 
+    // weight gradients: [dL | dD_1 .. dD_{p-1}] = delta^T . [X | G_1 .. G_{p-1}], and dC = dg_own^T . X beside it
+    Product dw{};
+    dw.a = view_plain_t(delta, so, B * so);
+    dw.b = q > 0 ? view_rowseg_t(b.X, si, (int)si, B * si, b.G, (int)k, B * k, 0, g.all ? 0 : NO_SKIP, g.all ? 1 : 0)
+                 : view_plain_t(b.X, si, B * si);
+    dw.o.p0 = b.dLw; dw.o.p1 = b.dDw; dw.o.g0 = so * si; dw.o.g1 = q * so * k;
+    dw.o.r = axis_plain(si, k);
+    dw.o.c = q > 0 ? axis_seg((int)si, (int)k, 1, 1, so * k) : axis_plain(1, 0);
+    dw.o.skip0 = NO_SKIP; dw.o.skip_g = 0;
+    dw.ep = epi_store();
+    dw.M = so; dw.N = g.Kc; dw.K = B;
+    Product dc{view_plain_t(b.dg_own, k, B * k), view_plain_t(b.X, si, B * si), view_plain(b.dCw, si, k * si), epi_store(),
+               q > 0 ? k : 0, si, B};
+    // Riders of the weight-gradient launch (MfmaTailBatch) exist on the matrix-core path for launches of at most one
+    // tile per compute unit.  PHANTOM_TAIL=0 switches them off (for measurements).
+    const int64_t tail_tiles = (tiles_of(dw.M, dw.N) + tiles_of(dc.M, dc.N)) * g.groups;
+    static const char *tail_force = getenv("PHANTOM_TAIL");
+    const bool riders = std::is_same<T, bf16_t>::value && g.vec > 0 && tail_tiles <= 256 && !(tail_force && tail_force[0] == '0');
+    // One rank, no input gradient wanted (the first layer): this layer's error compression has no launch to share
+    // with the input gradient and nothing waits for it, so it rides with the weight gradients.
+    const bool send_rides = riders && !g.all && !b.dX && q > 0;
+
     const GemmPlan plan_x{LD_KC, LD_KM, g.vec, false};
     if (g.all) {
         // the input gradient needs dg_own, which is the sum of what all ranks send: three launches
@@ -791,63 +814,56 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
             PH_TRY(check_launch("reduce-scatter"));
         }
         PH_TRY((launch_products<T, T>(plan_x, &dx, 1, g.groups, st, "input gradient")));
-    } else {
+    } else if (!send_rides) {
         Product both[2] = {dx, send};
         PH_TRY((launch_products<T, T>(plan_x, both, 2, g.groups, st, "input gradient + error compression",
                                       "input gradient", "error compression")));
     }
 
-    // weight gradients: [dL | dD_1 .. dD_{p-1}] = delta^T . [X | G_1 .. G_{p-1}], and dC = dg_own^T . X beside it
-    Product dw{};
-    dw.a = view_plain_t(delta, so, B * so);
-    dw.b = q > 0 ? view_rowseg_t(b.X, si, (int)si, B * si, b.G, (int)k, B * k, 0, g.all ? 0 : NO_SKIP, g.all ? 1 : 0)
-                 : view_plain_t(b.X, si, B * si);
-    dw.o.p0 = b.dLw; dw.o.p1 = b.dDw; dw.o.g0 = so * si; dw.o.g1 = q * so * k;
-    dw.o.r = axis_plain(si, k);
-    dw.o.c = q > 0 ? axis_seg((int)si, (int)k, 1, 1, so * k) : axis_plain(1, 0);
-    dw.o.skip0 = NO_SKIP; dw.o.skip_g = 0;
-    dw.ep = epi_store();
-    dw.M = so; dw.N = g.Kc; dw.K = B;
-    Product dc{view_plain_t(b.dg_own, k, B * k), view_plain_t(b.X, si, B * si), view_plain(b.dCw, si, k * si), epi_store(),
-               q > 0 ? k : 0, si, B};
     Product grads[2] = {dw, dc};
     if (b.below_done) *b.below_done = false;
     if (b.ride_sgd_done) *b.ride_sgd_done = false;
     if constexpr (std::is_same<T, bf16_t>::value) {
-        const int64_t tail_tiles = (tiles_of(dw.M, dw.N) + tiles_of(dc.M, dc.N)) * g.groups;
-        if (g.vec > 0 && tail_tiles <= 256) {
-            // Riders of the weight-gradient launch (MfmaTailBatch).  The layer below starts its backward with an
-            // error compression that fills half of the device or less for a short while: it comes along when it
-            // leaves at least half of the compute units to the weight gradients from the start (they take over
-            // the rest as it finishes).  The update of the layer above comes along when at least a quarter of the
-            // compute units would otherwise be idle.  PHANTOM_TAIL=0 switches both off (for measurements).
-            static const char *force = getenv("PHANTOM_TAIL");
-            const bool allowed = !(force && force[0] == '0');
+        if (riders) {
+            // The layer below starts its backward with an error compression that fills half of the device or less
+            // for a short while: it comes along when it leaves at least half of the compute units to the weight
+            // gradients from the start (they take over the rest as it finishes).  The update of the layer above
+            // comes along when at least a quarter of the compute units would otherwise be idle.
             Product below{};
             bool with_head = false;
             int64_t used = tail_tiles;
             int vec = g.vec;
-            if (allowed && b.below_Dw && b.below_g && b.below_g->vec > 0 && b.dX && g.all && q > 0) {
+            if (send_rides) {
+                below = send;
+                with_head = true;
+                used += (tiles_of(below.M, below.N) * g.groups + 7) & ~(int64_t)7;
+            } else if (b.below_Dw && b.below_g && b.below_g->vec > 0 && b.dX && g.all && q > 0) {
                 below = error_compression(b.dX, b.below_Dw, b.below_g->so, b.below_g->k);
                 vec = std::min(vec, b.below_g->vec);
                 const int64_t head_tiles = tiles_of(below.M, below.N) * g.groups;
                 with_head = head_tiles <= 128;
                 if (with_head) used += (head_tiles + 7) & ~(int64_t)7;
             }
-            const int64_t idle = 256 - ((used + 7) & ~(int64_t)7);
-            const bool with_sgd = allowed && b.ride_sgd && idle >= 64;
+            const int64_t idle = 256 - ((used + 7) & ~(int64_t)7);      // negative: the launch runs in rounds
+            // (a launch that runs in rounds anyway takes the update along on a quarter of the compute units: its
+            // workgroups go out before the error compression, which fills in as compute units come free)
+            const bool rounds = send_rides && used > 256;
+            const bool with_sgd = b.ride_sgd && (idle >= 64 || rounds);
             // a loss that no kernel has finished yet (and no update to carry it): one more workgroup does it
-            const bool with_loss = allowed && !with_sgd && !b.ride_sgd && b.loss_tail && b.loss_tail->partial;
+            const bool with_loss = !with_sgd && !b.ride_sgd && b.loss_tail && b.loss_tail->partial;
             if (with_head || with_sgd || with_loss) {
                 SgdBatch loss_only{};
                 if (with_loss) loss_only.tail = take_tail();
                 PH_TRY(launch_tail(with_head ? &below : nullptr, dw, dc, with_sgd ? b.ride_sgd : with_loss ? &loss_only : nullptr,
-                                   b.ride_lr, with_sgd ? (int)idle : 1, g.groups, vec, st,
-                                   with_head ? (with_sgd ? "weight + compressor gradients | error compr. below | SGD above"
-                                                         : "weight + compressor gradients | error compression below")
-                                             : with_sgd ? "weight + compressor gradients | SGD above"
-                                                        : "weight + compressor gradients | loss"));
-                if (b.below_done) *b.below_done = with_head;
+                                   b.ride_lr, with_sgd ? (int)std::max<int64_t>(idle, 64) : 1, g.groups, vec, st,
+                                   send_rides ? (with_sgd ? "weight + compressor gradients | error compression | SGD above"
+                                                          : "weight + compressor gradients | error compression")
+                                   : with_head ? (with_sgd ? "weight + compressor gradients | error compr. below | SGD above"
+                                                           : "weight + compressor gradients | error compression below")
+                                               : with_sgd ? "weight + compressor gradients | SGD above"
+                                                          : "weight + compressor gradients | loss",
+                                   rounds));
+                if (b.below_done) *b.below_done = with_head && !send_rides;
                 if (b.ride_sgd_done) *b.ride_sgd_done = with_sgd;
                 return PH_OK;
             }
