@@ -221,7 +221,7 @@ def measured_traffic(workload, row):
     The summary holds one line per (workload, kernel, shape): FETCH_SIZE and WRITE_SIZE per dispatch,
     already scaled by what the same counters read for a copy of known size in the same run.
     """
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.txt")
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "ffn_step_c2_hbm_traffic.txt")
     if not os.path.exists(path):
         return None
     key = [workload, row["name"].replace(" ", "_"), str(row["M"]), str(row["N"]), str(row["K"]), str(row["groups"])]
