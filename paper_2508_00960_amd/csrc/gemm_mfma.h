@@ -28,6 +28,9 @@
 // Workgroup ids are re-mapped so that the ids an XCD receives (id mod 8) form a contiguous range
 // of tiles: neighbouring tiles share operand panels in that XCD's L2.
 //
+// An operand's tail block may also be a sum that is formed on read (SumOnRead, fetch_summed): the in-memory
+// reduce-scatter of the backward pass as part of the input gradient's loader.
+//
 // Kernels in this file, all built on mfma_workgroup (one workgroup's work on one product):
 //   gemm_mfma_kernel       one product, or two of the same operand layout and output type
 //   gemm_mfma_tail_kernel  weight + compressor gradients with riders of other layouts (the error compression of
@@ -311,15 +314,83 @@ __device__ __forceinline__ bf16x8 lds_operand(const __bf16 *tile, int rbase, int
     }
 }
 
+// Reduce-scatter as a sum on read (all ranks on the device; Algorithm 1, backward): the tail block of operand A
+// (the k columns behind a.c.split, dg_own in the input-gradient product) is not read from memory but summed
+// from what the other ranks sent, dg_own[g] = sum_{j != g} src[j][slot of g on j], src = dG_send [p, p-1, per_slot],
+// per_slot = rows * k.  The workgroups of tile column 0 also write the sums to out [p, per_slot] for later kernels.
+// src == nullptr: operand A is read as its View says.
+struct SumOnRead {
+    const __bf16 *src;
+    __bf16 *out;
+    int64_t per_slot;
+    int p, k;
+};
+
 struct MfmaParams {
     View a, b, o;        // o: the row index must not decide the region (true for every output here)
     Epilogue ep;
+    SumOnRead rs;
     int M, N, K;
     int tiles_m, tiles_n;
     int ksplit;          // > 1: the reduction range is cut into ksplit pieces, results added atomically
     int k_per_split;     // multiple of KT
     int total_wg;
 };
+
+// The vectors of a K-contiguous A tile (reduction start c0) that lie in the summed block: replaces what the loader
+// fetched for them.  A thread holds NV vectors of the same columns in rows row0 + j * ROW_STEP; the loads of four
+// senders are in flight together (a sender that does not exist, or the rank itself, is read at a valid address
+// and not added).  Sums in fp32 in the order of the senders, one rounding to bf16.
+template <int VEC>
+__device__ __forceinline__ void fetch_summed(const SumOnRead &rs, int g, int r0, int r_limit, const StageState &s, int c0,
+                                             typename VecOf<VEC>::type (&regs)[StageCfg<LD_KC, VEC>::NV], bool write_out)
+{
+    typedef StageCfg<LD_KC, VEC> C;
+    typedef typename C::V V;
+    const int c = c0 + s.col;
+    if (c < s.c_split || c + VEC > s.c_lim) return;
+    const int w = c - s.c_split;
+    int64_t row_off[C::NV];
+#pragma unroll
+    for (int j = 0; j < C::NV; ++j) row_off[j] = (int64_t)min(r0 + s.row0 + j * C::ROW_STEP, r_limit - 1) * rs.k + w;
+    float acc[C::NV][VEC];
+#pragma unroll
+    for (int j = 0; j < C::NV; ++j)
+#pragma unroll
+        for (int u = 0; u < VEC; ++u) acc[j][u] = 0.f;
+    constexpr int AHEAD = 4;
+    for (int j0 = 0; j0 < rs.p; j0 += AHEAD) {
+        V v[AHEAD][C::NV];
+#pragma unroll
+        for (int a = 0; a < AHEAD; ++a) {
+            const int sender = min(j0 + a, rs.p - 1);
+            const int from = sender == g ? (g > 0 ? 0 : 1) : sender;          // p >= 2: a sender other than g exists
+            const int slot = g < from ? g : g - 1;
+            const __bf16 *base = rs.src + ((int64_t)from * (rs.p - 1) + slot) * rs.per_slot;
+#pragma unroll
+            for (int j = 0; j < C::NV; ++j) v[a][j] = load_global<V>(base + row_off[j]);
+        }
+#pragma unroll
+        for (int a = 0; a < AHEAD; ++a) {
+            const float take = (j0 + a < rs.p && j0 + a != g) ? 1.f : 0.f;
+#pragma unroll
+            for (int j = 0; j < C::NV; ++j) {
+                union { V v; __bf16 e[VEC]; } x;
+                x.v = v[a][j];
+#pragma unroll
+                for (int u = 0; u < VEC; ++u) acc[j][u] = fmaf(take, (float)x.e[u], acc[j][u]);
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < C::NV; ++j) {
+        union { V v; __bf16 e[VEC]; } x;
+#pragma unroll
+        for (int u = 0; u < VEC; ++u) x.e[u] = (__bf16)acc[j][u];
+        regs[j] = x.v;
+        if (write_out) *(V *)(rs.out + (int64_t)g * rs.per_slot + row_off[j]) = x.v;
+    }
+}
 
 template <int KA, int KB>
 __device__ __forceinline__ void mfma_tile(f32x16 (&acc)[2][2], const __bf16 *ta, const __bf16 *tb, int wm, int wn, int lane)
@@ -844,6 +915,12 @@ __device__ __forceinline__ void mfma_workgroup(const MfmaParams &P, int wg)
         if (ragged_first) PH_FETCH(0, c_of(0));
         else if (my_steps > 0) PH_FETCH_FAST(0, c_of(0));
         if (my_steps > 1) PH_FETCH_FAST(1, c_of(1));
+        if constexpr (KA == LD_KC && KB == LD_KM && VA == 8) {    // the input gradient's layout, 16-byte vectors
+            // the summed block lies in the tile processed first (the host sees to it: it starts at a tile boundary
+            // and is at most one tile long)
+            if (P.rs.src && my_steps > 0 && c_of(0) + KT > sa.c_split)
+                fetch_summed<VA>(P.rs, g, min(m0, (P.M - 1) / MT * MT), P.M, sa, c_of(0), ra0, tn == 0);
+        }
         if (ragged_first) {
             PH_STORE(0, 0, c_of(0));
         } else if (my_steps > 0) {

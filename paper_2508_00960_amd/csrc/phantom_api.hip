@@ -283,6 +283,7 @@ struct Product {
     View a, b, o;
     Epilogue ep;
     int64_t M, N, K;
+    SumOnRead rs;        // matrix-core path only: the tail block of a is summed on read (src != nullptr)
 };
 
 template <int KA, int KB, int VEC, typename TOut, bool ATOMIC, bool PAIR, bool DUAL, int EPI>
@@ -327,7 +328,7 @@ ph_status launch_mfma_vec(const MfmaBatch &batch, int vec, bool dual, hipStream_
 MfmaParams mfma_params(const Product &pr, int groups, int ksplit, bool dual)
 {
     MfmaParams P{};
-    P.a = pr.a; P.b = pr.b; P.o = pr.o; P.ep = pr.ep;
+    P.a = pr.a; P.b = pr.b; P.o = pr.o; P.ep = pr.ep; P.rs = pr.rs;
     P.M = (int)pr.M; P.N = (int)pr.N; P.K = (int)pr.K;
     const int mt = dual ? 2 * MT : MT;               // rows of C per workgroup
     P.tiles_m = (int)((pr.M + mt - 1) / mt);
@@ -798,7 +799,18 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
     if (g.all) {
         // the input gradient needs dg_own, which is the sum of what all ranks send: three launches
         if (!b.send_done) PH_TRY((launch_products<T, T>(plan_x, &send, 1, g.groups, st, "error compression")));
-        if (q > 0) {
+        // Reduce-scatter as a sum on read: the input gradient's loader sums the p-1 senders' slices while it stages
+        // the one reduction tile that holds dg_own, and writes dg_own out for the compressor gradient.  Conditions:
+        // the block starts on a tile boundary of the reduction index and fits one tile (so a multiple of 64,
+        // k a divisor of 64), 16-byte vectors, and at most 8 ranks: a thread takes the senders four at a
+        // time, and with 16 ranks the step got 0.4 % slower instead of 1.3 % faster.  PHANTOM_RS_ON_READ=0 keeps the kernel of its own (for measurements).
+        static const char *rs_force = getenv("PHANTOM_RS_ON_READ");
+        const bool sum_on_read = std::is_same<T, bf16_t>::value && g.vec == 8 && q > 0 && b.dX && g.p <= 8 && k <= KT &&
+                                 KT % k == 0 && so % KT == 0 && !(rs_force && rs_force[0] == '0');
+        if (sum_on_read) {
+            dx.rs.src = (const __bf16 *)b.dG_send; dx.rs.out = (__bf16 *)b.dg_own;
+            dx.rs.per_slot = B * k; dx.rs.p = (int)g.p; dx.rs.k = (int)k;
+        } else if (q > 0) {
             const int64_t per_slot = B * k;
             constexpr int RS_VEC = 16 / (int)sizeof(T);
             const bool wide = per_slot % RS_VEC == 0 && (((uintptr_t)b.dG_send | (uintptr_t)b.dg_own) & 15) == 0;
