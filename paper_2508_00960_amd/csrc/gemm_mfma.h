@@ -338,9 +338,9 @@ struct MfmaParams {
 };
 
 // The vectors of a K-contiguous A tile (reduction start c0) that lie in the summed block: replaces what the loader
-// fetched for them.  A thread holds NV vectors of the same columns in rows row0 + j * ROW_STEP; the loads of four
-// senders are in flight together (a sender that does not exist, or the rank itself, is read at a valid address
-// and not added).  Sums in fp32 in the order of the senders, one rounding to bf16.
+// fetched for them.  A thread holds NV vectors of the same columns in rows row0 + j * ROW_STEP; the loads of seven
+// senders are in flight together (with fewer senders the last one is read again and not added).  Sums in fp32 in
+// the order of the senders, one rounding to bf16.
 template <int VEC>
 __device__ __forceinline__ void fetch_summed(const SumOnRead &rs, int g, int r0, int r_limit, const StageState &s, int c0,
                                              typename VecOf<VEC>::type (&regs)[StageCfg<LD_KC, VEC>::NV], bool write_out)
@@ -358,13 +358,14 @@ __device__ __forceinline__ void fetch_summed(const SumOnRead &rs, int g, int r0,
     for (int j = 0; j < C::NV; ++j)
 #pragma unroll
         for (int u = 0; u < VEC; ++u) acc[j][u] = 0.f;
-    constexpr int AHEAD = 4;
-    for (int j0 = 0; j0 < rs.p; j0 += AHEAD) {
+    constexpr int AHEAD = 7;                 // the host allows at most 8 ranks: all senders in one batch
+    const int senders = rs.p - 1;
+    for (int a0 = 0; a0 < senders; a0 += AHEAD) {
         V v[AHEAD][C::NV];
 #pragma unroll
         for (int a = 0; a < AHEAD; ++a) {
-            const int sender = min(j0 + a, rs.p - 1);
-            const int from = sender == g ? (g > 0 ? 0 : 1) : sender;          // p >= 2: a sender other than g exists
+            const int i = min(a0 + a, senders - 1);            // the i-th sender other than g
+            const int from = i < g ? i : i + 1;
             const int slot = g < from ? g : g - 1;
             const __bf16 *base = rs.src + ((int64_t)from * (rs.p - 1) + slot) * rs.per_slot;
 #pragma unroll
@@ -372,7 +373,7 @@ __device__ __forceinline__ void fetch_summed(const SumOnRead &rs, int g, int r0,
         }
 #pragma unroll
         for (int a = 0; a < AHEAD; ++a) {
-            const float take = (j0 + a < rs.p && j0 + a != g) ? 1.f : 0.f;
+            const float take = a0 + a < senders ? 1.f : 0.f;
 #pragma unroll
             for (int j = 0; j < C::NV; ++j) {
                 union { V v; __bf16 e[VEC]; } x;

@@ -802,8 +802,8 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
         // Reduce-scatter as a sum on read: the input gradient's loader sums the p-1 senders' slices while it stages
         // the one reduction tile that holds dg_own, and writes dg_own out for the compressor gradient.  Conditions:
         // the block starts on a tile boundary of the reduction index and fits one tile (so a multiple of 64,
-        // k a divisor of 64), 16-byte vectors, and at most 8 ranks: a thread takes the senders four at a
-        // time, and with 16 ranks the step got 0.4 % slower instead of 1.3 % faster.  PHANTOM_RS_ON_READ=0 keeps the kernel of its own (for measurements).
+        // k a divisor of 64), 16-byte vectors, and at most 8 ranks: a thread has the loads of seven senders
+        // in flight at a time, and with 16 ranks the step got 0.4 % slower instead of 1.8 % faster.  PHANTOM_RS_ON_READ=0 keeps the kernel of its own (for measurements).
         static const char *rs_force = getenv("PHANTOM_RS_ON_READ");
         const bool sum_on_read = std::is_same<T, bf16_t>::value && g.vec == 8 && q > 0 && b.dX && g.p <= 8 && k <= KT &&
                                  KT % k == 0 && so % KT == 0 && !(rs_force && rs_force[0] == '0');
