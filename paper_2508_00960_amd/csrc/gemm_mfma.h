@@ -1028,6 +1028,8 @@ struct MfmaTailBatch {
     int sgd_wg;          // 0: no update
     int rotate;          // workgroup b does the work of number (b + rotate) mod the grid size: rotate = tail_first
                          //   sends the head's workgroups out last instead of first
+    int dual;            // every product of the launch in two-tile workgroups (DUAL of mfma_workgroup): for a launch
+                         //   that would otherwise not fit one workgroup per compute unit
 };
 
 template <int VEC>
@@ -1037,14 +1039,16 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_tail_kernel(MfmaTailBatch tb
     if (id >= (int)gridDim.x) id -= (int)gridDim.x;
     if (id < tb.tail_first) {                          // uniform, like every branch here
         if (id >= tb.head_wg) return;
-        mfma_workgroup<LD_KC, LD_KM, VEC, VEC, __bf16, false, false, EPI_STORE>(tb.head, xcd_order(id, 0, tb.head_wg));
+        if (tb.dual) mfma_workgroup<LD_KC, LD_KM, VEC, VEC, __bf16, false, true, EPI_STORE>(tb.head, xcd_order(id, 0, tb.head_wg));
+        else mfma_workgroup<LD_KC, LD_KM, VEC, VEC, __bf16, false, false, EPI_STORE>(tb.head, xcd_order(id, 0, tb.head_wg));
     } else if (id < tb.sgd_first) {
         if (id >= tb.tail_first + tb.tail_wg) return;
         int wg = xcd_order(id, tb.tail_first, tb.tail_wg);
         const bool second = wg >= tb.tail[0].total_wg;
         if (second) wg -= tb.tail[0].total_wg;
         const MfmaParams P = pick_params(second, tb.tail[0], tb.tail[1]);
-        mfma_workgroup<LD_KM, LD_KM, VEC, VEC, float, false, false, EPI_STORE>(P, wg);
+        if (tb.dual) mfma_workgroup<LD_KM, LD_KM, VEC, VEC, float, false, true, EPI_STORE>(P, wg);
+        else mfma_workgroup<LD_KM, LD_KM, VEC, VEC, float, false, false, EPI_STORE>(P, wg);
     } else {
         extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
         sgd_rider<__bf16>(tb.sgd, tb.lr, id - tb.sgd_first, tb.sgd_wg, MFMA_THREADS, (float *)smem_raw);

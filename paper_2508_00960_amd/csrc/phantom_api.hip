@@ -442,19 +442,30 @@ ph_status launch_tail(const Product *head, const Product &tail0, const Product &
                       int sgd_wg, int groups, int vec, hipStream_t st, const char *what, bool head_last = false)
 {
     MfmaTailBatch tb{};
-    if (head) tb.head = mfma_params(*head, groups, 1, false);
+    const bool two = tail1.M > 0 && tail1.N > 0;
+    // More tiles than compute units with the head's: in two-tile workgroups if the launch then fits one round
+    // (PHANTOM_TAIL_DUAL=0 / 1 forces the choice, for measurements)
+    auto wgs = [&](bool dual) {
+        int64_t n = (head ? (int64_t)mfma_params(*head, groups, 1, dual).total_wg : 0) + mfma_params(tail0, groups, 1, dual).total_wg;
+        if (two) n += mfma_params(tail1, groups, 1, dual).total_wg;
+        return n;
+    };
+    bool dual = head && !head_last && wgs(false) > 256 && wgs(true) <= 256;
+    static const char *dual_force = getenv("PHANTOM_TAIL_DUAL");
+    if (dual_force) dual = dual_force[0] == '1';
+    tb.dual = dual;
+    if (head) tb.head = mfma_params(*head, groups, 1, dual);
     tb.head_wg = head ? tb.head.total_wg : 0;
     tb.tail_first = (tb.head_wg + 7) & ~7;
-    tb.tail[0] = mfma_params(tail0, groups, 1, false);
+    tb.tail[0] = mfma_params(tail0, groups, 1, dual);
     tb.tail_wg = tb.tail[0].total_wg;
-    if (tail1.M > 0 && tail1.N > 0) {
-        tb.tail[1] = mfma_params(tail1, groups, 1, false);
+    if (two) {
+        tb.tail[1] = mfma_params(tail1, groups, 1, dual);
         tb.tail_wg += tb.tail[1].total_wg;
     }
     tb.sgd_first = (tb.tail_first + tb.tail_wg + 7) & ~7;
     tb.sgd_wg = sgd ? sgd_wg : 0;
     if (sgd) { tb.sgd = *sgd; tb.lr = lr; }
-    const bool two = tail1.M > 0 && tail1.N > 0;
     ProfScope prof(what, tail0.M, tail0.N, tail0.K, groups, st, two ? tail1.M : 0, two ? tail1.N : 0, two ? tail1.K : 0,
                    head ? head->M : 0, head ? head->N : 0, head ? head->K : 0);
     const unsigned total = (unsigned)(tb.sgd_first + tb.sgd_wg);
