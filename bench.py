@@ -1,16 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the phantom-layer hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c4]
 
 A "step" is one pass of the whole hot path over one batch of synthetic input that already sits in
-HBM: for the default workload (benchmark configuration 2: n=4096, p=8, shard 512, k=32, batch 1024,
-4 layers, ReLU, MSE, bf16 storage / fp32 accumulate, all 8 emulated ranks on the GPU) that is the
-forward through every layer, the loss, and the backward through every layer, via phantom_ffn_step.
+HBM.  The default workload is benchmark configuration 4, the largest single-GPU one: n=16384, p=16
+(shard 1024), k=64, batch 4096, 8 layers, GELU, MSE, bf16 storage / fp32 accumulate, rank 0 with the 15
+peers' phantom buffers seeded; its step is a training step through phantom_ffn_step (forward through
+every layer, loss, backward through every layer, SGD).
 Prints ONE JSON line: whole-step throughput (TFLOP/s from the algorithmic FLOP count
 6*B*s*(s+p*k) per layer and rank, and samples/s), the roofline of the dominant kernel measured
-with HIP events around each of its launches, the CPU oracle timed on a bounded sample, and the
-equal-width dense network through the same kernels.
+with HIP events around each of its launches, the CPU oracle timed on a bounded sample, the
+dense network of equal width (and one rank's tensor-parallel share of it) through the same kernels, and
+the other benchmark configurations (2, 3 and the forward sweep 5) as extra keys.
 """
 import argparse
 import json
@@ -215,22 +217,39 @@ def kernel_table(entries, steps, esize):
     return out, overhead
 
 
+def kernel_sources_hash():
+    """sha256 (first 16 hex digits) over the HIP sources the library is built from, in name order."""
+    import hashlib
+    csrc = os.path.join(ROOT, "paper_2508_00960_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(csrc)):
+        if name.endswith((".h", ".hip")):
+            h.update(name.encode())
+            h.update(open(os.path.join(csrc, name), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def measured_traffic(workload, row):
-    """HBM bytes per launch of one kernel, from the committed rocprofv3 counter summary (None if not measured).
+    """HBM bytes per launch of one kernel, from the committed rocprofv3 counter summary of this workload
+    (profiles/ffn_step_<workload>_hbm_traffic.txt); None if there is none, if it has no line for this kernel,
+    or if it was taken from other kernel sources than the ones in the tree (its "# kernel sources:" line).
 
     The summary holds one line per (workload, kernel, shape): FETCH_SIZE and WRITE_SIZE per dispatch,
     already scaled by what the same counters read for a copy of known size in the same run.
     """
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "ffn_step_c2_hbm_traffic.txt")
+    path = os.path.join(ROOT, "profiles", f"ffn_step_{workload}_hbm_traffic.txt")
     if not os.path.exists(path):
         return None
     key = [workload, row["name"].replace(" ", "_"), str(row["M"]), str(row["N"]), str(row["K"]), str(row["groups"])]
+    found, fresh = None, False
     with open(path) as f:
         for line in f:
             w = line.split()
+            if line.startswith("# kernel sources:"):
+                fresh = w[-1] == kernel_sources_hash()
             if len(w) >= 8 and not line.startswith("#") and w[:6] == key:
-                return float(w[6]) + float(w[7])
-    return None
+                found = float(w[6]) + float(w[7])
+    return found if fresh else None
 
 
 def cpu_baseline(bench, sample_batch):
@@ -267,10 +286,11 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="c4", choices=sorted(WORKLOADS))
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the other benchmark configurations (extra keys)")
     ap.add_argument("--cpu-sample-batch", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 256 MiB device copy: the dispatch of known size that scales rocprofv3's "
@@ -354,13 +374,45 @@ def main():
     }
 
     if not args.no_dense:
-        # equal-width dense (tensor-parallel-equivalent) network through the same kernels: p = 1
+        # the dense network of equal width and depth (p = 1: n x n weight blocks) through the same kernels ...
         d = Bench((c["n"], 1, 0, c["batch"], c["layers"], c["act"], c["dtype"], 0, c["mode"], c["lr"],
                    c["widths"], ()), seeded=False)
-        dms, dhow = d.time_steps(max(10, args.steps // 4), 5, graph=not args.no_graph)
+        dms, dhow = d.time_steps(max(5, args.steps // 4), 2, graph=not args.no_graph)
         out["dense_equal_width"] = {"ms_per_step": dms, "tflops": d.flops / dms * 1e-9, "launch": dhow,
-                                    "flop_per_step": d.flops, "phantom_speedup": dms / ms}
+                                    "flop_per_step": d.flops, "phantom_speedup": dms / ms,
+                                    "what": f"{c['layers']} dense layers {c['n']} x {c['n']}, batch {c['batch']}, step = {c['mode']}"}
         del d
+        torch.cuda.empty_cache()
+        # ... and one rank's share of that network under tensor parallelism: an [n/p, n] block of every layer
+        # applied to the full-width activation (one layer timed, times the depth)
+        if c["p"] > 1 and not c["widths"]:
+            t = Bench((c["n"], 1, 0, c["batch"], 1, c["act"], c["dtype"], 0, c["mode"], c["lr"],
+                       (c["n"], c["n"] // c["p"]), ()), seeded=False)
+            tms, thow = t.time_steps(max(10, args.steps // 2), 3, graph=not args.no_graph)
+            out["dense_tensor_parallel_share"] = {
+                "ms_per_layer": tms, "ms_per_step": tms * c["layers"], "tflops": t.flops / tms * 1e-9, "launch": thow,
+                "flop_per_layer": t.flops, "phantom_speedup": tms * c["layers"] / ms,
+                "what": f"one layer [{c['n'] // c['p']} x {c['n']}] on batch {c['batch']}, step = {c['mode']}, x {c['layers']} layers"}
+            del t
+            torch.cuda.empty_cache()
+    if not args.no_others:
+        # the other benchmark configurations, same measurement (HIP graph replays between device syncs), inputs of
+        # the same shapes and distributions drawn on the GPU
+        others = {}
+        for name in ("c2", "c3", "c5k4", "c5k16", "c5k64", "c5k256"):
+            if name == args.workload:
+                continue
+            o = Bench(name, seeded=False)
+            oms, ohow = o.time_steps(max(20, args.steps), 5, graph=not args.no_graph)
+            oc = o.cfg
+            others[name] = {"ms_per_step": oms, "tflops": o.flops / oms * 1e-9, "pct_mfma_peak": 100.0 * o.flops / oms * 1e-9 / MFMA_PEAK_TFLOPS,
+                            "pct_hbm_peak": 100.0 * (o.bytes / oms * 1e-6) / HBM_PEAK_GBS,
+                            "samples_per_s": oc["batch"] / oms * 1e3, "launch": ohow,
+                            "what": f"n={oc['n']} p={oc['p']} k={oc['k']} batch={oc['batch']} layers={oc['layers']} {oc['act']} "
+                                    f"{'all ranks' if oc['rank'] < 0 else 'rank 0'} step={oc['mode']}"}
+            del o
+            torch.cuda.empty_cache()
+        out["other_workloads"] = others
     if not args.no_cpu_baseline:
         sample = args.cpu_sample_batch or max(1, min(c["batch"], int(1.0e11 / (b.flops / c["batch"]))))
         out["cpu_baseline"] = cpu_baseline(b, sample)

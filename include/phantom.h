@@ -29,11 +29,15 @@
  * library never allocates or frees device memory, never synchronises, and
  * enqueues work only on the HIP stream it is given.  Every pointer is a DEVICE
  * pointer, 16-byte aligned, unless stated otherwise ("host").  Inputs are not
- * modified.  A call that returns an error has launched nothing.
+ * modified.
  *
  * Errors: every entry point returns a ph_status; phantom_last_error() gives
- * the message of the calling thread's last failure.  Argument errors are
- * found before any GPU call, so they can be exercised on a host without a GPU.
+ * the message of the calling thread's last failure.  PH_ERR_INVALID_ARG,
+ * PH_ERR_UNSUPPORTED and PH_ERR_WORKSPACE are decided from the arguments alone,
+ * before any GPU call (so they can be exercised on a host without a GPU): a call
+ * that returns one of them has launched nothing and touched no buffer.
+ * PH_ERR_LAUNCH is reported where it happens: launches that the same call
+ * made before it stay enqueued, and the call's outputs are then undefined.
  */
 #ifndef PHANTOM_H
 #define PHANTOM_H
@@ -50,7 +54,7 @@ typedef enum {
     PH_ERR_INVALID_ARG = -1,   /* bad shape, enum, null or misaligned pointer */
     PH_ERR_UNSUPPORTED = -2,   /* valid request this build cannot run */
     PH_ERR_WORKSPACE = -3,     /* workspace missing or too small */
-    PH_ERR_LAUNCH = -4         /* the HIP runtime refused a launch */
+    PH_ERR_LAUNCH = -4         /* the HIP runtime refused a launch in mid-call, or an internal inconsistency */
 } ph_status;
 
 typedef enum { PH_ACT_IDENTITY = 0, PH_ACT_RELU = 1, PH_ACT_GELU = 2 /* x*Phi(x), erf form */ } ph_act;
@@ -144,6 +148,27 @@ typedef enum {
 } ph_step_mode;
 
 /*
+ * Optional taps of phantom_ffn_step, for checking every stage of the step on its own (NULL in production):
+ * copies of the tensors that pass from one stage of Eq. (ylq) / Eq. (backprop) to the next, taken right after
+ * the launch that finishes each of them (one small copy launch per tap; the step's own launches are the same
+ * with and without taps).  HOST arrays of prob->layers DEVICE pointers, each array and each entry may be NULL;
+ * storage type, shapes per layer l as in phantom_layer_fwd / _bwd (all ranks: the leading [p] axis):
+ *   Y[l]       [B, so]       y_l as stored (the next layer's operand)
+ *   g_own[l]   [B, k]        g_l^(j) = C y_{l-1}^(j)          (all ranks: [p, B, k], the gathered buffer)
+ *   delta[l]   [B, so]       delta_l = dLoss/dz_l: Eq. (deltaL) for the last layer, Eq. (backprop) below it
+ *   dG_send[l] [p-1, B, k]   (D^(i,j))^T delta_l^(j), the Reduce-Scatter input
+ *   dg_own[l]  [p, B, k]     all-ranks mode only: the Reduce-Scatter result the step computed
+ * Ignored with PH_STEP_FORWARD: delta, dG_send, dg_own.
+ */
+typedef struct {
+    void *const *Y;
+    void *const *g_own;
+    void *const *delta;
+    void *const *dG_send;
+    void *const *dg_own;
+} ph_step_taps;
+
+/*
  * Arguments of phantom_ffn_step.  The arrays are HOST arrays of prob->layers
  * DEVICE pointers, read during the call.
  */
@@ -168,6 +193,7 @@ typedef struct {
     float *loss;               /* device scalar: 1/(2B) sum (y_L - t)^2 over batch, features and ranks held */
     float lr;                  /* SGD: w <- w - lr * dLoss/dw, all gradients taken before the update */
     int32_t mode;              /* ph_step_mode */
+    const ph_step_taps *taps;  /* host; NULL: none */
 } ph_step_args;
 
 /*
@@ -177,9 +203,9 @@ typedef struct {
  * backward through every layer (Eq. (backprop), (bpb)-(bpD)) and a plain SGD
  * update.  Between layers, y_l and delta_l = dLoss/dz_l are kept in the storage
  * type; delta_l is formed as (L^T delta + C^T dg_own) * sigma_l' and rounded once,
- * as Eq. (backprop) writes it (dLoss/dy_l itself is never stored).  With PH_BF16 and
- * GELU the sigma_l' factor is kept between forward and backward in IEEE half
- * precision (11 significant bits); with PH_F32 the pre-activation is kept in float.
+ * as Eq. (backprop) writes it (dLoss/dy_l itself is never stored).  For GELU the
+ * workspace keeps, between forward and backward, sigma_l'(b + z) in float (PH_BF16) or
+ * the pre-activation in float (PH_F32); ReLU's derivative is read off the stored y_l.
  * The workspace need not be cleared by the caller and holds nothing between calls.
  */
 ph_status phantom_ffn_step(const ph_problem *prob, const ph_step_args *args,

@@ -25,11 +25,8 @@ Readings of the paper (it is silent on these):
     cross the rank boundary (g, dLoss/dg^(i,j), and their reduce-scatter sum)
     are rounded to bfloat16 when formed; sums and elementwise functions are
     exact.  With storage type fp32 nothing is rounded (fp64 throughout).
-  * a training step in bfloat16 storage keeps sigma'(A_l) of every layer for the
-    backward pass, in half precision (11 significant bits), not A_l: the sigma'
-    factor of Eq. (deltaL) and Eq. (backprop) is that rounded value.  (ReLU's and
-    the identity's derivative are exact in half precision.)  The backward operator
-    called on its own is handed A and uses sigma'(A) unrounded.
+  * the sigma' factor of Eq. (deltaL) and Eq. (backprop) is sigma'(A_l) evaluated
+    in fp64 on the unrounded pre-activation, for every storage type.
   * SGD: w <- w - lr * dLoss/dw for L, C, D, b of every layer, all gradients
     taken at the weights before the update.
 
@@ -66,8 +63,6 @@ def lib():
         _lib = ctypes.CDLL(build())
         _lib.pho_round_bf16.restype = ctypes.c_double
         _lib.pho_round_bf16.argtypes = [ctypes.c_double]
-        _lib.pho_round_f16.restype = ctypes.c_double
-        _lib.pho_round_f16.argtypes = [ctypes.c_double]
         _lib.pho_num_threads.restype = ctypes.c_int
     return _lib
 
@@ -146,13 +141,12 @@ def layer_fwd(act, X, Lw, Cw, Dw, bias, G):
     return {"A": A, "Y": Y, "g_own": g}
 
 
-def delta_of(act, dY, A, storage="f32", deriv_f16=False):
-    """delta = dY * sigma'(A), Eq. (deltaL); rounded to bfloat16 when that is the storage type.
-    deriv_f16: sigma'(A) is rounded to half precision first (what a bf16 training step keeps of A)."""
+def delta_of(act, dY, A, storage="f32"):
+    """delta = dY * sigma'(A), Eq. (deltaL); rounded to bfloat16 when that is the storage type."""
     B, s = dY.shape
     dY_, pdY = _c(dY); A_, pA = _c(A)
     d = np.empty((B, s))
-    lib().pho_delta(_i(B), _i(s), ctypes.c_int(ACTS[act]), ctypes.c_int(int(storage == "bf16") | (2 if deriv_f16 else 0)),
+    lib().pho_delta(_i(B), _i(s), ctypes.c_int(ACTS[act]), ctypes.c_int(int(storage == "bf16")),
                     pdY, pA, _vp(d))
     return d
 
@@ -185,10 +179,10 @@ def layer_grads(delta, X, Lw, Cw, G, dg_own, need_dX=True):
     return {"dX": dX, "dLw": dLw, "dCw": dCw if q else None, "dDw": dDw if q else None, "dbias": db}
 
 
-def layer_bwd(act, dY, X, A, Lw, Cw, Dw, G, dg_own, storage="f32", need_dX=True, deriv_f16=False):
+def layer_bwd(act, dY, X, A, Lw, Cw, Dw, G, dg_own, storage="f32", need_dX=True):
     """Backward of one layer on one rank with the peers' reduce-scatter result dg_own given."""
     q = 0 if Dw is None else Dw.shape[0]
-    delta = delta_of(act, dY, A, storage, deriv_f16)
+    delta = delta_of(act, dY, A, storage)
     out = layer_grads(delta, X, Lw, Cw, G, dg_own, need_dX)
     out["delta"] = delta
     out["dG_send"] = error_compress(Dw, delta) if q else None
@@ -236,10 +230,10 @@ def reduce_scatter(dG_send, storage="f32"):
     return rd(out, storage)
 
 
-def all_ranks_bwd(act, dY, X, A, P, G_full, storage="f32", need_dX=True, deriv_f16=False):
+def all_ranks_bwd(act, dY, X, A, P, G_full, storage="f32", need_dX=True):
     """Backward of one layer on all ranks.  dY, X, A: [p,B,s].  Returns stacked gradients."""
     p, B, s = X.shape
-    delta = np.stack([delta_of(act, dY[j], A[j], storage, deriv_f16) for j in range(p)])
+    delta = np.stack([delta_of(act, dY[j], A[j], storage) for j in range(p)])
     if p == 1:
         g = layer_grads(delta[0], X[0], P["Lw"][0], None, None, None, need_dX)
         return {"delta": delta, "dX": None if g["dX"] is None else g["dX"][None], "dLw": g["dLw"][None],
@@ -295,18 +289,17 @@ def ffn_step(act, X0, T, layers, lr, storage="f32", all_ranks=True):
     reduce-scatter result of layer l."""
     fw = ffn_forward(act, X0, layers, storage, all_ranks)
     loss, dY = mse_loss(fw["out"], T)
-    deriv_f16 = storage == "bf16"    # reading in the module header: what a bf16 step keeps of A
     grads = [None] * len(layers)
     for l in reversed(range(len(layers))):
         P = layers[l]
         need_dX = l > 0
         if all_ranks:
-            g = all_ranks_bwd(act, dY, fw["X"][l], fw["A"][l], P, fw["G"][l], storage, need_dX, deriv_f16)
+            g = all_ranks_bwd(act, dY, fw["X"][l], fw["A"][l], P, fw["G"][l], storage, need_dX)
         else:
             q = P["Dw"].shape[0] if P.get("Dw") is not None else 0
             g = layer_bwd(act, dY, fw["X"][l], fw["A"][l], P["Lw"], P["Cw"] if q else None,
                           P["Dw"] if q else None, P["G"] if q else None, P["dg_own"] if q else None,
-                          storage, need_dX, deriv_f16)
+                          storage, need_dX)
         grads[l] = g
         dY = g["dX"]                 # dLoss/dy_{l-1}; the sigma' factor is applied by the next delta_of
     new_layers = []

@@ -32,10 +32,8 @@
  *   - when the storage type is bfloat16, a tensor that is the operand of a
  *     later matrix product (here: delta) is rounded to bfloat16 once it is
  *     formed; sums and elementwise functions are exact (fp64).
- *   - a training step in bfloat16 storage keeps, of a layer's pre-activation, only
- *     sigma'(A) for the backward pass, as an IEEE half (11 significant bits): the
- *     sigma' factor of Eq. (deltaL) / Eq. (backprop) is then that rounded value.  The
- *     backward operator on its own takes A and uses sigma'(A) unrounded.
+ *   - the sigma' factor of Eq. (deltaL) / Eq. (backprop) is sigma'(A) itself, in fp64, whatever the
+ *     storage type: the paper rounds nothing there.
  *
  * Parallelism: OpenMP over independent output rows only; no blocking, no
  * reordering of a sum other than the loop order written below.
@@ -84,18 +82,6 @@ double pho_round_bf16(double v) {
     u &= ~((UINT64_C(1) << drop) - 1);
     memcpy(&v, &u, sizeof v);
     return v;
-}
-
-/* Nearest-even rounding of a double to the IEEE half-precision grid: 11 significant bits down to
- * 2^-14, a fixed step of 2^-24 below that (subnormals).  Values beyond half's largest finite
- * number do not occur here (sigma' stays within [-0.2, 1.2]) and are returned unchanged. */
-double pho_round_f16(double v) {
-    if (v == 0.0 || !isfinite(v) || fabs(v) >= 65520.0) return v;
-    int e;
-    frexp(v, &e);                         /* |v| in [2^(e-1), 2^e) */
-    int step_exp = (e - 1 < -14 ? -14 : e - 1) - 10;
-    double step = ldexp(1.0, step_exp);
-    return nearbyint(v / step) * step;    /* both scalings are exact; nearbyint rounds half to even */
 }
 
 void pho_round_bf16_array(double *a, int64_t count) {
@@ -170,8 +156,7 @@ void pho_layer_fwd(int64_t B, int64_t si, int64_t so, int64_t k, int64_t q, int 
  * (Section IV-B, "Parallel Complexity"); pho_layer_bwd below runs them in order.
  *
  * (1) local error:        delta = dY * sigma'(A)            Eq. (deltaL); the sigma' factor of Eq. (backprop)
- *     round_operands bit 0: delta is rounded to bfloat16 when formed; bit 1: sigma'(A) is rounded to
- *     half precision before the product (see header).
+ *     round_operands != 0: delta is rounded to bfloat16 when formed (see header).
  */
 void pho_delta(int64_t B, int64_t s, int act, int round_operands,
                const double *dY, const double *A, double *delta)
@@ -179,10 +164,8 @@ void pho_delta(int64_t B, int64_t s, int act, int round_operands,
 #pragma omp parallel for schedule(static)
     for (int64_t b = 0; b < B; ++b) {
         for (int64_t o = 0; o < s; ++o) {
-            double df = act_df(act, A[b * s + o]);
-            if (round_operands & 2) df = pho_round_f16(df);
-            double d = dY[b * s + o] * df;
-            delta[b * s + o] = (round_operands & 1) ? pho_round_bf16(d) : d;
+            double d = dY[b * s + o] * act_df(act, A[b * s + o]);
+            delta[b * s + o] = round_operands ? pho_round_bf16(d) : d;
         }
     }
 }

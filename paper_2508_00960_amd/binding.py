@@ -45,6 +45,10 @@ class PhProblem(ctypes.Structure):
 _PP = ctypes.POINTER(ctypes.c_void_p)
 
 
+class PhStepTaps(ctypes.Structure):
+    _fields_ = [("Y", _PP), ("g_own", _PP), ("delta", _PP), ("dG_send", _PP), ("dg_own", _PP)]
+
+
 class PhStepArgs(ctypes.Structure):
     _fields_ = [
         ("X0", ctypes.c_void_p), ("T", ctypes.c_void_p),
@@ -54,6 +58,7 @@ class PhStepArgs(ctypes.Structure):
         ("dLw", _PP), ("dCw", _PP), ("dDw", _PP), ("dbias", _PP),
         ("Y_out", ctypes.c_void_p), ("loss", ctypes.c_void_p),
         ("lr", ctypes.c_float), ("mode", ctypes.c_int32),
+        ("taps", ctypes.POINTER(PhStepTaps)),
     ]
 
 
@@ -258,8 +263,9 @@ def _ptr_array(tensors: Optional[Sequence], layers: int):
 
 def ffn_step(prob, X0, T, Lw, Cw, Dw, bias, *, Lw_master=None, Cw_master=None, Dw_master=None, bias_master=None,
              G=None, dg_own=None, dLw=None, dCw=None, dDw=None, dbias=None, Y_out=None, loss=None, lr=0.0,
-             mode="train", workspace=None, stream=None):
-    """phantom_ffn_step; per-layer arguments are sequences of prob.layers tensors (or None)."""
+             mode="train", workspace=None, stream=None, taps=None):
+    """phantom_ffn_step; per-layer arguments are sequences of prob.layers tensors (or None).
+    taps: dict with any of "Y", "g_own", "delta", "dG_send", "dg_own" -> sequence of prob.layers tensors (ph_step_taps)."""
     L = prob.layers
     keep = []
     kinds = {"Lw": "L", "Cw": "C", "Dw": "D", "bias": "b", "Lw_master": "L32", "Cw_master": "C32", "Dw_master": "D32",
@@ -286,5 +292,16 @@ def ffn_step(prob, X0, T, Lw, Cw, Dw, bias, *, Lw_master=None, Cw_master=None, D
             setattr(args, name, ptr)
     args.lr = float(lr)
     args.mode = STEP_MODES[mode]
+    if taps:
+        tap_kinds = {"Y": "out", "g_own": "g", "delta": "out", "dG_send": "send", "dg_own": "g"}
+        tp = PhStepTaps()
+        for name, val in taps.items():
+            for layer in range(L):
+                _check_layer_tensors(prob, layer, {f"taps.{name}[{layer}]": (val[layer], tap_kinds[name])})
+            ptr, arr = _ptr_array(val, L)
+            keep.append(arr)
+            setattr(tp, name, ptr)
+        keep.append(tp)
+        args.taps = ctypes.pointer(tp)
     wp, wb = _ws(workspace)
     _check(load().phantom_ffn_step(ctypes.byref(prob), ctypes.byref(args), wp, wb, _stream(stream)))

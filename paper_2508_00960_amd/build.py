@@ -23,8 +23,11 @@ def sources():
 
 
 def build_library(verbose: bool = True) -> str:
-    """Compile every .hip file under csrc/ into one shared library.  Always recompiles."""
-    cmd = [HIPCC, *FLAGS, *sources(), "-o", LIB]
+    """Compile every .hip file under csrc/ into one shared library.  Always recompiles.
+    PHANTOM_TUNING=1 in the environment of THIS script builds the measurement variant, whose launch-schedule
+    choices can be forced through PHANTOM_* variables; the default build reads no environment variable."""
+    extra = ["-DPHANTOM_TUNING_ENV"] if os.environ.get("PHANTOM_TUNING") == "1" else []
+    cmd = [HIPCC, *FLAGS, *extra, *sources(), "-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)
     proc = subprocess.run(cmd, capture_output=True, text=True)

@@ -166,7 +166,7 @@ __global__ __launch_bounds__(256) void reduce_scatter_kernel(const T *__restrict
 // MSE output error (Section IV-B, "Local error at the output", Eq. (deltaL)):
 // delta_L = ((Y - T) / B) * sigma'(S) with one rounding (Eq. (deltaL) for the MSE loss), and one partial
 // sum of (Y - T)^2 per workgroup (added up by the rider of colsum_kernel).  S: pre-activation, or the
-// output for ReLU (s_kind 0: storage type, 1: float), or sigma'(pre-activation) itself in fp16
+// output for ReLU (s_kind 0: storage type, 1: float), or sigma'(pre-activation) itself in float
 // (s_kind 2).  VEC elements per thread and iteration (VEC > 1: count is a multiple of VEC and
 // every pointer is VEC-element aligned).
 // Rider: the kernel also clears `zero_count` floats at `zero` (the step's bias-gradient buffers, which later
@@ -193,13 +193,8 @@ __global__ __launch_bounds__(256) void mse_delta_kernel(const T *__restrict__ Y,
             y = *(const TV *)(Y + i);
             t = *(const TV *)(Tg + i);
             if (act != ACT_IDENTITY) {
-                if (s_kind == 1) {
+                if (s_kind == 1 || s_kind == 2) {
                     sv = *(const FV *)((const float *)S + i);
-                } else if (s_kind == 2) {
-                    typedef _Float16 HV __attribute__((ext_vector_type(VEC)));
-                    const HV sraw = *(const HV *)((const _Float16 *)S + i);
-#pragma unroll
-                    for (int u = 0; u < VEC; ++u) sv[u] = (float)sraw[u];
                 } else {
                     const TV sraw = *(const TV *)((const T *)S + i);
 #pragma unroll
@@ -209,7 +204,7 @@ __global__ __launch_bounds__(256) void mse_delta_kernel(const T *__restrict__ Y,
         } else {
             y[0] = Y[i]; t[0] = Tg[i];
             if (act != ACT_IDENTITY)
-                sv[0] = s_kind == 1 ? ((const float *)S)[i] : s_kind == 2 ? (float)((const _Float16 *)S)[i] : to_f32(((const T *)S)[i]);
+                sv[0] = s_kind != 0 ? ((const float *)S)[i] : to_f32(((const T *)S)[i]);
         }
 #pragma unroll
         for (int u = 0; u < VEC; ++u) {

@@ -22,14 +22,14 @@ struct Epilogue {
     int64_t aux_ld;      //   plain row-major [M x N]
     int64_t aux_g;
     int32_t aux_f32;     // aux holds float instead of the storage type
-    int32_t aux_deriv;   // aux holds sigma'(pre-activation) in fp16 instead of the pre-activation:
-                         //   EPI_BIAS_ACT writes it, EPI_DACT multiplies by it as it stands (aux_f32 = 0)
+    int32_t aux_deriv;   // aux holds sigma'(pre-activation), in float, instead of the pre-activation:
+                         //   EPI_BIAS_ACT writes it, EPI_DACT multiplies by it as it stands
     float *colsum;       // MFMA kernel only, optional: the column sums of the stored output (as rounded to
     int64_t colsum_g;    //   the output type) are ADDED to colsum[N] per group; the caller zeroes it first
     // MFMA kernel only, EPI_BIAS_ACT, optional (mse_target != NULL): the layer is the last one and the MSE output
     // error is formed on the way out (Eq. (deltaL)): with y the output as stored and t = mse_target (laid out
     // like aux: aux_ld, aux_g, storage type), mse_delta <- ((y - t) * mse_inv_b) * sigma'(pre-activation)
-    // (sigma' as the backward pass would read it back: through fp16 for GELU, from y for ReLU), colsum
+    // (sigma' of the pre-activation in float for GELU, from y for ReLU), colsum
     // then receives the column sums of mse_delta instead of y's, and mse_partial[tile] <- sum over the
     // tile of (y - t)^2, tile = (group * ceil(M/128) + tile row) * ceil(N/128) + tile column.
     const void *mse_target;
@@ -137,7 +137,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(View va, View vb, Vie
                 v += to_f32(((const TIn *)ep.bias)[g * ep.bias_g + n]);
                 if (ep.aux) {
                     const int64_t at = g * ep.aux_g + (int64_t)m * ep.aux_ld + n;
-                    if (ep.aux_deriv) ((_Float16 *)ep.aux)[at] = (_Float16)act_deriv(ep.act, v);
+                    if (ep.aux_deriv) ((float *)ep.aux)[at] = act_deriv(ep.act, v);
                     else if (ep.aux_f32) ((float *)ep.aux)[at] = v;
                     else ((TIn *)ep.aux)[at] = from_f32<TIn>(v);
                 }
@@ -145,7 +145,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(View va, View vb, Vie
             } else if (ep.mode == EPI_DACT) {
                 const int64_t at = g * ep.aux_g + (int64_t)m * ep.aux_ld + n;
                 if (ep.aux_deriv) {
-                    v *= (float)((const _Float16 *)ep.aux)[at];
+                    v *= ((const float *)ep.aux)[at];
                 } else {
                     const float a = ep.aux_f32 ? ((const float *)ep.aux)[at] : to_f32(((const TIn *)ep.aux)[at]);
                     v *= act_deriv(ep.act, a);

@@ -569,7 +569,6 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
     typedef typename PackOf<TOut, VEC>::type OutV;
     typedef typename PackOf<__bf16, VEC>::type BfV;
     typedef typename PackOf<float, VEC>::type FlV;
-    typedef typename PackOf<_Float16, VEC>::type HfV;
     TOut *o0 = (TOut *)P.o.p0 + g * P.o.g0, *o1 = (TOut *)P.o.p1 + g * P.o.g1;
     const int skip_o = P.o.skip0 + g * P.o.skip_g;
     const Epilogue &ep = P.ep;
@@ -610,14 +609,13 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
                 for (int u = 0; u < VEC; ++u) {
                     pre[u] = x[u];
                     gelu_both(pre[u], x[u], deriv[u]);
-                    deriv[u] = (float)(_Float16)deriv[u];      // as stored for, and read back by, the backward pass
                 }
                 if (ep.aux) {
                     if (ep.aux_deriv) {
-                        HfV a;
+                        FlV a;
 #pragma unroll
-                        for (int u = 0; u < VEC; ++u) a[u] = (_Float16)deriv[u];
-                        *(HfV *)((_Float16 *)ep.aux + aux_at) = a;
+                        for (int u = 0; u < VEC; ++u) a[u] = deriv[u];
+                        *(FlV *)((float *)ep.aux + aux_at) = a;
                     } else if (ep.aux_f32) {
                         FlV a;
 #pragma unroll
@@ -633,10 +631,10 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
             } else {
                 if (ep.aux) {
                     if (ep.aux_deriv) {
-                        HfV a;
+                        FlV a;
 #pragma unroll
-                        for (int u = 0; u < VEC; ++u) a[u] = (_Float16)act_deriv(ep.act, x[u]);
-                        *(HfV *)((_Float16 *)ep.aux + aux_at) = a;
+                        for (int u = 0; u < VEC; ++u) a[u] = act_deriv(ep.act, x[u]);
+                        *(FlV *)((float *)ep.aux + aux_at) = a;
                     } else if (ep.aux_f32) {
                         FlV a;
 #pragma unroll
@@ -656,21 +654,18 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
                 }
             }
         } else if (EPI == EPI_DACT && ep.mode == EPI_DACT && ep.aux) {      // no aux: sigma' = 1, column sums only
-            if (ep.aux_f32) {
+            if (ep.aux_deriv) {                        // sigma' itself, float
+                const FlV a = *(const FlV *)((const float *)ep.aux + aux_at);
+#pragma unroll
+                for (int u = 0; u < VEC; ++u) x[u] *= a[u];
+            } else if (ep.aux_f32) {
                 const FlV a = *(const FlV *)((const float *)ep.aux + aux_at);
 #pragma unroll
                 for (int u = 0; u < VEC; ++u) x[u] *= act_deriv(ep.act, a[u]);
-            } else {
-                // 16-bit aux: sigma' itself in fp16, or the pre-activation (or ReLU output) in bf16
-                if (ep.aux_deriv) {
-                    const HfV a = *(const HfV *)((const _Float16 *)ep.aux + aux_at);
+            } else {                                   // the pre-activation (or ReLU output) in bf16
+                const BfV a = *(const BfV *)((const __bf16 *)ep.aux + aux_at);
 #pragma unroll
-                    for (int u = 0; u < VEC; ++u) x[u] *= (float)a[u];
-                } else {
-                    const BfV a = *(const BfV *)((const __bf16 *)ep.aux + aux_at);
-#pragma unroll
-                    for (int u = 0; u < VEC; ++u) x[u] *= act_deriv(ep.act, (float)a[u]);
-                }
+                for (int u = 0; u < VEC; ++u) x[u] *= act_deriv(ep.act, (float)a[u]);
             }
         }
         const Loc ln = locate(P.o.c, n, skip_o);

@@ -40,6 +40,19 @@ ph_status fail(ph_status st, const char *fmt, ...)
 
 #define PH_TRY(expr) do { ph_status st__ = (expr); if (st__ != PH_OK) return st__; } while (0)
 
+// Measurement switches (force one of two launch schedules that the library otherwise chooses between by
+// its own model) exist only in a library built with -DPHANTOM_TUNING_ENV; a production build reads no
+// environment variable.
+inline const char *tuning_env(const char *name)
+{
+#ifdef PHANTOM_TUNING_ENV
+    return getenv(name);
+#else
+    (void)name;
+    return nullptr;
+#endif
+}
+
 // One layer's shapes on this GPU.  si / so: inputs / outputs of the layer held by one rank (equal unless
 // the problem gives per-layer widths).
 struct Geo {
@@ -103,6 +116,15 @@ ph_status make_geo(const ph_problem *pr, Geo &g, int layer = 0)
     // index arithmetic inside the kernels uses 32-bit row/column numbers and a 3-D grid
     if (g.B > (1 << 22) || si > (1 << 22) || so > (1 << 22) || g.Kc > (1 << 24) || so + g.q * g.k > (1 << 24) || g.p > 65535)
         return fail(PH_ERR_UNSUPPORTED, "problem too large for 32-bit tile indices (batch, n/p <= 2^22, n/p+(p-1)k <= 2^24)");
+    // ... and numbers its 128 x 128 output tiles with 32 bits, over all ranks held: the largest product of the layer
+    {
+        auto t = [](int64_t x) { return (x + 127) / 128; };
+        const int64_t tiles = std::max({t(g.B) * t(so), t(g.B) * t(si), t(g.B) * t(std::max<int64_t>(g.q * g.k, 1)),
+                                        t(so) * t(g.Kc), t(std::max<int64_t>(g.k, 1)) * t(si)}) * g.groups;
+        if (tiles * 8 > 0x7fffffff)
+            return fail(PH_ERR_UNSUPPORTED, "layer %d: %lld output tiles in one product, more than the kernels number", layer,
+                        (long long)tiles);
+    }
     return PH_OK;
 }
 
@@ -231,8 +253,8 @@ StepWs carve_step(Arena &a, const std::vector<Geo> &geos)
     for (const Geo &g : geos) {
         const size_t act_bytes = (size_t)g.groups * g.B * g.so * g.esz;
         w.Y.push_back(a.take(act_bytes));
-        // GELU keeps per layer: fp32 storage, the pre-activation; bf16 storage, sigma'(pre-activation) in fp16
-        w.A.push_back(g.act == PH_ACT_GELU ? a.take(g.esz == 2 ? act_bytes : (size_t)g.groups * g.B * g.so * sizeof(float)) : nullptr);
+        // GELU keeps per layer, in float: fp32 storage, the pre-activation; bf16 storage, sigma'(pre-activation)
+        w.A.push_back(g.act == PH_ACT_GELU ? a.take((size_t)g.groups * g.B * g.so * sizeof(float)) : nullptr);
         w.G.push_back(g.q > 0 ? a.take((size_t)g.groups * g.B * g.k * g.esz) : nullptr);   // all-ranks: [p,B,k]; one-rank: [B,k]
         act_max = std::max(act_max, (size_t)std::max(g.si, g.so));
         k_max = std::max(k_max, (size_t)g.k);
@@ -240,7 +262,7 @@ StepWs carve_step(Arena &a, const std::vector<Geo> &geos)
         cw_max = std::max(cw_max, (size_t)(g.k * g.si));
         dw_max = std::max(dw_max, (size_t)(g.q * g.so * g.k));
         w.dbias_at.push_back(dbias_total);
-        dbias_total += (int64_t)g.groups * g.so;
+        dbias_total += ((int64_t)g.groups * g.so + 3) & ~(int64_t)3;   // every layer's block starts 16-byte aligned
     }
     w.dbias_at.push_back(dbias_total);
     const size_t groups = (size_t)g0.groups, B = (size_t)g0.B;
@@ -348,7 +370,7 @@ ph_status launch_mfma(const GemmPlan &plan, const Product *prods, int count, int
     int ksplit = 1;
     const Product &first = prods[0];
     const int64_t tiles = ((first.M + MT - 1) / MT) * ((first.N + MT - 1) / MT) * groups;
-    if (tiles * 8 > 0x7fffffff) return fail(PH_ERR_UNSUPPORTED, "%s: too many tiles", what);
+    if (tiles * 8 > 0x7fffffff) return fail(PH_ERR_LAUNCH, "%s: internal error, too many tiles (make_geo admits none such)", what);
     if (count == 1 && plan.may_split && std::is_same<TOut, float>::value && first.ep.mode == EPI_STORE) {
         // Splitting pays only when the tiles cover a small part of the 256 compute units: the atomic
         // adds of a split cost about as much as the product itself (measured: 512 x 736 x 1024 x 8
@@ -367,7 +389,7 @@ ph_status launch_mfma(const GemmPlan &plan, const Product *prods, int count, int
         int64_t all_tiles = tiles;
         if (count == 2) all_tiles += ((prods[1].M + MT - 1) / MT) * ((prods[1].N + MT - 1) / MT) * groups;
         dual = all_tiles > 256;
-        static const char *force = getenv("PHANTOM_DUAL");
+        static const char *force = tuning_env("PHANTOM_DUAL");
         if (force) dual = force[0] == '1';
     }
     MfmaBatch batch{};
@@ -394,7 +416,7 @@ ph_status launch_mfma(const GemmPlan &plan, const Product *prods, int count, int
             ProfScope prof(what, first.M, first.N, first.K, groups, st);
             if (plan.ka == LD_KM && plan.kb == LD_KM) return launch_mfma_vec<LD_KM, LD_KM, float, true, EPI_STORE>(batch, plan.vec, false, st, what);
         }
-        return fail(PH_ERR_UNSUPPORTED, "%s: split reduction not available for this operand layout", what);
+        return fail(PH_ERR_LAUNCH, "%s: internal error, split reduction asked for an operand layout that has none", what);
     }
     ProfScope prof(what, first.M, first.N, first.K, groups, st, count == 2 ? second.M : 0, count == 2 ? second.N : 0,
                    count == 2 ? second.K : 0);
@@ -403,7 +425,7 @@ ph_status launch_mfma(const GemmPlan &plan, const Product *prods, int count, int
     // store alone, in the storage type; the weight-gradient layout with the plain store in float.  The
     // second product of a pair always stores plainly.
     const int mode = first.ep.mode;
-    if (count == 2 && second.ep.mode != EPI_STORE) return fail(PH_ERR_UNSUPPORTED, "%s: the second product of a pair must store plainly", what);
+    if (count == 2 && second.ep.mode != EPI_STORE) return fail(PH_ERR_LAUNCH, "%s: internal error, the second product of a pair must store plainly", what);
     if constexpr (std::is_same<TOut, float>::value) {
         if (plan.ka == LD_KM && plan.kb == LD_KM && mode == EPI_STORE)
             return launch_mfma_vec<LD_KM, LD_KM, float, false, EPI_STORE>(batch, plan.vec, dual, st, what);
@@ -417,7 +439,7 @@ ph_status launch_mfma(const GemmPlan &plan, const Product *prods, int count, int
             if (mode == EPI_STORE) return launch_mfma_vec<LD_KC, LD_KM, TOut, false, EPI_STORE>(batch, plan.vec, dual, st, what);
         }
     }
-    return fail(PH_ERR_UNSUPPORTED, "%s: operand layout, output type and epilogue are not built together", what);
+    return fail(PH_ERR_LAUNCH, "%s: internal error, no kernel for this operand layout, output type and epilogue", what);
 }
 
 // The weight + compressor gradients (tail0, tail1; tail1 may be empty) with their riders in one launch: the
@@ -451,7 +473,7 @@ ph_status launch_tail(const Product *head, const Product &tail0, const Product &
         return n;
     };
     bool dual = head && !head_last && wgs(false) > 256 && wgs(true) <= 256;
-    static const char *dual_force = getenv("PHANTOM_TAIL_DUAL");
+    static const char *dual_force = tuning_env("PHANTOM_TAIL_DUAL");
     if (dual_force) dual = dual_force[0] == '1';
     tb.dual = dual;
     if (head) tb.head = mfma_params(*head, groups, 1, dual);
@@ -496,7 +518,7 @@ ph_status launch_fwd_kernel(const MfmaFwdBatch &fb, unsigned total_wg, hipStream
 ph_status launch_fwd_pair(const Product &update, const Product &compress, int groups, int vec, hipStream_t st, const char *what)
 {
     const int64_t tiles = tiles_of(update.M, update.N) * groups;
-    if (tiles * 8 > 0x7fffffff) return fail(PH_ERR_UNSUPPORTED, "%s: too many tiles", what);
+    if (tiles * 8 > 0x7fffffff) return fail(PH_ERR_LAUNCH, "%s: internal error, too many tiles (make_geo admits none such)", what);
     const bool dual = tiles > 256;                     // as for a launch of the update alone
     MfmaFwdBatch fb{};
     fb.update = mfma_params(update, groups, 1, dual);
@@ -549,7 +571,7 @@ ph_status launch_products(const GemmPlan &plan, const Product *prods_in, int cou
                 const double together = launch_us(t0 + t1, std::max(prods[0].K, prods[1].K));
                 const double apart = launch_us(t0, prods[0].K) + launch_us(t1, prods[1].K) + 2.5;
                 pair = together < apart;
-                static const char *force = getenv("PHANTOM_PAIR");
+                static const char *force = tuning_env("PHANTOM_PAIR");
                 if (force) pair = force[0] == '1';
             }
             if (pair || count == 1) return launch_mfma<TOut>(plan, prods, count, groups, st, count == 2 ? what : names[0]);
@@ -589,7 +611,7 @@ struct FwdArgs {
     const void *X, *Lw, *Cw, *Dw, *bias, *G;
     void *Y, *g_own, *A_save;
     bool a_f32;   // step only: A_save is float
-    bool a_deriv; // step only: A_save receives sigma'(A) in fp16 instead of A
+    bool a_deriv; // step only: A_save receives sigma'(A), in float, instead of A
     const struct OutputError *mse;   // step only, last layer: form the MSE output error in the update's epilogue
 };
 
@@ -668,7 +690,7 @@ ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
     const int64_t tiles_both = (tiles_of(B, so) + tiles_of(B, k)) * g.groups;
     if (thin && tiles_both > 256) {
         if constexpr (std::is_same<T, bf16_t>::value) {
-            static const char *force = getenv("PHANTOM_FWD_PAIR");     // =0: two launches (for measurements)
+            static const char *force = tuning_env("PHANTOM_FWD_PAIR");     // =0: two launches (for measurements)
             if (!(force && force[0] == '0'))
                 return launch_fwd_pair(update, compress, g.groups, g.vec, st, "layer update + thin compression");
         }
@@ -688,7 +710,7 @@ struct BwdArgs {
     void *dG_send;
     const void *delta_ready;   // step only: delta already formed (dY, S unused)
     bool dx_S_f32;             // step only: dx_S holds float
-    bool dx_S_deriv;           // step only: dx_S holds sigma' itself, in fp16
+    bool dx_S_deriv;           // step only: dx_S holds sigma' itself, in float
     const void *dx_S;          // step only: multiply dX by sigma'(dx_S) on the way out, which makes it the
                                //   previous layer's delta with a single rounding (Eq. (backprop))
     float *dx_colsum;          // step only: zeroed [groups, s]; the input-gradient product adds the column sums
@@ -704,7 +726,18 @@ struct BwdArgs {
     bool *ride_sgd_done;       //   whether it did
     LossTail *loss_tail;       // step only, last layer: the first memory-bound kernel of this backward finishes
                                //   the loss as a rider and clears loss_tail->partial; left alone if there is none
+    void *tap_dG_send;         // step only, optional: copies of this layer's dG_send / (all ranks) dg_own, taken right
+    void *tap_dg_own;          //   after the launch that finishes each
 };
+
+// copy of a tensor for a tap of the step (count elements of the storage type)
+template <typename T>
+ph_status tap_copy(void *dst, const void *src, int64_t count, hipStream_t st)
+{
+    if (!dst || !src || count <= 0) return PH_OK;
+    hipLaunchKernelGGL((copy_kernel<T>), dim3(blocks_for(count)), dim3(256), 0, st, (const T *)src, (T *)dst, count);
+    return check_launch("tap copy");
+}
 
 template <typename T>
 ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t st)
@@ -800,22 +833,24 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
     // Riders of the weight-gradient launch (MfmaTailBatch) exist on the matrix-core path for launches of at most one
     // tile per compute unit.  PHANTOM_TAIL=0 switches them off (for measurements).
     const int64_t tail_tiles = (tiles_of(dw.M, dw.N) + tiles_of(dc.M, dc.N)) * g.groups;
-    static const char *tail_force = getenv("PHANTOM_TAIL");
+    static const char *tail_force = tuning_env("PHANTOM_TAIL");
     const bool riders = std::is_same<T, bf16_t>::value && g.vec > 0 && tail_tiles <= 256 && !(tail_force && tail_force[0] == '0');
     // One rank, no input gradient wanted (the first layer): this layer's error compression has no launch to share
     // with the input gradient and nothing waits for it, so it rides with the weight gradients.
     const bool send_rides = riders && !g.all && !b.dX && q > 0;
 
     const GemmPlan plan_x{LD_KC, LD_KM, g.vec, false};
+    const int64_t send_count = (int64_t)g.groups * q * B * k;
     if (g.all) {
         // the input gradient needs dg_own, which is the sum of what all ranks send: three launches
         if (!b.send_done) PH_TRY((launch_products<T, T>(plan_x, &send, 1, g.groups, st, "error compression")));
+        PH_TRY(tap_copy<T>(b.tap_dG_send, b.dG_send, send_count, st));
         // Reduce-scatter as a sum on read: the input gradient's loader sums the p-1 senders' slices while it stages
         // the one reduction tile that holds dg_own, and writes dg_own out for the compressor gradient.  Conditions:
         // the block starts on a tile boundary of the reduction index and fits one tile (so a multiple of 64,
         // k a divisor of 64), 16-byte vectors, and at most 8 ranks: a thread has the loads of seven senders
         // in flight at a time, and with 16 ranks the step got 0.4 % slower instead of 1.8 % faster.  PHANTOM_RS_ON_READ=0 keeps the kernel of its own (for measurements).
-        static const char *rs_force = getenv("PHANTOM_RS_ON_READ");
+        static const char *rs_force = tuning_env("PHANTOM_RS_ON_READ");
         const bool sum_on_read = std::is_same<T, bf16_t>::value && g.vec == 8 && q > 0 && b.dX && g.p <= 8 && k <= KT &&
                                  KT % k == 0 && so % KT == 0 && !(rs_force && rs_force[0] == '0');
         if (sum_on_read) {
@@ -837,10 +872,12 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
             PH_TRY(check_launch("reduce-scatter"));
         }
         PH_TRY((launch_products<T, T>(plan_x, &dx, 1, g.groups, st, "input gradient")));
+        PH_TRY(tap_copy<T>(b.tap_dg_own, b.dg_own, (int64_t)g.groups * B * k, st));
     } else if (!send_rides) {
         Product both[2] = {dx, send};
         PH_TRY((launch_products<T, T>(plan_x, both, 2, g.groups, st, "input gradient + error compression",
                                       "input gradient", "error compression")));
+        PH_TRY(tap_copy<T>(b.tap_dG_send, b.dG_send, send_count, st));
     }
 
     Product grads[2] = {dw, dc};
@@ -888,11 +925,13 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
                                    rounds));
                 if (b.below_done) *b.below_done = with_head && !send_rides;
                 if (b.ride_sgd_done) *b.ride_sgd_done = with_sgd;
+                if (send_rides) PH_TRY(tap_copy<T>(b.tap_dG_send, b.dG_send, send_count, st));
                 return PH_OK;
             }
         }
     }
     // a lone weight-gradient product with few tiles may split its reduction; a pair never does
+    // (send_rides never gets here: its launch above carries the error compression)
     return launch_products<T, float>(GemmPlan{LD_KM, LD_KM, g.vec, true}, grads, q > 0 ? 2 : 1, g.groups, st,
                                      "weight + compressor gradients", "weight gradients", "compressor gradient");
 }
@@ -940,9 +979,9 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
 
     // What the backward pass needs of a layer's pre-activation A is sigma'(A) alone.  ReLU reads it off the
     // layer's output.  GELU in bf16 storage has the forward epilogue, which evaluates erf and exp for
-    // sigma(A) anyway, store sigma'(A) in fp16 (values in [-0.13, 1.13]; 11 significant bits, four times finer
-    // than the bf16 that delta is rounded to): half the bytes of an fp32 A both ways and no second
-    // evaluation in the input-gradient epilogue.  fp32 storage keeps A itself.
+    // sigma(A) anyway, store sigma'(A) in float: the bytes of an fp32 A and no second evaluation in the
+    // input-gradient epilogue.  (Any coarser grid for that factor moves delta across bf16 rounding
+    // boundaries often enough to show after a few layers.)  fp32 storage keeps A itself.
     const bool gelu = g.act == PH_ACT_GELU;
     const bool save_deriv = gelu && std::is_same<T, bf16_t>::value;
 
@@ -990,6 +1029,11 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
                   (mse_in_update && l == L - 1) ? &oe : nullptr};
         PH_TRY(fwd_impl<T>(geos[(size_t)l], f, st));
         in = w.Y[l];
+        if (a.taps) {
+            const Geo &gl = geos[(size_t)l];
+            if (a.taps->Y) PH_TRY(tap_copy<T>(a.taps->Y[l], w.Y[l], (int64_t)gl.groups * B * gl.so, st));
+            if (a.taps->g_own && q) PH_TRY(tap_copy<T>(a.taps->g_own[l], w.G[l], (int64_t)gl.groups * B * gl.k, st));
+        }
     }
     if (a.Y_out) {
         hipLaunchKernelGGL((copy_kernel<T>), dim3(blocks_for(act_count)), dim3(256), 0, st, (const T *)w.Y[L - 1],
@@ -1019,6 +1063,8 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
                                w.mse_partial, clear_at, clear_count);
         PH_TRY(check_launch("output error"));
     }
+
+    if (a.taps && a.taps->delta) PH_TRY(tap_copy<T>(a.taps->delta[L - 1], w.dYa, act_count, st));   // delta_L, Eq. (deltaL)
 
     void *dY = w.dYa, *dX = w.dYb;    // delta of the current layer / of the layer below
     bool send_done = false;           // the current layer's error compression went out with the layer above
@@ -1060,7 +1106,13 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
         b.ride_sgd_done = &sgd_rode;
         const Geo &gl = geos[(size_t)l];
         const int64_t si = gl.si, so = gl.so, k = gl.k;
+        if (a.taps) {
+            b.tap_dG_send = (a.taps->dG_send && q) ? a.taps->dG_send[l] : nullptr;
+            b.tap_dg_own = (a.taps->dg_own && q && g.all) ? a.taps->dg_own[l] : nullptr;
+        }
         PH_TRY(bwd_impl<T>(gl, b, w.bwd, st));
+        // what the input gradient's epilogue left in dX is delta_{l-1} (Eq. (backprop), sigma' applied)
+        if (a.taps && a.taps->delta && l > 0) PH_TRY(tap_copy<T>(a.taps->delta[l - 1], dX, (int64_t)g.groups * B * si, st));
         if (have_pending && !sgd_rode) PH_TRY(launch_sgd(pending, 4, pending_largest, pending_elems));
         have_pending = false;
 
@@ -1125,7 +1177,7 @@ ph_status check_ptr_array(const void *const *arr, int L, const char *name)
 
 extern "C" {
 
-int32_t phantom_abi_version(void) { return 2; }
+int32_t phantom_abi_version(void) { return 3; }
 
 ph_status phantom_profile_begin(int32_t max_launches)
 {
@@ -1224,10 +1276,13 @@ ph_status phantom_layer_bwd(const ph_problem *prob, const void *dY, const void *
     return g.dtype == PH_F32 ? bwd_impl<float>(g, b, w, st) : bwd_impl<bf16_t>(g, b, w, st);
 }
 
-ph_status phantom_ffn_step(const ph_problem *prob, const ph_step_args *args, void *workspace, size_t workspace_bytes,
-                           void *hip_stream)
+}  // extern "C"
+
+namespace {
+
+// The argument checks of a step, all made before any GPU call; `ws_need`: the bytes of workspace it takes.
+ph_status check_step_args(const ph_problem *prob, const ph_step_args *args, std::vector<Geo> &geos, size_t &ws_need)
 {
-    std::vector<Geo> geos;
     PH_TRY(make_geos(prob, geos));
     const Geo &g = geos[0];
     if (!args) return fail(PH_ERR_INVALID_ARG, "args is NULL");
@@ -1263,13 +1318,43 @@ ph_status phantom_ffn_step(const ph_problem *prob, const ph_step_args *args, voi
         if (g.q > 0 && args->dCw) PH_TRY(check_ptr_array((const void *const *)args->dCw, L, "dCw"));
         if (g.q > 0 && args->dDw) PH_TRY(check_ptr_array((const void *const *)args->dDw, L, "dDw"));
     }
+    if (args->taps) {
+        const ph_step_taps &t = *args->taps;
+        const struct { void *const *arr; const char *name; } taps[] = {
+            {t.Y, "taps.Y"}, {t.g_own, "taps.g_own"}, {t.delta, "taps.delta"}, {t.dG_send, "taps.dG_send"}, {t.dg_own, "taps.dg_own"}};
+        for (const auto &tp : taps)
+            for (int l = 0; tp.arr && l < L; ++l) {
+                char nm[64];
+                snprintf(nm, sizeof nm, "%s[%d]", tp.name, l);
+                PH_TRY(optional(tp.arr[l], nm));
+            }
+    }
     Arena sizing{nullptr, 0};
     carve_step(sizing, geos);
-    PH_TRY(check_ws(workspace, workspace_bytes, sizing.used));
+    ws_need = sizing.used;
+    return PH_OK;
+}
+
+ph_status run_step(const std::vector<Geo> &geos, const ph_step_args *args, void *workspace, void *hip_stream)
+{
     Arena a{(char *)workspace, 0};
     StepWs w = carve_step(a, geos);
     hipStream_t st = (hipStream_t)hip_stream;
-    return g.dtype == PH_F32 ? step_impl<float>(geos, *args, w, st) : step_impl<bf16_t>(geos, *args, w, st);
+    return geos[0].dtype == PH_F32 ? step_impl<float>(geos, *args, w, st) : step_impl<bf16_t>(geos, *args, w, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+ph_status phantom_ffn_step(const ph_problem *prob, const ph_step_args *args, void *workspace, size_t workspace_bytes,
+                           void *hip_stream)
+{
+    std::vector<Geo> geos;
+    size_t ws_need = 0;
+    PH_TRY(check_step_args(prob, args, geos, ws_need));
+    PH_TRY(check_ws(workspace, workspace_bytes, ws_need));
+    return run_step(geos, args, workspace, hip_stream);
 }
 
 }  // extern "C"

@@ -24,13 +24,15 @@ def test_library_exports_every_declared_symbol():
             "phantom_last_error"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
-    assert ph.abi_version() == 2
+    assert ph.abi_version() == 3
 
 
 def test_struct_layout_matches_header():
     assert ctypes.sizeof(ph.PhProblem) == 4 * 8 + 4 * 4 + 2 * 8
     from paper_2508_00960_amd.binding import PhStepArgs
-    assert ctypes.sizeof(PhStepArgs) == 18 * 8 + 8
+    assert ctypes.sizeof(PhStepArgs) == 18 * 8 + 8 + 8
+    from paper_2508_00960_amd.binding import PhStepTaps
+    assert ctypes.sizeof(PhStepTaps) == 5 * 8
 
 
 @pytest.mark.parametrize("kwargs,fragment", [
@@ -90,6 +92,43 @@ def test_step_checks_per_layer_pointer_arrays():
         ph.ffn_step(prob, ok, ok, two, two, [ok, None], two, G=two, mode="forward", workspace=(0x2000, 1 << 40))
     with pytest.raises(ValueError):
         ph.ffn_step(prob, ok, ok, [ok], two, two, two)
+
+
+def test_capability_limits_are_found_before_any_launch():
+    """A problem that is valid but beyond what the kernels index (PH_ERR_UNSUPPORTED) is refused from its shapes
+    alone, on a host without a GPU: nothing can have been launched."""
+    ok = 0x1000
+    # 2^22 batch rows x 64 ranks of 2^22 neurons: 2^15 x 2^15 x 64 output tiles in the layer update
+    huge = ph.make_problem((1 << 22) * 64, 64, 8, 1 << 22, dtype="bf16", rank=-1)
+    with pytest.raises(ph.PhantomError) as e:
+        ph.workspace_bytes(huge)
+    assert e.value.status == -2 and "output tiles" in str(e.value)
+    with pytest.raises(ph.PhantomError) as e:
+        ph.layer_fwd(huge, ok, ok, ok, ok, ok, ok, ok, ok, None)
+    assert e.value.status == -2
+    with pytest.raises(ph.PhantomError) as e:
+        ph.ffn_step(huge, ok, ok, [ok], [ok], [ok], [ok], loss=ok, mode="no_update", workspace=(0x2000, 1 << 40))
+    assert e.value.status == -2
+    wide = ph.make_problem((1 << 23) * 2, 2, 8, 16, dtype="bf16")      # n/p beyond 2^22
+    with pytest.raises(ph.PhantomError) as e:
+        ph.workspace_bytes(wide)
+    assert e.value.status == -2
+
+
+def test_production_library_reads_no_tuning_variable(monkeypatch):
+    """The switches that force a launch schedule exist only in a build made for measurements."""
+    data = open(ph.library_path(), "rb").read()
+    for name in (b"PHANTOM_DUAL", b"PHANTOM_TAIL_DUAL", b"PHANTOM_PAIR", b"PHANTOM_FWD_PAIR", b"PHANTOM_RS_ON_READ"):
+        assert name not in data, name
+
+
+def test_step_taps_are_checked():
+    prob = ph.make_problem(256, 4, 8, 32, layers=2, dtype="bf16")
+    ok = 0x1000
+    two = [ok, ok]
+    with pytest.raises(ph.PhantomError, match=r"taps.delta\[1\] is not 16-byte aligned"):
+        ph.ffn_step(prob, ok, ok, two, two, two, two, G=two, dg_own=two, loss=ok, mode="no_update",
+                    workspace=(0x2000, 1 << 40), taps={"delta": [ok, ok + 4]})
 
 
 def test_workspace_grows_with_the_problem():

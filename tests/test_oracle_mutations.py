@@ -85,15 +85,15 @@ def _compressor_rows_reversed(X, Cw):
     return _orig["compress"](X, Cw[::-1].copy())
 
 
-def _derivative_at_the_output(act, dY, A, storage="f32", deriv_f16=False):
+def _derivative_at_the_output(act, dY, A, storage="f32"):
     """sigma' evaluated at sigma(A) instead of A (right for ReLU, wrong for a smooth activation)."""
     if act == "gelu":
         import math
         Y = 0.5 * A * (1.0 + np.vectorize(math.erf)(A / math.sqrt(2.0)))
-        return _orig["delta_of"](act, dY, Y, storage, deriv_f16)
+        return _orig["delta_of"](act, dY, Y, storage)
     if act == "identity":
-        return 2.0 * _orig["delta_of"](act, dY, A, storage, deriv_f16)
-    return _orig["delta_of"](act, dY, np.abs(A), storage, deriv_f16)       # ReLU' = 1 everywhere but at 0
+        return 2.0 * _orig["delta_of"](act, dY, A, storage)
+    return _orig["delta_of"](act, dY, np.abs(A), storage)       # ReLU' = 1 everywhere but at 0
 
 
 def _error_compression_peers_reversed(Dw, delta):

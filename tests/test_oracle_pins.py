@@ -347,43 +347,22 @@ def test_bf16_rounding_matches_torch():
     assert np.array_equal(pin.round_to_storage(vals, "bf16"), want)
 
 
-def test_f16_rounding_matches_numpy():
-    """Nearest-even rounding to IEEE half against numpy's conversion: normal numbers, exact ties,
-    the subnormal range, and the values sigma' takes."""
-    vals = np.concatenate([
-        pin.normal((4096,), seed=2, tensor="aux") * 0.5,
-        pin.normal((512,), seed=3, tensor="aux") * 2.0 ** -16,            # subnormal halves
-        np.array([1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, -(1.0 + 2.0 ** -11), 0.0, 2.0 ** -24, 2.0 ** -25,
-                  3 * 2.0 ** -25, 2.0 ** -14 - 2.0 ** -26, 1.1289, -0.1289, 0.5, 2047.5, 2048.5 * 2]),
-    ])
-    want = vals.astype(np.float16).astype(np.float64)
-    got = np.array([oracle.lib().pho_round_f16(float(v)) for v in vals])
-    assert np.array_equal(got, want)
-
-
-def test_a_bf16_step_uses_the_half_precision_derivative():
-    """delta_of with deriv_f16: the factor that multiplies dY is sigma'(A) on the half grid, and only that
-    changes (dY = 1 makes delta the factor itself); fp32 storage never rounds it."""
-    a = np.linspace(-5, 5, 401).reshape(1, -1)
-    ones = np.ones_like(a)
-    exact = oracle.delta_of("gelu", ones, a)
-    half = oracle.delta_of("gelu", ones, a, "f32", True)
-    assert np.array_equal(half, exact.astype(np.float16).astype(np.float64))
-    assert 0 < np.abs(half - exact).max() <= 2.0 ** -11 * 1.13
-    both = oracle.delta_of("gelu", 3.0 * ones, a, "bf16", True)
-    assert np.array_equal(both, oracle.round_bf16(3.0 * half))
-    for act in ("relu", "identity"):
-        assert np.array_equal(oracle.delta_of(act, ones, a, "f32", True), oracle.delta_of(act, ones, a))
-    # the step: bf16 storage rounds the factor, fp32 storage does not
+def test_sigma_prime_factor_of_a_bf16_step_is_unrounded():
+    """Eq. (deltaL) / Eq. (backprop) multiply by sigma'(b + z) as it is: in a bfloat16-storage step the only
+    rounding in delta_{l-1} is the one of the finished product, and the sigma' factor is torch's GELU
+    derivative of the unrounded pre-activation (fp64), not a value on any coarser grid."""
     prob = pin.Problem(n=16, p=2, k=3, batch=4, layers=2, act="gelu", dtype="bf16", rank=-1)
     data = pin.all_rank_step_inputs(prob, seed=9)
-    for storage, rounded in (("bf16", True), ("f32", False)):
-        st = oracle.ffn_step("gelu", data["X0"], data["T"], data["layers"], lr=0.01, storage=storage)
-        A, dX = st["forward"]["A"][0], st["grads"][1]["dX"]
-        want = np.stack([oracle.delta_of("gelu", dX[j], A[j], storage, rounded) for j in range(2)])
-        assert np.array_equal(st["grads"][0]["delta"], want)
-        if rounded:
-            assert not np.array_equal(want, np.stack([oracle.delta_of("gelu", dX[j], A[j], storage) for j in range(2)]))
+    st = oracle.ffn_step("gelu", data["X0"], data["T"], data["layers"], lr=0.01, storage="bf16")
+    A, dX = st["forward"]["A"][0], st["grads"][1]["dX"]
+    at = _t(A, grad=True)
+    torch.nn.functional.gelu(at).backward(torch.ones_like(at))
+    want = oracle.round_bf16(dX * at.grad.numpy())
+    got = st["grads"][0]["delta"]
+    # the two evaluations of erf differ in the last bits of fp64: a product that lands within 1e-13 of a
+    # bfloat16 tie could round either way; everything else is identical
+    assert np.mean(got == want) > 0.99 and np.abs(got - want).max() <= 2.0 ** -7 * np.abs(want).max()
+    assert not np.array_equal(A, oracle.round_bf16(A))
 
 
 def test_gelu_and_its_derivative_match_torch():
