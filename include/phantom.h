@@ -211,6 +211,21 @@ typedef struct {
 ph_status phantom_ffn_step(const ph_problem *prob, const ph_step_args *args,
                            void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * phantom_ffn_step for callers that cannot allocate device memory: code under HIP graph capture, serving
+ * loops that must not call hipMalloc, harnesses that forbid it.  Same arguments, same kernels and same
+ * results as phantom_ffn_step, but the workspace is the library's own: a file-scope device array of
+ * phantom_static_workspace_bytes() = 64 MiB that every GPU the library runs on holds until the process
+ * ends.  The call allocates and frees nothing (no hipMalloc, hipFree or allocating library routine); its
+ * first call on a device looks the array's address up there (hipGetSymbolAddress), later calls reuse it.
+ * A problem whose step needs more than that (phantom_workspace_bytes) is refused with PH_ERR_WORKSPACE
+ * before any GPU call: use phantom_ffn_step with a workspace of the caller's.
+ * All calls on one GPU share that one array, which keeps the last call's contents; the step clears what it
+ * needs cleared itself.  Two calls that overlap on one GPU (different streams, or threads) race: serialise them.
+ */
+ph_status phantom_ffn_step_static(const ph_problem *prob, const ph_step_args *args, void *hip_stream);
+size_t phantom_static_workspace_bytes(void);
+
 /* Message of the calling thread's last error ("" if none).  Host string owned by the library. */
 const char *phantom_last_error(void);
 

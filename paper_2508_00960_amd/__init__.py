@@ -3,6 +3,6 @@
 Thin binding over libphantom.so; see include/phantom.h for the contract.
 """
 from .binding import (  # noqa: F401
-    ACTS, DTYPES, STEP_MODES, PhantomError, PhProblem, abi_version, ffn_step, layer_bwd, layer_fwd, last_error,
-    library_path, load, make_problem, profile_begin, profile_end, workspace_bytes,
+    ACTS, DTYPES, STEP_MODES, PhantomError, PhProblem, abi_version, ffn_step, ffn_step_static, layer_bwd, layer_fwd, last_error,
+    library_path, load, make_problem, profile_begin, profile_end, static_workspace_bytes, workspace_bytes,
 )

@@ -100,6 +100,9 @@ def load():
     lib.phantom_layer_bwd.argtypes = [prob] + [vp] * 14 + [vp, sz, vp]
     lib.phantom_ffn_step.restype = ctypes.c_int
     lib.phantom_ffn_step.argtypes = [prob, ctypes.POINTER(PhStepArgs), vp, sz, vp]
+    lib.phantom_ffn_step_static.restype = ctypes.c_int
+    lib.phantom_ffn_step_static.argtypes = [prob, ctypes.POINTER(PhStepArgs), vp]
+    lib.phantom_static_workspace_bytes.restype = ctypes.c_size_t
     lib.phantom_profile_begin.restype = ctypes.c_int
     lib.phantom_profile_begin.argtypes = [ctypes.c_int32]
     lib.phantom_profile_end.restype = ctypes.c_int
@@ -263,7 +266,7 @@ def _ptr_array(tensors: Optional[Sequence], layers: int):
 
 def ffn_step(prob, X0, T, Lw, Cw, Dw, bias, *, Lw_master=None, Cw_master=None, Dw_master=None, bias_master=None,
              G=None, dg_own=None, dLw=None, dCw=None, dDw=None, dbias=None, Y_out=None, loss=None, lr=0.0,
-             mode="train", workspace=None, stream=None, taps=None):
+             mode="train", workspace=None, stream=None, taps=None, static=False):
     """phantom_ffn_step; per-layer arguments are sequences of prob.layers tensors (or None).
     taps: dict with any of "Y", "g_own", "delta", "dG_send", "dg_own" -> sequence of prob.layers tensors (ph_step_taps)."""
     L = prob.layers
@@ -303,5 +306,18 @@ def ffn_step(prob, X0, T, Lw, Cw, Dw, bias, *, Lw_master=None, Cw_master=None, D
             setattr(tp, name, ptr)
         keep.append(tp)
         args.taps = ctypes.pointer(tp)
+    if static:
+        _check(load().phantom_ffn_step_static(ctypes.byref(prob), ctypes.byref(args), _stream(stream)))
+        return
     wp, wb = _ws(workspace)
     _check(load().phantom_ffn_step(ctypes.byref(prob), ctypes.byref(args), wp, wb, _stream(stream)))
+
+
+def ffn_step_static(prob, X0, T, Lw, Cw, Dw, bias, **kwargs):
+    """phantom_ffn_step_static: the step on the library's own scratch array (no workspace argument)."""
+    assert "workspace" not in kwargs
+    ffn_step(prob, X0, T, Lw, Cw, Dw, bias, static=True, **kwargs)
+
+
+def static_workspace_bytes() -> int:
+    return int(load().phantom_static_workspace_bytes())

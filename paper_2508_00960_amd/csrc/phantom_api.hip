@@ -10,6 +10,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <algorithm>
+#include <mutex>
 #include <string>
 #include <type_traits>
 #include <vector>
@@ -1343,6 +1344,34 @@ ph_status run_step(const std::vector<Geo> &geos, const ph_step_args *args, void 
     return geos[0].dtype == PH_F32 ? step_impl<float>(geos, *args, w, st) : step_impl<bf16_t>(geos, *args, w, st);
 }
 
+// ---- the step for callers that cannot allocate -------------------------------------------------
+// Its workspace is this array: device memory that every GPU the library runs on holds from the moment the
+// code object is loaded there until the process ends.  In host code the array's name is only a handle:
+// the address a kernel can use comes from hipGetSymbolAddress, once per device, with that device current.
+constexpr size_t STATIC_WS_BYTES = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_WS_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+void *g_scratch_ptr[MAX_DEVICES];      // per device; written once under g_scratch_lock
+std::mutex g_scratch_lock;
+
+ph_status scratch_of_current_device(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(PH_ERR_LAUNCH, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(PH_ERR_UNSUPPORTED, "device index %d beyond %d", dev, MAX_DEVICES);
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) return fail(PH_ERR_LAUNCH, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return PH_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1355,6 +1384,21 @@ ph_status phantom_ffn_step(const ph_problem *prob, const ph_step_args *args, voi
     PH_TRY(check_step_args(prob, args, geos, ws_need));
     PH_TRY(check_ws(workspace, workspace_bytes, ws_need));
     return run_step(geos, args, workspace, hip_stream);
+}
+
+size_t phantom_static_workspace_bytes(void) { return STATIC_WS_BYTES; }
+
+ph_status phantom_ffn_step_static(const ph_problem *prob, const ph_step_args *args, void *hip_stream)
+{
+    std::vector<Geo> geos;
+    size_t ws_need = 0;
+    PH_TRY(check_step_args(prob, args, geos, ws_need));
+    if (ws_need > STATIC_WS_BYTES)
+        return fail(PH_ERR_WORKSPACE, "the step needs %zu bytes of workspace, the library's own scratch array holds %zu: "
+                                      "use phantom_ffn_step with a workspace of the caller's", ws_need, STATIC_WS_BYTES);
+    void *ws = nullptr;
+    PH_TRY(scratch_of_current_device(&ws));
+    return run_step(geos, args, ws, hip_stream);
 }
 
 }  // extern "C"

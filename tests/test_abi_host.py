@@ -131,6 +131,16 @@ def test_step_taps_are_checked():
                     workspace=(0x2000, 1 << 40), taps={"delta": [ok, ok + 4]})
 
 
+def test_static_step_refuses_a_problem_beyond_its_scratch_array_on_the_host():
+    big = ph.make_problem(16384, 16, 64, 4096, 8, "gelu", "bf16", 0)
+    assert ph.workspace_bytes(big) > ph.static_workspace_bytes() == 64 << 20
+    ok = 0x1000
+    eight = [ok] * 8
+    with pytest.raises(ph.PhantomError) as e:
+        ph.ffn_step_static(big, ok, ok, eight, eight, eight, eight, G=eight, dg_own=eight, loss=ok, mode="no_update")
+    assert e.value.status == -3 and "scratch" in str(e.value)
+
+
 def test_workspace_grows_with_the_problem():
     small = ph.workspace_bytes(ph.make_problem(256, 4, 8, 32, layers=2))
     big = ph.workspace_bytes(ph.make_problem(4096, 8, 32, 1024, layers=4, dtype="bf16", rank=-1))
