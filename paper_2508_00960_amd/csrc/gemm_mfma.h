@@ -35,7 +35,7 @@
 //   gemm_mfma_kernel       one product, or two of the same operand layout and output type
 //   gemm_mfma_tail_kernel  weight + compressor gradients with riders of other layouts (the error compression of
 //                          the layer below, the SGD update of the layer above)
-//   gemm_mfma_fwd_kernel   a rank's thin compression and layer update
+//   gemm_mfma_fwd_kernel   a rank's layer update with the thin compression shared out over its workgroups
 #pragma once
 #include "common.h"
 #include "elementwise.h"    // SgdBatch, sgd_rider
@@ -1050,34 +1050,40 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_tail_kernel(MfmaTailBatch tb
     }
 }
 
-// One rank's forward of a layer in one launch: the thin compression g = C y (see thin_product.h) and the layer
-// update, which in one-rank mode do not depend on each other (the peers' g are inputs).  The compression's
-// workgroups come first (32 rows each, all 8 wavefronts splitting the reduction range), so they are
-// dispatched first and the update takes over their compute units as they finish.
+// One rank's forward of a layer in one launch: the layer update, and the thin compression g = C y (see
+// thin_product.h), which in one-rank mode do not depend on each other (the peers' g are inputs).  Every
+// workgroup takes one tile (or pair of tiles) of the update and then its share of the compression's rows:
+// thin_rows consecutive rows (a multiple of 16), all 8 wavefronts splitting the reduction range.  The rows are
+// read again right after the update streamed them through the same XCD's L2 (workgroup w's rows lie in the
+// band of tile rows that its XCD works on), and no compute unit waits for a compression workgroup: as
+// workgroups of their own in front of the update's, the compression's kept half of the device from the
+// update for 9 us of a 38 us launch (configuration 5, k = 64: 40.9 -> 38.4 us per launch; at configuration 4,
+// where each workgroup's share is 16 rows, the two arrangements take the same time: a share costs a chain of
+// latencies, load -> multiply -> exchange -> store, about 5 us however short it is, and starting its loads
+// ahead of the update's epilogue changed nothing).
 struct MfmaFwdBatch {
     MfmaParams update;
     const __bf16 *X, *C;     // compression operands: X [M, K] per group, C [N, K] per group
     __bf16 *G;               // [M, N] per group
     int M, N, K;
     int64_t x_g, c_g, o_g;
-    int thin_per_group;      // workgroups of the compression per group = ceil(M / 32)
-    int thin_wg;             // = thin_per_group * groups
-    int update_first;        // thin_wg rounded up to a multiple of 8; the workgroups in between do nothing
+    int wg_per_group;        // workgroups of the update per group
+    int thin_rows;           // rows of the compression per workgroup: wg_per_group * thin_rows >= M
 };
 
 template <int VEC, bool DUAL>
 __global__ __launch_bounds__(512, 1) void gemm_mfma_fwd_kernel(MfmaFwdBatch fb)
 {
-    const int id = blockIdx.x;
-    if (id < fb.update_first) {                        // uniform
-        if (id >= fb.thin_wg) return;
-        extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-        const int grp = id / fb.thin_per_group, m0 = (id - grp * fb.thin_per_group) * THIN_ROWS;
-        if (fb.N <= 32) thin_workgroup<1, 8>(fb.X, fb.C, fb.G, fb.M, fb.N, fb.K, fb.x_g, fb.c_g, fb.o_g, m0, grp, (float *)smem_raw);
-        else thin_workgroup<2, 8>(fb.X, fb.C, fb.G, fb.M, fb.N, fb.K, fb.x_g, fb.c_g, fb.o_g, m0, grp, (float *)smem_raw);
-    } else {
-        mfma_workgroup<LD_KC, LD_KC, VEC, VEC, __bf16, false, DUAL, EPI_BIAS_ACT>(
-            fb.update, xcd_order(id, fb.update_first, fb.update.total_wg));
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    const int wg = xcd_order((int)blockIdx.x, 0, fb.update.total_wg);
+    mfma_workgroup<LD_KC, LD_KC, VEC, VEC, __bf16, false, DUAL, EPI_BIAS_ACT>(fb.update, wg);
+    const int grp = wg / fb.wg_per_group;
+    const int first = (wg - grp * fb.wg_per_group) * fb.thin_rows;
+    const int last = min(first + fb.thin_rows, fb.M);
+    for (int m0 = first; m0 < last; m0 += THIN_ROWS) {           // uniform
+        __syncthreads();                                         // the epilogue, or the block before, is done with LDS
+        if (fb.N <= 32) thin_workgroup<1, 8>(fb.X, fb.C, fb.G, last, fb.N, fb.K, fb.x_g, fb.c_g, fb.o_g, m0, grp, (float *)smem_raw);
+        else thin_workgroup<2, 8>(fb.X, fb.C, fb.G, last, fb.N, fb.K, fb.x_g, fb.c_g, fb.o_g, m0, grp, (float *)smem_raw);
     }
 }
 

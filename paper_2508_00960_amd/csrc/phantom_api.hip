@@ -526,10 +526,9 @@ ph_status launch_fwd_pair(const Product &update, const Product &compress, int gr
     fb.X = (const __bf16 *)compress.a.p0; fb.C = (const __bf16 *)compress.b.p0; fb.G = (__bf16 *)compress.o.p0;
     fb.M = (int)compress.M; fb.N = (int)compress.N; fb.K = (int)compress.K;
     fb.x_g = compress.a.g0; fb.c_g = compress.b.g0; fb.o_g = compress.o.g0;
-    fb.thin_per_group = (int)((compress.M + THIN_ROWS - 1) / THIN_ROWS);
-    fb.thin_wg = fb.thin_per_group * groups;
-    fb.update_first = (fb.thin_wg + 7) & ~7;
-    const unsigned total = (unsigned)(fb.update_first + fb.update.total_wg);
+    fb.wg_per_group = fb.update.total_wg / groups;
+    fb.thin_rows = (int)(((compress.M + fb.wg_per_group - 1) / fb.wg_per_group + 15) / 16 * 16);
+    const unsigned total = (unsigned)fb.update.total_wg;
     ProfScope prof(what, update.M, update.N, update.K, groups, st, compress.M, compress.N, compress.K);
     switch (vec) {
     case 8: return dual ? launch_fwd_kernel<8, true>(fb, total, st, what) : launch_fwd_kernel<8, false>(fb, total, st, what);

@@ -22,6 +22,8 @@ typedef float thin_f32x16 __attribute__((ext_vector_type(16)));
 // One workgroup's share: rows [m0, m0 + 32) of group grp.  NF = number of 32-wide column blocks (1: N <= 32,
 // 2: N <= 64); WAVES wavefronts split the K / 16 reduction chunks (K is a multiple of 16); part: WAVES * NF * 1024
 // floats of LDS.  x_g, c_g, o_g: element offsets per group.
+// M: end of the rows this call may read and store (the matrix's row count, or the end of a shorter share of a
+// 32-row block: the MFMA rows beyond it repeat the last one and are dropped).
 template <int NF, int WAVES>
 __device__ __forceinline__ void thin_workgroup(const __bf16 *__restrict__ X, const __bf16 *__restrict__ C,
                                                __bf16 *__restrict__ G, int M, int N, int K, int64_t x_g, int64_t c_g,
