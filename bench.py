@@ -252,6 +252,51 @@ def measured_traffic(workload, row):
     return found if fresh else None
 
 
+def vendor_gemm_reference(c, shapes, groups):
+    """Context only, never part of `value`: what the vendor GEMM library (hipBLASLt / rocBLAS through torch.matmul)
+    takes for the bare matrix products of ONE layer of this workload at the same shapes and operand layouts,
+    without bias, activation, sigma' or any fusion, one product per call (torch.bmm over the ranks held).
+    Shows what a product of this shape costs on this chip apart from this library's kernels."""
+    import torch
+    si, so, k = shapes[-1]
+    B, q = c["batch"], c["p"] - 1
+    Kc = si + q * k
+
+    def r(*shape):
+        return torch.randn(*((groups,) + shape), device="cuda", dtype=torch.bfloat16)
+
+    def time_us(fn, iters=30):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / iters
+
+    xcat, wcat, delta = r(B, Kc), r(so, Kc), r(B, so)
+    out = {"layer update [B,Kc]x[so,Kc]^T": time_us(lambda: torch.bmm(xcat, wcat.transpose(1, 2)))}
+    if q:
+        x, cw = r(B, si), r(k, si)
+        out["compression [B,si]x[k,si]^T"] = time_us(lambda: torch.bmm(x, cw.transpose(1, 2)))
+    if c["mode"] != "forward":
+        lc, dcat = r(so + (k if q else 0), si), r(B, so + (k if q else 0))
+        out["input gradient [B,so+k]x[so+k,si]"] = time_us(lambda: torch.bmm(dcat, lc))
+        out["weight gradients [B,so]^Tx[B,Kc]"] = time_us(lambda: torch.bmm(delta.transpose(1, 2), xcat))
+        if q:
+            dw, dg, x = r(so, q * k), r(B, k), r(B, si)
+            out["error compression [B,so]x[so,(p-1)k]"] = time_us(lambda: torch.bmm(delta, dw))
+            out["compressor gradient [B,k]^Tx[B,si]"] = time_us(lambda: torch.bmm(dg.transpose(1, 2), x))
+    total = sum(out.values())
+    return {"per_layer_us": {name: round(us, 2) for name, us in out.items()}, "layer_us": round(total, 2),
+            "step_ms_products_only": total * c["layers"] * 1e-3,
+            "what": "torch.bmm (vendor GEMM library) on the bare products of the last layer's shapes, one call each, "
+                    "no epilogues; context, not a target and not this library's path"}
+
+
 def cpu_baseline(bench, sample_batch):
     """The fp64 oracle as it stands on the host cores, on a batch subset of the same workload."""
     import phantom_inputs as pin
@@ -290,6 +335,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of a HIP graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-vendor-reference", action="store_true", help="skip the torch.bmm timings of the bare products")
     ap.add_argument("--no-others", action="store_true", help="skip the other benchmark configurations (extra keys)")
     ap.add_argument("--cpu-sample-batch", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -395,6 +441,8 @@ def main():
                 "what": f"one layer [{c['n'] // c['p']} x {c['n']}] on batch {c['batch']}, step = {c['mode']}, x {c['layers']} layers"}
             del t
             torch.cuda.empty_cache()
+    if not args.no_vendor_reference:
+        out["vendor_gemm_reference"] = vendor_gemm_reference(c, b.shapes, b.groups)
     if not args.no_others:
         # the other benchmark configurations, same measurement (HIP graph replays between device syncs), inputs of
         # the same shapes and distributions drawn on the GPU

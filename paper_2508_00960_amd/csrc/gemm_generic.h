@@ -36,7 +36,10 @@ struct Epilogue {
     void *mse_delta;
     float *mse_partial;
     float mse_inv_b;
-    int32_t pad_;
+    int32_t aux_bits;    // MFMA kernel, 8-element vectors, ReLU only: aux holds ONE BIT per element, (stored output > 0), i.e.
+                         //   ReLU' as the backward pass reads it off the stored output, in an eighth of the bytes:
+                         //   EPI_BIAS_ACT writes it (bit u of byte (g*aux_g + m*aux_ld + n) / 8 = column n + u),
+                         //   EPI_DACT keeps or zeroes each element by it
 };
 
 constexpr int GT = 64;   // tile edge

@@ -629,7 +629,7 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
                     }
                 }
             } else {
-                if (ep.aux) {
+                if (ep.aux && !ep.aux_bits) {
                     if (ep.aux_deriv) {
                         FlV a;
 #pragma unroll
@@ -654,7 +654,13 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
                 }
             }
         } else if (EPI == EPI_DACT && ep.mode == EPI_DACT && ep.aux) {      // no aux: sigma' = 1, column sums only
-            if (ep.aux_deriv) {                        // sigma' itself, float
+            if (ep.aux_bits) {                         // one bit per element: ReLU' of the stored output
+                if constexpr (VEC == 8) {
+                    const unsigned bits = ((const uint8_t *)ep.aux)[aux_at >> 3];
+#pragma unroll
+                    for (int u = 0; u < VEC; ++u) x[u] = (bits >> u) & 1u ? x[u] : 0.f;
+                }
+            } else if (ep.aux_deriv) {                 // sigma' itself, float
                 const FlV a = *(const FlV *)((const float *)ep.aux + aux_at);
 #pragma unroll
                 for (int u = 0; u < VEC; ++u) x[u] *= a[u];
@@ -675,6 +681,14 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
 #pragma unroll
         for (int u = 0; u < VEC; ++u) o[u] = from_f32<TOut>(x[u]);
         *(OutV *)dst = o;
+        if constexpr (EPI == EPI_BIAS_ACT && VEC == 8) {
+            if (ep.mode == EPI_BIAS_ACT && ep.aux && ep.aux_bits) {     // uniform
+                unsigned bits = 0;
+#pragma unroll
+                for (int u = 0; u < VEC; ++u) bits |= ((float)o[u] > 0.f ? 1u : 0u) << u;
+                ((uint8_t *)ep.aux)[aux_at >> 3] = (uint8_t)bits;
+            }
+        }
         if (EPI == EPI_BIAS_ACT && sizeof(TOut) == 2 && ep.mode == EPI_BIAS_ACT && ep.mse_target) {      // uniform
             // the MSE output error of Eq. (deltaL) from the output as stored, rounded once
             const BfV t = *(const BfV *)((const __bf16 *)ep.mse_target + aux_at);

@@ -236,6 +236,7 @@ BwdWs carve_bwd(Arena &a, const Geo &g)
 
 struct StepWs {
     std::vector<void *> Y, A, G;
+    std::vector<void *> relu_bits;                  // per layer, or NULL: one bit per element of y_l (y_l > 0), see relu_bits_ok
     void *dYa, *dYb, *dG_send, *dg_own;
     float *dLw[2], *dCw[2], *dDw[2];                // two sets, used by alternate layers: a layer's update may still read
                                                     //   its gradients while the layer below writes its own
@@ -244,10 +245,22 @@ struct StepWs {
     BwdWs bwd;
 };
 
+// ReLU in bf16 storage: what the backward pass needs of layer l is the sign of its stored output alone.  Where the
+// update of layer l and the input gradient of layer l + 1 (whose epilogue multiplies by sigma'_l) both run on the
+// matrix cores with 8-element vectors, the update leaves one bit per element and the input gradient reads
+// that instead of the bf16 output: an eighth of the bytes (configuration 2: 8.4 MB -> 0.5 MB per launch).
+bool relu_bits_ok(const std::vector<Geo> &geos, size_t l)
+{
+    return l + 1 < geos.size() && geos[l].act == PH_ACT_RELU && geos[l].dtype == PH_BF16 && geos[l].vec == 8 &&
+           geos[l + 1].vec == 8;
+}
+
 // geos: every layer's shapes.  Buffers that are reused from layer to layer take the largest layer's size.
 StepWs carve_step(Arena &a, const std::vector<Geo> &geos)
 {
     StepWs w;
+    for (size_t l = 0; l < geos.size(); ++l)
+        w.relu_bits.push_back(relu_bits_ok(geos, l) ? a.take((size_t)geos[l].groups * geos[l].B * geos[l].so / 8) : nullptr);
     const Geo &g0 = geos[0];
     size_t act_max = 0, k_max = 0, lw_max = 0, cw_max = 0, dw_max = 0;
     int64_t dbias_total = 0;
@@ -612,6 +625,7 @@ struct FwdArgs {
     void *Y, *g_own, *A_save;
     bool a_f32;   // step only: A_save is float
     bool a_deriv; // step only: A_save receives sigma'(A), in float, instead of A
+    bool a_bits;  // step only, ReLU: A_save receives one bit per element (stored output > 0)
     const struct OutputError *mse;   // step only, last layer: form the MSE output error in the update's epilogue
 };
 
@@ -652,7 +666,7 @@ ph_status fwd_impl(const Geo &g, const FwdArgs &f, hipStream_t st)
     update.b = q > 0 ? view_rowseg(f.Lw, si, (int)si, so * si, f.Dw, (int)k, so * k, q * so * k) : view_plain(f.Lw, si, so * si);
     update.o = view_plain(f.Y, so, B * so);
     update.ep.mode = EPI_BIAS_ACT; update.ep.act = g.act; update.ep.bias = f.bias; update.ep.bias_g = so;
-    update.ep.aux = f.A_save; update.ep.aux_ld = so; update.ep.aux_g = B * so; update.ep.aux_f32 = f.a_f32; update.ep.aux_deriv = f.a_deriv;
+    update.ep.aux = f.A_save; update.ep.aux_ld = so; update.ep.aux_g = B * so; update.ep.aux_f32 = f.a_f32; update.ep.aux_deriv = f.a_deriv; update.ep.aux_bits = f.a_bits;
     update.M = B; update.N = so; update.K = g.Kc;
     float *clear_at = nullptr;
     int64_t clear_count = 0;
@@ -711,6 +725,7 @@ struct BwdArgs {
     const void *delta_ready;   // step only: delta already formed (dY, S unused)
     bool dx_S_f32;             // step only: dx_S holds float
     bool dx_S_deriv;           // step only: dx_S holds sigma' itself, in float
+    bool dx_S_bits;            // step only, ReLU: dx_S holds one bit per element (the layer below's stored output > 0)
     const void *dx_S;          // step only: multiply dX by sigma'(dx_S) on the way out, which makes it the
                                //   previous layer's delta with a single rounding (Eq. (backprop))
     float *dx_colsum;          // step only: zeroed [groups, s]; the input-gradient product adds the column sums
@@ -810,7 +825,7 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
     dx.ep = epi_store();
     if (b.dx_S && g.act != PH_ACT_IDENTITY) {
         dx.ep.mode = EPI_DACT; dx.ep.act = g.act; dx.ep.aux = const_cast<void *>(b.dx_S); dx.ep.aux_ld = si;
-        dx.ep.aux_g = B * si; dx.ep.aux_f32 = b.dx_S_f32; dx.ep.aux_deriv = b.dx_S_deriv;
+        dx.ep.aux_g = B * si; dx.ep.aux_f32 = b.dx_S_f32; dx.ep.aux_deriv = b.dx_S_deriv; dx.ep.aux_bits = b.dx_S_bits;
     } else if (b.dx_colsum) {
         dx.ep.mode = EPI_DACT; dx.ep.act = g.act; dx.ep.aux = nullptr;      // identity: column sums only
     }
@@ -1024,9 +1039,10 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
     std::vector<const void *> inputs(L);
     for (int l = 0; l < L; ++l) {
         inputs[l] = in;
+        const bool bits = train && w.relu_bits[(size_t)l] != nullptr;
         FwdArgs f{in, a.Lw[l], q ? a.Cw[l] : nullptr, q ? a.Dw[l] : nullptr, a.bias[l],
-                  (q && !g.all) ? a.G[l] : nullptr, w.Y[l], w.G[l], w.A[l], !save_deriv, save_deriv,
-                  (mse_in_update && l == L - 1) ? &oe : nullptr};
+                  (q && !g.all) ? a.G[l] : nullptr, w.Y[l], w.G[l], bits ? w.relu_bits[(size_t)l] : w.A[l],
+                  !save_deriv && !bits, save_deriv, bits, (mse_in_update && l == L - 1) ? &oe : nullptr};
         PH_TRY(fwd_impl<T>(geos[(size_t)l], f, st));
         in = w.Y[l];
         if (a.taps) {
@@ -1088,7 +1104,8 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
         b.dbias_ready = l < L - 1 ? on_mfma(l + 1) : mse_in_update;
         b.dx_colsum = (on_mfma(l) && l > 0) ? dbias_of(l - 1) : nullptr;
         b.delta_ready = dY; b.X = inputs[l];
-        b.dx_S = l > 0 ? (g.act == PH_ACT_GELU ? w.A[l - 1] : w.Y[l - 1]) : nullptr;
+        b.dx_S_bits = l > 0 && w.relu_bits[(size_t)l - 1] != nullptr;
+        b.dx_S = l > 0 ? (b.dx_S_bits ? w.relu_bits[(size_t)l - 1] : g.act == PH_ACT_GELU ? w.A[l - 1] : w.Y[l - 1]) : nullptr;
         b.dx_S_f32 = gelu && !save_deriv;
         b.dx_S_deriv = save_deriv;
         b.Lw = a.Lw[l]; b.Cw = q ? a.Cw[l] : nullptr; b.Dw = q ? a.Dw[l] : nullptr;
@@ -1252,7 +1269,8 @@ ph_status phantom_layer_fwd(const ph_problem *prob, const void *X, const void *L
     (void)workspace; (void)workspace_bytes;
     Geo g;
     PH_TRY(make_geo(prob, g));
-    FwdArgs f{X, Lw, Cw, Dw, bias, G, Y, g_own, A_save, false};
+    FwdArgs f{};
+    f.X = X; f.Lw = Lw; f.Cw = Cw; f.Dw = Dw; f.bias = bias; f.G = G; f.Y = Y; f.g_own = g_own; f.A_save = A_save;
     PH_TRY(check_fwd_args(g, f));
     hipStream_t st = (hipStream_t)hip_stream;
     return g.dtype == PH_F32 ? fwd_impl<float>(g, f, st) : fwd_impl<bf16_t>(g, f, st);
@@ -1265,7 +1283,9 @@ ph_status phantom_layer_bwd(const ph_problem *prob, const void *dY, const void *
 {
     Geo g;
     PH_TRY(make_geo(prob, g));
-    BwdArgs b{dY, X, A_or_Y, Lw, Cw, Dw, G, dg_own, dX, dLw, dCw, dDw, dbias, dG_send, nullptr, false, false, nullptr};
+    BwdArgs b{};
+    b.dY = dY; b.X = X; b.S = A_or_Y; b.Lw = Lw; b.Cw = Cw; b.Dw = Dw; b.G = G; b.dg_own = dg_own; b.dX = dX;
+    b.dLw = dLw; b.dCw = dCw; b.dDw = dDw; b.dbias = dbias; b.dG_send = dG_send;
     PH_TRY(check_bwd_args(g, b));
     Arena sizing{nullptr, 0};
     carve_bwd(sizing, g);
