@@ -416,7 +416,7 @@ def main():
         "roofline": roof,
         "empty_launch_us": round(event_overhead_us, 3),
         "measured_copy_gbs": round(copy_gbs, 1),
-        "kernels": [{k_: v for k_, v in r.items() if k_ not in ("flops", "bytes")} for r in table],
+        "kernels": [{{"flops": "flop", "bytes": "algorithmic_bytes"}.get(k_, k_): v for k_, v in r.items()} for r in table],
     }
 
     if not args.no_dense:
