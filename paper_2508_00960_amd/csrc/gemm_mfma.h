@@ -467,10 +467,56 @@ __device__ __forceinline__ void read_operands(bf16x8 (&f)[4], const __bf16 *ta, 
 
 constexpr int part_lo(int n, int q) { return n * q / 3; }       // the q-th third of n vectors
 
-// DRAIN = true: the last steps of a team's run, where a part of the work no longer exists; do_mfma (this
-// step's tile exists), do_store (the next tile exists) and do_fetch (the tile three steps on exists) are
-// the same for the whole team.  DRAIN = false ignores them: everything exists.
-template <int KA, int KB, int VA, int VB, int BP, bool DRAIN>
+// ---- the compression inside the update's reduction loop (one rank's forward) ----------------------------
+// g = X C^T shares its A operand with the update: the rows of X that a workgroup stages for its tile are the rows the
+// compression needs, over the first part [0, K) of the update's reduction range.  The 128 rows of a tile row and the
+// N <= 64 phantom neurons make 4 x ceil(N / 32) blocks of 32 x 32; the workgroup of tile column tn takes block tn:
+// it stages the block's 32 rows of C beside its B tile (4 KB per step, one more 16-byte vector per thread), and the
+// one wavefront whose A fragment covers the block's rows issues one more MFMA per quarter step with the fragment it
+// has read anyway.  No second pass over X, no partial sums between workgroups, and the work rides under a loop that
+// the memory side bounds.  Conditions (host): 8-element vectors, regular shapes (fast path only), a tile row has at
+// least as many workgroups as blocks, one tile per workgroup (the two-tile loop has no registers left for it).
+// Configuration 4's forward launch: 36.1 us, against 37.6 with the compression as a share of rows behind the epilogue
+// and 33.9 without any compression.
+struct FoldParams {
+    const __bf16 *C;     // [N, K] per group
+    __bf16 *G;           // [M, N] per group, M = the update's
+    int64_t c_g, o_g;    // element offsets per group
+    int N, K;
+    int ncb;             // blocks per row of blocks = ceil(N / 32)
+    int nblocks;         // 4 * ncb; 0: no folding
+};
+
+constexpr int E_SLOT_OFF = MT * KC_PITCH;      // a K-contiguous tile leaves the last 1024 elements of its slot unused:
+static_assert(TILE_ELEMS - E_SLOT_OFF >= 16 * KT, "room for 16 unpadded rows of the block's C tile behind a K-contiguous tile");
+
+struct FoldState {
+    bool on;             // the workgroup has a block (uniform)
+    bool owner;          // this wavefront multiplies it (uniform per wavefront)
+    bool own_hi;         // ... with the second of its two 32-row A fragments
+    int limit;           // reduction indices below it belong to X (uniform)
+    const __bf16 *base;  // row 0 of the block's C rows, reduction index 0 (uniform)
+    int src_off;         // this thread's 16-byte vector of those rows: element offset from base
+    int st_off;          // where that vector goes inside a stage's C tile (element offset)
+    int rd_off;          // owner: element offset of the lane's row inside a stage's C tile, and
+    int rd_swz;          //        the XOR of its 16-byte slot index
+    f32x16 acc;
+    bf16x8 fe;
+};
+
+// The C tile of a stage: two halves of 16 rows, HALF elements apart (the halves sit behind two different operand tiles
+// when two teams share an output tile); rows of 64 elements without padding; the 16-byte slots of row r sit at
+// slot ^ ((r >> 1) & 7), which spreads the 16 rows that the lanes of an operand read touch over all banks.
+__device__ __forceinline__ bf16x8 fold_read(const FoldState &fs, const __bf16 *tile, int kk, int lane)
+{
+    const int slot = (2 * kk + (lane >> 5)) ^ fs.rd_swz;
+    return *(const bf16x8 *)(tile + fs.rd_off + slot * 8);
+}
+
+// FOLD: the step also carries the compression's block: fs; re: the register that holds the next tile's vector of C
+// rows (stored, then refilled with the tile's at c_fetch); e_cur, e_nxt: the C tile in the current and in the next
+// stage; c_cur, c_next: where this step's and the next step's tiles start in the reduction range.
+template <int KA, int KB, int VA, int VB, int BP, bool DRAIN, bool FOLD = false>
 __device__ __forceinline__ void fast_step(f32x16 (&acc)[2][2], bf16x8 (&fr)[2][4], const __bf16 *ta, const __bf16 *tb,
                                           int wm, int wn, int lane,
                                           const StageState &sa, const int (&a_off0)[StageCfg<KA, VA>::NV],
@@ -479,9 +525,20 @@ __device__ __forceinline__ void fast_step(f32x16 (&acc)[2][2], bf16x8 (&fr)[2][4
                                           const StageState &sb, const int (&b_off0)[StageCfg<KB, VB, BP>::NV],
                                           const int (&b_off1)[StageCfg<KB, VB, BP>::NV],
                                           typename VecOf<VB>::type (&rb)[StageCfg<KB, VB, BP>::NV], __bf16 *nb, int c_fetch,
-                                          bool do_mfma = true, bool do_store = true, bool do_fetch = true)
+                                          bool do_mfma, bool do_store, bool do_fetch,
+                                          FoldState &fs, u32x4 &re, const __bf16 *e_cur, __bf16 *e_nxt, int c_cur, int c_next)
 {
     constexpr int NA = StageCfg<KA, VA>::NV, NB = StageCfg<KB, VB, BP>::NV;
+    // all uniform (per workgroup, or per wavefront for the owner's)
+    const bool e_mul = FOLD && fs.owner && (!DRAIN || do_mfma) && c_cur < fs.limit;
+    const bool e_next = FOLD && fs.on && (!DRAIN || do_store) && c_next < fs.limit;
+    const bool e_fetch = FOLD && fs.on && (!DRAIN || do_fetch) && c_fetch < fs.limit;
+    // the block's operand of a quarter is read at the quarter's start and used behind its four MFMAs (one register set)
+#define PH_E_READ(kk) do { if (FOLD && e_mul) fs.fe = fold_read(fs, e_cur, kk, lane); } while (0)
+    // (a branch, not a select between the two fragments: a select of array elements would move the array to memory)
+#define PH_E_MFMA(buf) do { if (FOLD && e_mul) { \
+        if (fs.own_hi) fs.acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fs.fe, fr[buf][1], fs.acc, 0, 0, 0); \
+        else fs.acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fs.fe, fr[buf][0], fs.acc, 0, 0, 0); } } while (0)
     // a tile that does not exist has no valid address: its step start is replaced by one that does
     const int c_safe = (DRAIN && !do_fetch) ? sa.c_lim - KT : c_fetch;
     const FastStep fa = fast_step_addr<KA, VA>(sa, c_safe), fb = fast_step_addr<KB, VB>(sb, c_safe);
@@ -492,30 +549,35 @@ __device__ __forceinline__ void fast_step(f32x16 (&acc)[2][2], bf16x8 (&fr)[2][4
 #define PH_FETCH_B(q) do { if (!DRAIN || do_fetch) fast_fetch<KB, VB, BP, part_lo(NB, q), part_lo(NB, q + 1)>(fb, b_off0, b_off1, rb); } while (0)
 #define PH_PIN __builtin_amdgcn_sched_barrier(0)   /* the compiler's scheduler would regroup the sequence */
     // quarter 0
-    PH_PIN; read_operands<KA, KB>(fr[1], ta, tb, wm, wn, 1, lane); PH_PIN;
+    PH_PIN; read_operands<KA, KB>(fr[1], ta, tb, wm, wn, 1, lane); PH_E_READ(0); PH_PIN;
     PH_MFMA(0, 0, 0); PH_STORE_A(0); PH_PIN;
     PH_MFMA(0, 0, 1); PH_STORE_B(0); PH_PIN;
     PH_MFMA(0, 1, 0);
-    PH_MFMA(0, 1, 1); PH_PIN;
+    if (FOLD && e_next) *(u32x4 *)(e_nxt + fs.st_off) = re;
+    PH_MFMA(0, 1, 1); PH_E_MFMA(0); PH_PIN;
     // quarter 1
-    read_operands<KA, KB>(fr[0], ta, tb, wm, wn, 2, lane); PH_PIN;
+    read_operands<KA, KB>(fr[0], ta, tb, wm, wn, 2, lane); PH_E_READ(1); PH_PIN;
     PH_MFMA(1, 0, 0); PH_STORE_A(1); PH_PIN;
     PH_MFMA(1, 0, 1); PH_STORE_B(1); PH_PIN;
     PH_MFMA(1, 1, 0); PH_FETCH_A(0); PH_PIN;
-    PH_MFMA(1, 1, 1); PH_FETCH_B(0); PH_PIN;
+    PH_MFMA(1, 1, 1); PH_FETCH_B(0); PH_E_MFMA(1); PH_PIN;
     // quarter 2
-    read_operands<KA, KB>(fr[1], ta, tb, wm, wn, 3, lane); PH_PIN;
+    read_operands<KA, KB>(fr[1], ta, tb, wm, wn, 3, lane); PH_E_READ(2); PH_PIN;
     PH_MFMA(0, 0, 0); PH_STORE_A(2); PH_PIN;
     PH_MFMA(0, 0, 1); PH_STORE_B(2); PH_PIN;
     PH_MFMA(0, 1, 0); PH_FETCH_A(1); PH_PIN;
-    PH_MFMA(0, 1, 1); PH_FETCH_B(1); PH_PIN;
+    PH_MFMA(0, 1, 1); PH_FETCH_B(1); PH_E_MFMA(0); PH_PIN;
+    PH_E_READ(3); PH_PIN;          // before the barrier, like every read of the current stage
     __syncthreads();
     // quarter 3
     PH_PIN; read_operands<KA, KB>(fr[0], na, nb, wm, wn, 0, lane); PH_PIN;
     PH_MFMA(1, 0, 0); PH_FETCH_A(2); PH_PIN;
     PH_MFMA(1, 0, 1); PH_FETCH_B(2); PH_PIN;
     PH_MFMA(1, 1, 0);
-    PH_MFMA(1, 1, 1); PH_PIN;
+    if (FOLD && e_fetch) re = load_global<u32x4>(fs.base + (fs.src_off + c_fetch));
+    PH_MFMA(1, 1, 1); PH_E_MFMA(1); PH_PIN;
+#undef PH_E_READ
+#undef PH_E_MFMA
 #undef PH_PIN
 #undef PH_MFMA
 #undef PH_STORE_A
@@ -612,10 +674,12 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
                 }
                 if (ep.aux) {
                     if (ep.aux_deriv) {
+                        // written once, read once by the backward pass much later: a streaming store keeps it from
+                        // pushing the operand panels that other workgroups still share out of L2
                         FlV a;
 #pragma unroll
                         for (int u = 0; u < VEC; ++u) a[u] = deriv[u];
-                        *(FlV *)((float *)ep.aux + aux_at) = a;
+                        __builtin_nontemporal_store(a, (FlV *)((float *)ep.aux + aux_at));
                     } else if (ep.aux_f32) {
                         FlV a;
 #pragma unroll
@@ -660,8 +724,8 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
 #pragma unroll
                     for (int u = 0; u < VEC; ++u) x[u] = (bits >> u) & 1u ? x[u] : 0.f;
                 }
-            } else if (ep.aux_deriv) {                 // sigma' itself, float
-                const FlV a = *(const FlV *)((const float *)ep.aux + aux_at);
+            } else if (ep.aux_deriv) {                 // sigma' itself, float; read once
+                const FlV a = __builtin_nontemporal_load((const FlV *)((const float *)ep.aux + aux_at));
 #pragma unroll
                 for (int u = 0; u < VEC; ++u) x[u] *= a[u];
             } else if (ep.aux_f32) {
@@ -833,9 +897,12 @@ __device__ __forceinline__ int xcd_order(int id, int first, int count)
 }
 
 // One workgroup's work: workgroup number wg (of P.total_wg, in tile order) of the product P.
-template <int KA, int KB, int VA, int VB, typename TOut, bool ATOMIC, bool DUAL, int EPI>
-__device__ __forceinline__ void mfma_workgroup(const MfmaParams &P, int wg)
+// FOLD (the forward layout with 8-element vectors, regular shapes only): the workgroup also computes its block of
+// the compression F (FoldParams).
+template <int KA, int KB, int VA, int VB, typename TOut, bool ATOMIC, bool DUAL, int EPI, bool FOLD = false>
+__device__ __forceinline__ void mfma_workgroup(const MfmaParams &P, int wg, const FoldParams *Fp = nullptr)
 {
+    static_assert(!FOLD || (KA == LD_KC && KB == LD_KC && VA == 8 && !ATOMIC), "the compression rides with the forward product only");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     static_assert(!(DUAL && ATOMIC), "a split reduction keeps the two-teams-per-tile form");
     static_assert(!ATOMIC || EPI == EPI_STORE, "partial sums are added as they are");
@@ -875,6 +942,30 @@ __device__ __forceinline__ void mfma_workgroup(const MfmaParams &P, int wg)
     PH_PHASE(7);
     typename SA::V ra0[SA::NV], ra1[SA::NV];
     typename SB::V rb0[SB::NV], rb1[SB::NV];
+    // the compression's block of this workgroup: block tn of its tile row (block = 32 rows x 32 phantom neurons)
+    FoldState fs;
+    u32x4 re0 = {0, 0, 0, 0}, re1 = {0, 0, 0, 0};
+    int e_rb = 0, e_cb = 0;
+    fs.on = false; fs.owner = false;
+    // the two halves (16 rows each) of a stage's C tile lie this many elements apart
+    constexpr int E_HALF = DUAL ? 16 * KT : TILE_ELEMS;
+    if constexpr (FOLD) {
+        const FoldParams &F = *Fp;
+        fs.on = tn < F.nblocks;
+        e_rb = tn / F.ncb; e_cb = tn - e_rb * F.ncb;
+        fs.owner = fs.on && __builtin_amdgcn_readfirstlane(wave) == (e_rb >> 1) * 2;   // the wavefront with wm = 64 (rb / 2), wn = 0
+        fs.own_hi = e_rb & 1;
+        fs.limit = F.K;
+        const int erow = tid >> 3, eslot = tid & 7;              // 256 threads of a team: 32 rows x 8 vectors
+        fs.base = F.C + g * F.c_g + (int64_t)(e_cb * 32) * F.K;
+        fs.src_off = min(erow, F.N - 1 - e_cb * 32) * F.K + eslot * 8;
+        fs.st_off = (erow >> 4) * E_HALF + (erow & 15) * KT + ((eslot ^ ((erow >> 1) & 7)) * 8);
+        const int rrow = lane & 31;
+        fs.rd_off = (rrow >> 4) * E_HALF + (rrow & 15) * KT;
+        fs.rd_swz = (rrow >> 1) & 7;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) fs.acc[e] = 0.f;
+    }
 #define PH_FETCH(set, c0) do { stage_fetch<KA, VA, true>(sa, a_off0, a_off1, ra##set, (c0)); \
                                stage_fetch<KB, VB, true, BP>(sb, b_off0, b_off1, rb##set, (c0)); } while (0)
 #define PH_STORE(set, stage, c0) do { stage_store<KA, VA, true>(sa, ra##set, s##stage##a, (c0)); \
@@ -898,6 +989,13 @@ __device__ __forceinline__ void mfma_workgroup(const MfmaParams &P, int wg)
         s0b = smem + 4 * TILE_ELEMS; s1b = s0b + TILE_ELEMS;
     } else {
         s0a = smem + team * 4 * TILE_ELEMS; s0b = s0a + TILE_ELEMS; s1a = s0a + 2 * TILE_ELEMS; s1b = s0a + 3 * TILE_ELEMS;
+    }
+    // the C tile of the compression's block, per stage.  Two teams on one tile: its halves behind the team's own A and
+    // B tiles; DUAL (B stages shared by the teams): in the space behind the six operand tiles.
+    __bf16 *e0 = nullptr, *e1 = nullptr;
+    if constexpr (FOLD) {
+        if (DUAL) { e0 = smem + 6 * TILE_ELEMS + team * 4 * 16 * KT; e1 = e0 + 2 * 16 * KT; }
+        else { e0 = s0a + E_SLOT_OFF; e1 = s1a + E_SLOT_OFF; }
     }
     // The reduction range is cut into tiles of KT.  Two teams on one tile: team q takes the tiles q, q+2, ...;
     // DUAL: every team takes every tile.  Both teams pass the same number of barriers (`steps`).
@@ -939,27 +1037,40 @@ __device__ __forceinline__ void mfma_workgroup(const MfmaParams &P, int wg)
         }
         if (my_steps > 2) PH_FETCH_FAST(0, c_of(2));
 #undef PH_FETCH_FAST
+        if constexpr (FOLD) {
+            // the C tile of the block for the first three tiles, as far as they lie in X's part of the reduction range
+            if (fs.on) {                                             // uniform
+                if (my_steps > 1 && c_of(1) < fs.limit) re1 = load_global<u32x4>(fs.base + (fs.src_off + c_of(1)));
+                if (my_steps > 0 && c_of(0) < fs.limit)
+                    *(u32x4 *)(e0 + fs.st_off) = load_global<u32x4>(fs.base + (fs.src_off + c_of(0)));
+                if (my_steps > 2 && c_of(2) < fs.limit) re0 = load_global<u32x4>(fs.base + (fs.src_off + c_of(2)));
+            }
+        }
         __syncthreads();
         PH_PHASE(2);
         // step i multiplies LDS stage i%2; on entry tile i+1 sits in register set (i+1)%2 and is moved to the other
         // stage (whose readers finished before the barrier inside step i-1), tile i+2 in the other set
         bf16x8 fr[2][4];
         read_operands<KA, KB>(fr[0], s0a, s0b, wm, wn, 0, lane);
+#define PH_ES(cur, nxt, i) e##cur, e##nxt, c_of(i), c_of((i) + 1)
         for (; t + 1 < steps && t + 4 < my_steps; t += 2) {          // everything these two steps touch exists
-            fast_step<KA, KB, VA, VB, BP, false>(acc, fr, s0a, s0b, wm, wn, lane, sa, a_off0, a_off1, ra1, s1a, sb, b_off0, b_off1,
-                                                 rb1, s1b, c_of(t + 3));
-            fast_step<KA, KB, VA, VB, BP, false>(acc, fr, s1a, s1b, wm, wn, lane, sa, a_off0, a_off1, ra0, s0a, sb, b_off0, b_off1,
-                                                 rb0, s0b, c_of(t + 4));
+            fast_step<KA, KB, VA, VB, BP, false, FOLD>(acc, fr, s0a, s0b, wm, wn, lane, sa, a_off0, a_off1, ra1, s1a, sb, b_off0, b_off1,
+                                                       rb1, s1b, c_of(t + 3), true, true, true, fs, re1, PH_ES(0, 1, t));
+            fast_step<KA, KB, VA, VB, BP, false, FOLD>(acc, fr, s1a, s1b, wm, wn, lane, sa, a_off0, a_off1, ra0, s0a, sb, b_off0, b_off1,
+                                                       rb0, s0b, c_of(t + 4), true, true, true, fs, re0, PH_ES(1, 0, t + 1));
         }
         for (; t + 1 < steps; t += 2) {                              // the last steps: the pipeline runs empty
-            fast_step<KA, KB, VA, VB, BP, true>(acc, fr, s0a, s0b, wm, wn, lane, sa, a_off0, a_off1, ra1, s1a, sb, b_off0, b_off1,
-                                                rb1, s1b, c_of(t + 3), t < my_steps, t + 1 < my_steps, t + 3 < my_steps);
-            fast_step<KA, KB, VA, VB, BP, true>(acc, fr, s1a, s1b, wm, wn, lane, sa, a_off0, a_off1, ra0, s0a, sb, b_off0, b_off1,
-                                                rb0, s0b, c_of(t + 4), t + 1 < my_steps, t + 2 < my_steps, t + 4 < my_steps);
+            fast_step<KA, KB, VA, VB, BP, true, FOLD>(acc, fr, s0a, s0b, wm, wn, lane, sa, a_off0, a_off1, ra1, s1a, sb, b_off0, b_off1,
+                                                      rb1, s1b, c_of(t + 3), t < my_steps, t + 1 < my_steps, t + 3 < my_steps, fs, re1,
+                                                      PH_ES(0, 1, t));
+            fast_step<KA, KB, VA, VB, BP, true, FOLD>(acc, fr, s1a, s1b, wm, wn, lane, sa, a_off0, a_off1, ra0, s0a, sb, b_off0, b_off1,
+                                                      rb0, s0b, c_of(t + 4), t + 1 < my_steps, t + 2 < my_steps, t + 4 < my_steps, fs, re0,
+                                                      PH_ES(1, 0, t + 1));
         }
         if (t < steps)
-            fast_step<KA, KB, VA, VB, BP, true>(acc, fr, s0a, s0b, wm, wn, lane, sa, a_off0, a_off1, ra1, s1a, sb, b_off0, b_off1,
-                                                rb1, s1b, 0, t < my_steps, false, false);
+            fast_step<KA, KB, VA, VB, BP, true, FOLD>(acc, fr, s0a, s0b, wm, wn, lane, sa, a_off0, a_off1, ra1, s1a, sb, b_off0, b_off1,
+                                                      rb1, s1b, 0, t < my_steps, false, false, fs, re1, PH_ES(0, 1, t));
+#undef PH_ES
     } else {
         // prologue: tile 0 into LDS stage 0; tiles 1 and 2 on their way in register sets 1 and 0.  A tile past the
         // end of the range (the shorter team's last step) is stored as zeros.
@@ -999,6 +1110,42 @@ __device__ __forceinline__ void mfma_workgroup(const MfmaParams &P, int wg)
     else if constexpr (DUAL) epilogue_from_lds<VA, TOut, true, EPI>(P, g, ctile + team * CT_ELEMS, m0, n0, tid, ctile + 2 * CT_ELEMS);
     else epilogue_from_lds<VA, TOut, false, EPI>(P, g, ctile, m0, n0, (int)threadIdx.x, ctile + 2 * CT_ELEMS);
     PH_PHASE(5);
+    if constexpr (FOLD) {
+        if (fs.on) {                                                 // uniform
+            // the block of g: two teams on one tile hold partial sums of it (alternate reduction steps): team 1's goes
+            // through LDS to team 0's owner.  A lane holds row (lane & 31) of the block and the columns
+            // 8 * (e / 4) + 4 * (lane >> 5) + e % 4 (B operand first, as in acc_to_lds).
+            const FoldParams &F = *Fp;
+            float *ex = (float *)smem_raw;
+            if (!DUAL) {
+                __syncthreads();                                     // the tile's epilogue is done with LDS
+                if (fs.owner && team == 1) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) ex[e * 64 + lane] = fs.acc[e];
+                }
+                __syncthreads();
+                if (fs.owner && team == 0) {
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) fs.acc[e] += ex[e * 64 + lane];
+                }
+            }
+            if (fs.owner && (DUAL || team == 0)) {
+                const int m = m0 + 32 * e_rb + (lane & 31);
+                if (m < P.M) {
+                    __bf16 *row = F.G + g * F.o_g + (int64_t)m * F.N;
+                    typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int c = 32 * e_cb + 8 * q + 4 * (lane >> 5);
+                        if (c < F.N) {                               // N is a multiple of 8: four columns at a time stay inside
+                            bf16x4 v = {(__bf16)fs.acc[4 * q], (__bf16)fs.acc[4 * q + 1], (__bf16)fs.acc[4 * q + 2], (__bf16)fs.acc[4 * q + 3]};
+                            *(bf16x4 *)(row + c) = v;
+                        }
+                    }
+                }
+            }
+        }
+    }
 }
 
 template <int KA, int KB, int VA, int VB, typename TOut, bool ATOMIC, bool PAIR, bool DUAL, int EPI>
@@ -1083,21 +1230,27 @@ struct MfmaFwdBatch {
     int64_t x_g, c_g, o_g;
     int wg_per_group;        // workgroups of the update per group
     int thin_rows;           // rows of the compression per workgroup: wg_per_group * thin_rows >= M
+    FoldParams fold;         // FOLD kernels: the compression inside the update's loop instead (the fields above unused)
 };
 
-template <int VEC, bool DUAL>
+template <int VEC, bool DUAL, bool FOLD>
 __global__ __launch_bounds__(512, 1) void gemm_mfma_fwd_kernel(MfmaFwdBatch fb)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     const int wg = xcd_order((int)blockIdx.x, 0, fb.update.total_wg);
-    mfma_workgroup<LD_KC, LD_KC, VEC, VEC, __bf16, false, DUAL, EPI_BIAS_ACT>(fb.update, wg);
-    const int grp = wg / fb.wg_per_group;
-    const int first = (wg - grp * fb.wg_per_group) * fb.thin_rows;
-    const int last = min(first + fb.thin_rows, fb.M);
-    for (int m0 = first; m0 < last; m0 += THIN_ROWS) {           // uniform
-        __syncthreads();                                         // the epilogue, or the block before, is done with LDS
-        if (fb.N <= 32) thin_workgroup<1, 8>(fb.X, fb.C, fb.G, last, fb.N, fb.K, fb.x_g, fb.c_g, fb.o_g, m0, grp, (float *)smem_raw);
-        else thin_workgroup<2, 8>(fb.X, fb.C, fb.G, last, fb.N, fb.K, fb.x_g, fb.c_g, fb.o_g, m0, grp, (float *)smem_raw);
+    if constexpr (FOLD) {
+        // the compression rides inside the update's reduction loop (FoldParams)
+        mfma_workgroup<LD_KC, LD_KC, VEC, VEC, __bf16, false, DUAL, EPI_BIAS_ACT, true>(fb.update, wg, &fb.fold);
+    } else {
+        mfma_workgroup<LD_KC, LD_KC, VEC, VEC, __bf16, false, DUAL, EPI_BIAS_ACT>(fb.update, wg);
+        const int grp = wg / fb.wg_per_group;
+        const int first = (wg - grp * fb.wg_per_group) * fb.thin_rows;
+        const int last = min(first + fb.thin_rows, fb.M);
+        for (int m0 = first; m0 < last; m0 += THIN_ROWS) {           // uniform
+            __syncthreads();                                         // the epilogue, or the block before, is done with LDS
+            if (fb.N <= 32) thin_workgroup<1, 8>(fb.X, fb.C, fb.G, last, fb.N, fb.K, fb.x_g, fb.c_g, fb.o_g, m0, grp, (float *)smem_raw);
+            else thin_workgroup<2, 8>(fb.X, fb.C, fb.G, last, fb.N, fb.K, fb.x_g, fb.c_g, fb.o_g, m0, grp, (float *)smem_raw);
+        }
     }
 }
 

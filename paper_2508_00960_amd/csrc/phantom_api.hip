@@ -514,10 +514,10 @@ ph_status launch_tail(const Product *head, const Product &tail0, const Product &
 }
 
 // One rank's thin compression and layer update in one launch: see MfmaFwdBatch.
-template <int VEC, bool DUAL>
+template <int VEC, bool DUAL, bool FOLD = false>
 ph_status launch_fwd_kernel(const MfmaFwdBatch &fb, unsigned total_wg, hipStream_t st, const char *what)
 {
-    auto kern = gemm_mfma_fwd_kernel<VEC, DUAL>;
+    auto kern = gemm_mfma_fwd_kernel<VEC, DUAL, FOLD>;
     static thread_local bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, MFMA_LDS_BYTES);
@@ -543,6 +543,18 @@ ph_status launch_fwd_pair(const Product &update, const Product &compress, int gr
     fb.thin_rows = (int)(((compress.M + fb.wg_per_group - 1) / fb.wg_per_group + 15) / 16 * 16);
     const unsigned total = (unsigned)fb.update.total_wg;
     ProfScope prof(what, update.M, update.N, update.K, groups, st, compress.M, compress.N, compress.K);
+    // The compression inside the update's reduction loop (FoldParams): 16-byte vectors, shapes that take the loop's
+    // fast path (widths multiples of 64; the phantom width a divisor of 64), and a tile row with at least as many
+    // workgroups as the compression has 32 x 32 blocks per 128 rows.
+    const int64_t si = compress.K, k = compress.N;
+    const int ncb = (int)((k + 31) / 32);
+    // One tile per workgroup only: with two tiles per workgroup (more than 256 tiles) the loop has no registers to
+    // spare, and the share behind the epilogue measured as fast or faster (configuration 5, k = 16: 0.195 against 0.221 ms).
+    if (!dual && vec == 8 && si % KT == 0 && KT % k == 0 && 4 * ncb <= fb.update.tiles_n && update.a.c.decides && update.a.c.split == si) {
+        fb.fold.C = fb.C; fb.fold.G = fb.G; fb.fold.c_g = fb.c_g; fb.fold.o_g = fb.o_g;
+        fb.fold.N = (int)k; fb.fold.K = (int)si; fb.fold.ncb = ncb; fb.fold.nblocks = 4 * ncb;
+        return launch_fwd_kernel<8, false, true>(fb, total, st, what);
+    }
     switch (vec) {
     case 8: return dual ? launch_fwd_kernel<8, true>(fb, total, st, what) : launch_fwd_kernel<8, false>(fb, total, st, what);
     case 4: return dual ? launch_fwd_kernel<4, true>(fb, total, st, what) : launch_fwd_kernel<4, false>(fb, total, st, what);
