@@ -202,15 +202,19 @@ def kernel_table(entries, steps, esize):
         if e["K"] > 0:
             out_e = 4 if "gradients" in e["name"] or e["name"] == "compressor gradient" else esize
             flops, byts = 0.0, 0.0
-            # the third product of a launch is the error compression riding with the weight gradients: storage type out
+            # the third and fourth product of a launch are the input gradient and / or the error compression riding with
+            # the weight gradients: storage type out
             for M, N, K, oe in ((e["M"], e["N"], e["K"], out_e), (e.get("M2", 0), e.get("N2", 0), e.get("K2", 0), out_e),
-                                (e.get("M3", 0), e.get("N3", 0), e.get("K3", 0), esize)):
+                                (e.get("M3", 0), e.get("N3", 0), e.get("K3", 0), esize),
+                                (e.get("M4", 0), e.get("N4", 0), e.get("K4", 0), esize)):
                 flops += 2.0 * M * N * K * e["groups"]
                 byts += (esize * (M + N) * K + oe * M * N) * e["groups"]
             if e.get("K2", 0):
                 row.update(M2=e["M2"], N2=e["N2"], K2=e["K2"])
             if e.get("K3", 0):
                 row.update(M3=e["M3"], N3=e["N3"], K3=e["K3"])
+            if e.get("K4", 0):
+                row.update(M4=e["M4"], N4=e["N4"], K4=e["K4"])
             row.update(tflops=round(flops / avg_us * 1e-6, 2), gbs=round(byts / avg_us * 1e-3, 1),
                        flops=flops, bytes=byts)
         out.append(row)

@@ -247,8 +247,9 @@ typedef struct {
     int32_t groups;
     int32_t calls;
     double total_ms;
-    int64_t M2, N2, K2;   /* a launch that carries two or three products side by side: the second one's shape */
-    int64_t M3, N3, K3;   /*   and the third one's, else 0 */
+    int64_t M2, N2, K2;   /* a launch that carries several products: the second one's shape, */
+    int64_t M3, N3, K3;   /*   the third one's */
+    int64_t M4, N4, K4;   /*   and the fourth one's, else 0 */
 } ph_profile_entry;
 
 ph_status phantom_profile_begin(int32_t max_launches);

@@ -68,6 +68,7 @@ class PhProfileEntry(ctypes.Structure):
         ("groups", ctypes.c_int32), ("calls", ctypes.c_int32), ("total_ms", ctypes.c_double),
         ("M2", ctypes.c_int64), ("N2", ctypes.c_int64), ("K2", ctypes.c_int64),
         ("M3", ctypes.c_int64), ("N3", ctypes.c_int64), ("K3", ctypes.c_int64),
+        ("M4", ctypes.c_int64), ("N4", ctypes.c_int64), ("K4", ctypes.c_int64),
     ]
 
 
@@ -121,7 +122,7 @@ def profile_end(capacity: int = 256):
     count = ctypes.c_int32(0)
     _check(load().phantom_profile_end(entries, capacity, ctypes.byref(count)))
     return [dict(name=e.name.decode(), M=e.M, N=e.N, K=e.K, groups=e.groups, calls=e.calls, total_ms=e.total_ms,
-                 M2=e.M2, N2=e.N2, K2=e.K2, M3=e.M3, N3=e.N3, K3=e.K3)
+                 M2=e.M2, N2=e.N2, K2=e.K2, M3=e.M3, N3=e.N3, K3=e.K3, M4=e.M4, N4=e.N4, K4=e.K4)
             for e in entries[:count.value]]
 
 

@@ -33,6 +33,7 @@
 //
 // Kernels in this file, all built on mfma_workgroup (one workgroup's work on one product):
 //   gemm_mfma_kernel       one product, or two of the same operand layout and output type
+//   gemm_mfma_bwd_kernel   one rank: input gradient + error compression, then pieces of the layer above's weight gradients
 //   gemm_mfma_tail_kernel  weight + compressor gradients with riders of other layouts (the error compression of
 //                          the layer below, the SGD update of the layer above)
 //   gemm_mfma_fwd_kernel   a rank's layer update with the thin compression shared out over its workgroups
@@ -326,15 +327,29 @@ struct SumOnRead {
     int p, k;
 };
 
+// SGD inside the epilogue that finishes a cut weight gradient (epilogue_pieces_from_lds): the parameters that the
+// gradient belongs to, laid out like the output View's two regions.  master0 == nullptr: none.
+struct SgdInPlace {
+    float *master0, *master1;    // fp32 master copies: master -= lr * gradient
+    __bf16 *w0, *w1;             // bf16 compute copies: w = bf16(master)
+    float lr;
+    int keep_grad;               // also store the gradient (the caller wants to see it)
+};
+
 struct MfmaParams {
     View a, b, o;        // o: the row index must not decide the region (true for every output here)
     Epilogue ep;
     SumOnRead rs;
     int M, N, K;
     int tiles_m, tiles_n;
-    int ksplit;          // > 1: the reduction range is cut into ksplit pieces, results added atomically
+    int ksplit;          // > 1: the reduction range is cut into ksplit pieces; their results are added atomically
+                         //   (ATOMIC kernels) or by the piece that finishes last (parts)
     int k_per_split;     // multiple of KT
     int total_wg;
+    float *parts;        // ksplit > 1 without atomics (float output, 8-element vectors, one group): room for ksplit
+    unsigned *arrived;   //   tiles of 128 x 128 floats per output tile, and one word per output tile, zero on entry
+                         //   and left zero (see epilogue_pieces_from_lds)
+    SgdInPlace sgd;      //   ... and what the piece that finishes a tile does with the gradient besides storing it
 };
 
 // The vectors of a K-contiguous A tile (reduction start c0) that lie in the summed block: replaces what the loader
@@ -667,7 +682,8 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
             else aux_v[i].h = *(const BfV *)((const __bf16 *)ep.aux + aux_at);
         }
     }
-#pragma unroll(EPI == EPI_DACT ? PASSES : 2)
+    constexpr int EPI_UNROLL = EPI == EPI_DACT ? PASSES : 2;     // EPI_DACT: unrolled, the prefetched vectors stay in registers
+#pragma unroll EPI_UNROLL
     for (int i = 0; i < PASSES; ++i) {
         const int v = thread + i * THREADS;
         const int row = v / PER_ROW, col = (v % PER_ROW) * VEC;
@@ -872,9 +888,130 @@ __device__ __forceinline__ void epilogue_atomic_from_lds(const MfmaParams &P, in
     }
 }
 
+// The epilogue of one piece of a reduction that is cut into ksplit pieces without atomics (float output, plain store
+// semantics, 8 columns per thread, all 512 threads).  Every piece writes its 128 x 128 result to its own slot of
+// P.parts and then counts itself in P.arrived[tile]; the piece that finds all others counted adds the slots up in the
+// order of the pieces (its own from registers), writes the output and leaves the word zero for the next launch.  The
+// sum does not depend on which piece comes last, and no workgroup ever waits for another.
+// The pieces may run on different XCDs, whose L2 caches do not see each other's lines.  What goes from one to the
+// other therefore uses device-scope atomic stores and loads (8 bytes each; the cache policy writes them through to
+// memory and reads them from there), as the counter does, so no cache has to be written back or invalidated as a whole:
+// with such fences, one per wavefront, the launch took 130 us against 44 us for the uncut product.  Within a slot,
+// thread t holds the 8-byte words t, t + 512, ...: every store and load instruction covers 4 KB without gaps.
+__device__ __forceinline__ void epilogue_pieces_from_lds(const MfmaParams &P, int tile, int ks, const float *ctile, unsigned *lds_word,
+                                                         int m0, int n0, int thread)
+{
+    typedef unsigned long long u64;
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    constexpr int VEC = 8, PER_ROW = MT / VEC, PASSES = MT * PER_ROW / MFMA_THREADS, WORDS = VEC / 2;
+    constexpr int ROWS_PER_PASS = MFMA_THREADS / PER_ROW;
+    constexpr int64_t SLOT = MT * MT / 2;              // 8-byte words per slot
+    constexpr int GROUP = 2;                           // other pieces whose loads are in flight together
+    union Two { u64 w; float f[2]; __device__ Two() {} };
+    // passes whose rows all lie below the output's last row (the compressor gradient has k <= 64 rows) move nothing
+    const int passes = min(PASSES, (P.M - m0 + ROWS_PER_PASS - 1) / ROWS_PER_PASS);      // uniform
+    float x[PASSES][VEC];
+#pragma unroll
+    for (int i = 0; i < PASSES; ++i) {
+        const int v = thread + i * MFMA_THREADS;
+        const int row = v / PER_ROW, col = (v % PER_ROW) * VEC;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const f32x4 c0 = *(const f32x4 *)(ctile + row * CT_PITCH + col + 4 * h);
+            const f32x4 c1 = *(const f32x4 *)(ctile + CT_ELEMS + row * CT_PITCH + col + 4 * h);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) x[i][4 * h + u] = c0[u] + c1[u];
+        }
+    }
+    u64 *slots = (u64 *)P.parts + (int64_t)tile * P.ksplit * SLOT;
+    u64 *mine = slots + ks * SLOT + thread;
+#pragma unroll
+    for (int i = 0; i < PASSES; ++i) {
+        if (i >= passes) break;
+#pragma unroll
+        for (int c = 0; c < WORDS; ++c) {
+            Two t;
+            t.f[0] = x[i][2 * c]; t.f[1] = x[i][2 * c + 1];
+            __hip_atomic_store(mine + (i * WORDS + c) * MFMA_THREADS, t.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // written through before this piece counts itself
+    __syncthreads();
+    if (thread == 0) *lds_word = __hip_atomic_fetch_add(P.arrived + tile, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (*lds_word + 1 != (unsigned)P.ksplit) return;   // uniform: another piece will finish the tile
+    float t[PASSES][VEC];
+#pragma unroll
+    for (int i = 0; i < PASSES; ++i)
+#pragma unroll
+        for (int u = 0; u < VEC; ++u) t[i][u] = 0.f;
+    for (int j0 = 0; j0 < P.ksplit; j0 += GROUP) {     // uniform
+        Two got[GROUP][PASSES][WORDS];
+#pragma unroll
+        for (int jj = 0; jj < GROUP; ++jj) {
+            const int j = j0 + jj;
+            if (j >= P.ksplit || j == ks) continue;
+            const u64 *theirs = slots + j * SLOT + thread;
+#pragma unroll
+            for (int i = 0; i < PASSES; ++i) {
+                if (i >= passes) break;
+#pragma unroll
+                for (int c = 0; c < WORDS; ++c)
+                    got[jj][i][c].w = __hip_atomic_load(theirs + (i * WORDS + c) * MFMA_THREADS, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+#pragma unroll
+        for (int jj = 0; jj < GROUP; ++jj) {
+            const int j = j0 + jj;
+            if (j >= P.ksplit) break;
+#pragma unroll
+            for (int i = 0; i < PASSES; ++i) {
+                if (i >= passes) break;
+#pragma unroll
+                for (int c = 0; c < WORDS; ++c) {
+                    t[i][2 * c] += j == ks ? x[i][2 * c] : got[jj][i][c].f[0];
+                    t[i][2 * c + 1] += j == ks ? x[i][2 * c + 1] : got[jj][i][c].f[1];
+                }
+            }
+        }
+    }
+    float *o0 = (float *)P.o.p0, *o1 = (float *)P.o.p1;
+#pragma unroll
+    for (int i = 0; i < PASSES; ++i) {
+        const int v = thread + i * MFMA_THREADS;
+        const int m = m0 + v / PER_ROW, n = n0 + (v % PER_ROW) * VEC;
+        if (m >= P.M || n >= P.N) continue;
+        const Loc ln = locate(P.o.c, n, P.o.skip0);
+        const int region = ln.region > 0 ? 1 : 0;
+        const int64_t at = (region ? ln.off1 : ln.off0) + (int64_t)m * (region ? P.o.r.mult1 : P.o.r.mult0);
+        float *dst = (region ? o1 : o0) + at;
+        if (P.sgd.master0) {                           // uniform: Section VI's plain SGD on the finished gradient
+            float *master = (region ? P.sgd.master1 : P.sgd.master0) + at;
+            __bf16 *w = (region ? P.sgd.w1 : P.sgd.w0) + at;
+            const f32x4 m_lo = *(const f32x4 *)master, m_hi = *(const f32x4 *)(master + 4);
+            float nm[VEC];
+            bf16x8 nw;
+#pragma unroll
+            for (int u = 0; u < VEC; ++u) {
+                nm[u] = (u < 4 ? m_lo[u] : m_hi[u - 4]) - P.sgd.lr * t[i][u];
+                nw[u] = (__bf16)nm[u];
+            }
+            *(f32x4 *)master = f32x4{nm[0], nm[1], nm[2], nm[3]};
+            *(f32x4 *)(master + 4) = f32x4{nm[4], nm[5], nm[6], nm[7]};
+            *(bf16x8 *)w = nw;
+            if (!P.sgd.keep_grad) continue;
+        }
+        *(f32x4 *)dst = f32x4{t[i][0], t[i][1], t[i][2], t[i][3]};
+        *(f32x4 *)(dst + 4) = f32x4{t[i][4], t[i][5], t[i][6], t[i][7]};
+    }
+    if (thread == 0) __hip_atomic_store(P.arrived + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 #ifdef PHANTOM_TIMELINE   // cycle stamps for the development micro-benchmark, never built into the library
-#define PH_PHASE(slot) do { __builtin_amdgcn_sched_barrier(0); if ((blockIdx.x == 0 || blockIdx.x == gridDim.x - 1) && threadIdx.x == 0) \
-        ((long long *)P.rs.out)[(blockIdx.x ? 16 : 0) + (slot)] = clock64(); __builtin_amdgcn_sched_barrier(0); } while (0)
+// per workgroup 16 words at P.rs.out: slots 0..7 the core clock, 8..15 the 100 MHz wall clock at the same points
+#define PH_PHASE(slot) do { __builtin_amdgcn_sched_barrier(0); if (threadIdx.x == 0 && P.rs.out) { \
+        ((long long *)P.rs.out)[blockIdx.x * 16 + (slot)] = clock64(); ((long long *)P.rs.out)[blockIdx.x * 16 + 8 + (slot)] = wall_clock64(); } \
+        __builtin_amdgcn_sched_barrier(0); } while (0)
 #else
 #define PH_PHASE(slot) do { } while (0)
 #endif
@@ -891,17 +1028,28 @@ struct MfmaBatch {
     MfmaParams p[2];
     int count;
     int total_wg;
+    int first_wg;        // = p[0].total_wg
 };
 
-__device__ __forceinline__ MfmaParams pick_params(bool second, const MfmaParams &a, const MfmaParams &b)
+
+// The parameter block of one product, read from the kernel-argument segment at a byte offset that the compiler
+// cannot see through.  With several blocks as ordinary arguments (or a word-by-word selection between two of
+// them) it moves the loads of all of them to the top of the kernel and, out of scalar registers, spills each one
+// before loading the next: a chain of load-wait-spill rounds in front of the first product (four blocks: some
+// fifty rounds, 3 us; two blocks: 1.7 us).  This way a block is read where the product starts, with loads that
+// do not wait for each other.  The batch structure is the kernel's only argument, so it starts at offset 0.
+__device__ __forceinline__ MfmaParams params_at(size_t offset)
 {
-    static_assert(sizeof(MfmaParams) % 4 == 0, "parameter block is a whole number of words");
     constexpr int WORDS = sizeof(MfmaParams) / 4;
     union Words { MfmaParams p; uint32_t w[WORDS]; __device__ Words() {} };
     Words out;
-    const uint32_t *wa = (const uint32_t *)&a, *wb = (const uint32_t *)&b;
+#if defined(__HIP_DEVICE_COMPILE__)
+    asm volatile("" : "+s"(offset) :: "memory");
+    typedef const uint32_t __attribute__((address_space(4))) *ArgWords;
+    const ArgWords in = (ArgWords)((const char __attribute__((address_space(4))) *)__builtin_amdgcn_kernarg_segment_ptr() + offset);
 #pragma unroll
-    for (int i = 0; i < WORDS; ++i) out.w[i] = second ? wb[i] : wa[i];
+    for (int i = 0; i < WORDS; ++i) out.w[i] = in[i];
+#endif
     return out.p;
 }
 
@@ -1125,12 +1273,17 @@ __device__ __forceinline__ void mfma_workgroup(const MfmaParams &P, int wg, cons
     // each team writes its fp32 tile over the staging space (free after the barrier above).  Two teams
     // on one tile hold partial sums of it: the epilogue adds the two while reading.
     float *ctile = (float *)smem_raw;
+    constexpr bool PIECES = !ATOMIC && !DUAL && !FOLD && EPI == EPI_STORE && sizeof(TOut) == 4 && VA == 8;
     acc_to_lds(ctile + team * CT_ELEMS, acc, wm, wn, lane);
     __syncthreads();
     PH_PHASE(4);
     if constexpr (ATOMIC) epilogue_atomic_from_lds(P, g, ctile, m0, n0, (int)threadIdx.x);
     else if constexpr (DUAL) epilogue_from_lds<VA, TOut, true, EPI>(P, g, ctile + team * CT_ELEMS, m0, n0, tid, ctile + 2 * CT_ELEMS);
-    else epilogue_from_lds<VA, TOut, false, EPI>(P, g, ctile, m0, n0, (int)threadIdx.x, ctile + 2 * CT_ELEMS);
+    else if constexpr (PIECES) {
+        if (P.parts && P.ksplit > 1)                                 // uniform (one group: the host sees to that)
+            epilogue_pieces_from_lds(P, rem, ks, ctile, (unsigned *)(ctile + 2 * CT_ELEMS), m0, n0, (int)threadIdx.x);
+        else epilogue_from_lds<VA, TOut, false, EPI>(P, g, ctile, m0, n0, (int)threadIdx.x, ctile + 2 * CT_ELEMS);
+    } else epilogue_from_lds<VA, TOut, false, EPI>(P, g, ctile, m0, n0, (int)threadIdx.x, ctile + 2 * CT_ELEMS);
     PH_PHASE(5);
     if constexpr (FOLD) {
         if (fs.on) {                                                 // uniform
@@ -1174,12 +1327,9 @@ template <int KA, int KB, int VA, int VB, typename TOut, bool ATOMIC, bool PAIR,
 __global__ __launch_bounds__(512, 1) void gemm_mfma_kernel(MfmaBatch batch)
 {
     int wg = xcd_order(blockIdx.x, 0, batch.total_wg);
-    // Indexing the two parameter blocks with a run-time value turns every later read of a parameter
-    // into a small dependent load (measured: 1.8 us per launch); a single product reads its block
-    // directly, a pair selects word by word between two blocks that are both read with fixed offsets
-    const bool second = PAIR && wg >= batch.p[0].total_wg;
-    if (second) wg -= batch.p[0].total_wg;
-    const MfmaParams P = PAIR ? pick_params(second, batch.p[0], batch.p[1]) : batch.p[0];
+    const bool second = PAIR && wg >= batch.first_wg;
+    if (second) wg -= batch.first_wg;
+    const MfmaParams P = params_at(second ? offsetof(MfmaBatch, p[1]) : offsetof(MfmaBatch, p[0]));
     mfma_workgroup<KA, KB, VA, VB, TOut, ATOMIC, DUAL, EPI>(P, wg);
 }
 
@@ -1202,6 +1352,7 @@ struct MfmaTailBatch {
     int head_wg;         // = head.total_wg (0: no head)
     int tail_first;
     int tail_wg;         // = tail[0].total_wg + tail[1].total_wg
+    int tail0_wg;        // = tail[0].total_wg
     int sgd_first;
     int sgd_wg;          // 0: no update
     int rotate;          // workgroup b does the work of number (b + rotate) mod the grid size: rotate = tail_first
@@ -1217,19 +1368,81 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_tail_kernel(MfmaTailBatch tb
     if (id >= (int)gridDim.x) id -= (int)gridDim.x;
     if (id < tb.tail_first) {                          // uniform, like every branch here
         if (id >= tb.head_wg) return;
-        if (tb.dual) mfma_workgroup<LD_KC, LD_KM, VEC, VEC, __bf16, false, true, EPI_STORE>(tb.head, xcd_order(id, 0, tb.head_wg));
-        else mfma_workgroup<LD_KC, LD_KM, VEC, VEC, __bf16, false, false, EPI_STORE>(tb.head, xcd_order(id, 0, tb.head_wg));
+        const MfmaParams P = params_at(offsetof(MfmaTailBatch, head));
+        if (tb.dual) mfma_workgroup<LD_KC, LD_KM, VEC, VEC, __bf16, false, true, EPI_STORE>(P, xcd_order(id, 0, tb.head_wg));
+        else mfma_workgroup<LD_KC, LD_KM, VEC, VEC, __bf16, false, false, EPI_STORE>(P, xcd_order(id, 0, tb.head_wg));
     } else if (id < tb.sgd_first) {
         if (id >= tb.tail_first + tb.tail_wg) return;
-        int wg = xcd_order(id, tb.tail_first, tb.tail_wg);
-        const bool second = wg >= tb.tail[0].total_wg;
-        if (second) wg -= tb.tail[0].total_wg;
-        const MfmaParams P = pick_params(second, tb.tail[0], tb.tail[1]);
+        // The XCD-aware order within each product, and within each slab of pieces of a product whose reduction is cut
+        // (all first pieces, then all second ones, ...: a piece waits for the one before it, which must not sit
+        // behind it in the dispatch order)
+        int wg = id - tb.tail_first;
+        const bool second = wg >= tb.tail0_wg;
+        if (second) wg -= tb.tail0_wg;
+        wg = xcd_order(wg, 0, second ? tb.tail_wg - tb.tail0_wg : tb.tail0_wg);
+        const MfmaParams P = params_at(second ? offsetof(MfmaTailBatch, tail[1]) : offsetof(MfmaTailBatch, tail[0]));
         if (tb.dual) mfma_workgroup<LD_KM, LD_KM, VEC, VEC, float, false, true, EPI_STORE>(P, wg);
         else mfma_workgroup<LD_KM, LD_KM, VEC, VEC, float, false, false, EPI_STORE>(P, wg);
     } else {
         extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
         sgd_rider<__bf16>(tb.sgd, tb.lr, id - tb.sgd_first, tb.sgd_wg, MFMA_THREADS, (float *)smem_raw);
+    }
+}
+
+// One rank's backward launch: up to three pieces of work per workgroup, one after the other.
+//  1. a tile (DUAL: two tiles) of the input gradient of layer l (dx, sigma' epilogue) or of its error compression
+//     (send): workgroups [0, first_wg), dx's before send's; either may be empty;
+//  2. a piece of the weight gradients of layer l + 1 (dw), whose launch of its own would leave half of the compute
+//     units idle (configuration 4: 128 tiles): cut along the batch into dw.ksplit pieces (MfmaParams::parts), so
+//     that every compute unit that has finished a tile of 1. goes on with a piece of about equal length;
+//  3. a piece of that layer's compressor gradient (dc), on the workgroups that had the error compression in 1.,
+//     which finish earlier than those of the input gradient (no sigma' to read), or on the first ones (dc_by_id).
+// Nothing in 2. and 3. depends on 1.: the deltas of both layers are there before the launch.  Behind the
+// main_wg workgroups of the products, sgd_wg more run the SGD update of layer l + 2 (or only finish the loss).
+struct MfmaBwdBatch {
+    MfmaParams dx, send, dw, dc;
+    SgdBatch sgd;
+    float lr;
+    int dx_wg, send_wg, dw_wg, dc_wg;      // = their total_wg (the kernel reads the blocks only where it needs them)
+    int first_wg;        // = dx_wg + send_wg
+    int dual;            // dx and send in two-tile workgroups
+    int dc_by_id;        // dc's pieces on the first workgroups instead (no error compression, or too few workgroups of it)
+    int main_wg;         // multiple of 8, >= first_wg, dw.total_wg, and dc.total_wg if dc_by_id
+    int sgd_wg;          // 0 with work in sgd: workgroup 0 does it behind its products (a bias, the loss: little)
+};
+
+template <int VEC>
+__global__ __launch_bounds__(512, 1) void gemm_mfma_bwd_kernel(MfmaBwdBatch bb)
+{
+    const int id = (int)blockIdx.x;
+    if (id >= bb.main_wg) {
+        extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+        sgd_rider<__bf16>(bb.sgd, bb.lr, id - bb.main_wg, bb.sgd_wg, MFMA_THREADS, (float *)smem_raw);
+        return;
+    }
+    int on_send = -1;                                  // this workgroup's number among those of the error compression
+    if (id < bb.first_wg) {                            // uniform, like every branch here
+        int wg = xcd_order(id, 0, bb.first_wg);
+        const bool second = wg >= bb.dx_wg;
+        if (second) { wg -= bb.dx_wg; on_send = wg; }
+        const MfmaParams P = params_at(second ? offsetof(MfmaBwdBatch, send) : offsetof(MfmaBwdBatch, dx));
+        if (bb.dual) mfma_workgroup<LD_KC, LD_KM, VEC, VEC, __bf16, false, true, EPI_DACT>(P, wg);
+        else mfma_workgroup<LD_KC, LD_KM, VEC, VEC, __bf16, false, false, EPI_DACT>(P, wg);
+    }
+    for (int item = 0; item < 2; ++item) {
+        const int count = item ? bb.dc_wg : bb.dw_wg;
+        int wg;
+        if (item == 0 || bb.dc_by_id) wg = id < count ? xcd_order(id, 0, count) : -1;
+        else wg = on_send;
+        if (wg < 0 || wg >= count) continue;
+        __syncthreads();                               // whatever ran before is done with LDS
+        const MfmaParams P = params_at(item ? offsetof(MfmaBwdBatch, dc) : offsetof(MfmaBwdBatch, dw));
+        mfma_workgroup<LD_KM, LD_KM, VEC, VEC, float, false, false, EPI_STORE>(P, wg);
+    }
+    if (id == 0 && bb.sgd_wg == 0 && (bb.sgd.tail.partial || bb.sgd.t[0].count > 0)) {
+        extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+        __syncthreads();
+        sgd_rider<__bf16>(bb.sgd, bb.lr, 0, 1, MFMA_THREADS, (float *)smem_raw);
     }
 }
 
@@ -1250,6 +1463,7 @@ struct MfmaFwdBatch {
     __bf16 *G;               // [M, N] per group
     int M, N, K;
     int64_t x_g, c_g, o_g;
+    int update_wg;           // = update.total_wg
     int wg_per_group;        // workgroups of the update per group
     int thin_rows;           // rows of the compression per workgroup: wg_per_group * thin_rows >= M
     FoldParams fold;         // FOLD kernels: the compression inside the update's loop instead (the fields above unused)
@@ -1259,12 +1473,13 @@ template <int VEC, bool DUAL, bool FOLD>
 __global__ __launch_bounds__(512, 1) void gemm_mfma_fwd_kernel(MfmaFwdBatch fb)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    const int wg = xcd_order((int)blockIdx.x, 0, fb.update.total_wg);
+    const int wg = xcd_order((int)blockIdx.x, 0, fb.update_wg);
+    const MfmaParams update = params_at(offsetof(MfmaFwdBatch, update));
     if constexpr (FOLD) {
         // the compression rides inside the update's reduction loop (FoldParams)
-        mfma_workgroup<LD_KC, LD_KC, VEC, VEC, __bf16, false, DUAL, EPI_BIAS_ACT, true>(fb.update, wg, &fb.fold);
+        mfma_workgroup<LD_KC, LD_KC, VEC, VEC, __bf16, false, DUAL, EPI_BIAS_ACT, true>(update, wg, &fb.fold);
     } else {
-        mfma_workgroup<LD_KC, LD_KC, VEC, VEC, __bf16, false, DUAL, EPI_BIAS_ACT>(fb.update, wg);
+        mfma_workgroup<LD_KC, LD_KC, VEC, VEC, __bf16, false, DUAL, EPI_BIAS_ACT>(update, wg);
         const int grp = wg / fb.wg_per_group;
         const int first = (wg - grp * fb.wg_per_group) * fb.thin_rows;
         const int last = min(first + fb.thin_rows, fb.M);

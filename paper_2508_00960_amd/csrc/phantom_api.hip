@@ -163,8 +163,9 @@ struct ProfRec {
     const char *name;
     int64_t M, N, K;
     int groups;
-    int64_t M2, N2, K2;   // second and third product of a launch that carries several (0 if none)
+    int64_t M2, N2, K2;   // second to fourth product of a launch that carries several (0 if none)
     int64_t M3, N3, K3;
+    int64_t M4, N4, K4;
 };
 struct Profiler {
     bool on = false;
@@ -182,7 +183,8 @@ struct ProfScope {
     hipStream_t st;
     long idx = -1;
     ProfScope(const char *name, int64_t M, int64_t N, int64_t K, int groups, hipStream_t s, int64_t M2 = 0,
-              int64_t N2 = 0, int64_t K2 = 0, int64_t M3 = 0, int64_t N3 = 0, int64_t K3 = 0) : st(s)
+              int64_t N2 = 0, int64_t K2 = 0, int64_t M3 = 0, int64_t N3 = 0, int64_t K3 = 0, int64_t M4 = 0, int64_t N4 = 0,
+              int64_t K4 = 0) : st(s)
     {
         if (!g_prof.on) return;
         if (!g_prof.calibrated) {
@@ -192,7 +194,7 @@ struct ProfScope {
             g_prof.calibrated = true;
             for (int i = 0; i < PROF_CALIBRATION_LAUNCHES && g_prof.recs.size() < g_prof.cap; ++i) {
                 const long at = (long)g_prof.recs.size();
-                g_prof.recs.push_back(ProfRec{PROF_EMPTY_NAME, 0, 0, 0, 1, 0, 0, 0, 0, 0, 0});
+                g_prof.recs.push_back(ProfRec{PROF_EMPTY_NAME, 0, 0, 0, 1, 0, 0, 0, 0, 0, 0, 0, 0, 0});
                 (void)hipEventRecord(g_prof.ev[2 * at], st);
                 hipLaunchKernelGGL(fill_zero_kernel, dim3(256), dim3(256), 0, st, (float *)nullptr, (int64_t)0);
                 (void)hipEventRecord(g_prof.ev[2 * at + 1], st);
@@ -200,7 +202,7 @@ struct ProfScope {
         }
         if (g_prof.recs.size() >= g_prof.cap) return;
         idx = (long)g_prof.recs.size();
-        g_prof.recs.push_back(ProfRec{name, M, N, K, groups, M2, N2, K2, M3, N3, K3});
+        g_prof.recs.push_back(ProfRec{name, M, N, K, groups, M2, N2, K2, M3, N3, K3, M4, N4, K4});
         (void)hipEventRecord(g_prof.ev[2 * idx], st);
     }
     ~ProfScope()
@@ -222,6 +224,7 @@ struct Arena {
 };
 
 constexpr int MSE_BLOCKS = 1024;
+constexpr int PIECE_WORDS = 512;      // output tiles of the products of one launch whose reduction may be cut into pieces (MfmaParams::arrived)
 
 struct BwdWs {
     void *delta;        // [groups, B, so] storage type
@@ -242,6 +245,9 @@ struct StepWs {
                                                     //   its gradients while the layer below writes its own
     float *dbias, *mse_partial;                     // dbias: one block, layer l's [groups, so_l] at dbias_at[l]
     std::vector<int64_t> dbias_at;                  // float offsets into dbias; dbias_at[layers] = the block's length
+    unsigned *arrived;                              // PIECE_WORDS words right behind the dbias block: cleared with it at the
+                                                    //   start of a step, left zero by every launch that uses them
+    float *parts;                                   // one rank: the pieces' results of cut weight gradients (plan_pieces)
     BwdWs bwd;
 };
 
@@ -253,6 +259,41 @@ bool relu_bits_ok(const std::vector<Geo> &geos, size_t l)
 {
     return l + 1 < geos.size() && geos[l].act == PH_ACT_RELU && geos[l].dtype == PH_BF16 && geos[l].vec == 8 &&
            geos[l + 1].vec == 8;
+}
+
+inline int64_t tiles_of(int64_t M, int64_t N) { return ((M + MT - 1) / MT) * ((N + MT - 1) / MT); }
+
+// One rank's weight gradients [so, si + q k] and compressor gradient [k, si] cover few of the 256 compute units when
+// the shard is narrow (configuration 4: 128 + 8 tiles of 64 reduction steps each).  They are cut along the batch
+// into pieces that add up without atomics (MfmaParams::parts): the weight gradients towards one piece per compute
+// unit with at least 16 steps each, the compressor gradient into pieces of at least 8 steps.
+struct PiecePlan {
+    int split_dw, split_dc;
+    size_t slots;        // 128 x 128 float tiles for the pieces' results
+};
+
+PiecePlan plan_pieces(const Geo &g)
+{
+    const int64_t ksteps = (g.B + KT - 1) / KT;
+    const int64_t t_dw = tiles_of(g.so, g.Kc), t_dc = g.q > 0 ? tiles_of(g.k, g.si) : 0;
+    PiecePlan pl{1, 1, 0};
+    pl.split_dw = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(256 / t_dw, ksteps / 16), 4));
+    pl.split_dc = (int)std::max<int64_t>(1, std::min<int64_t>(ksteps / 8, 8));
+    if (pl.split_dw > 1) pl.slots += (size_t)t_dw * pl.split_dw;
+    if (pl.split_dc > 1) pl.slots += (size_t)t_dc * pl.split_dc;
+    return pl;
+}
+
+// Does the step run its backward pass in one rank's merged launches (gemm_mfma_bwd_kernel)?  One rank with peers,
+// bf16 with 8-element vectors in every layer, and weight gradients that leave compute units idle.
+bool merged_backward(const std::vector<Geo> &geos)
+{
+    for (const Geo &g : geos) {
+        if (g.all || g.dtype != PH_BF16 || g.vec != 8 || g.q <= 0) return false;
+        const int64_t t_dw = tiles_of(g.so, g.Kc), t_dc = tiles_of(g.k, g.si);
+        if (t_dw > 192 || t_dw + t_dc > PIECE_WORDS) return false;
+    }
+    return true;
 }
 
 // geos: every layer's shapes.  Buffers that are reused from layer to layer take the largest layer's size.
@@ -289,7 +330,12 @@ StepWs carve_step(Arena &a, const std::vector<Geo> &geos)
         w.dCw[set] = (float *)a.take(groups * cw_max * 4 + 16);
         w.dDw[set] = (float *)a.take(groups * dw_max * 4 + 16);
     }
-    w.dbias = (float *)a.take((size_t)dbias_total * 4);
+    w.dbias = (float *)a.take((size_t)(dbias_total + PIECE_WORDS) * 4);
+    w.arrived = w.dbias ? (unsigned *)(w.dbias + dbias_total) : nullptr;
+    size_t parts_bytes = 0;
+    if (merged_backward(geos))
+        for (const Geo &g : geos) parts_bytes = std::max(parts_bytes, plan_pieces(g).slots * (size_t)MT * MT * sizeof(float));
+    w.parts = parts_bytes ? (float *)a.take(parts_bytes) : nullptr;
     w.mse_partial = (float *)a.take(MSE_BLOCKS * sizeof(float));
     w.bwd.delta = a.take(groups * B * act_max * g0.esz);
     return w;
@@ -303,8 +349,6 @@ inline unsigned blocks_for(int64_t count, int per_block = 256, int cap = 8192)
     if (b > cap) b = cap;
     return (unsigned)b;
 }
-
-inline int64_t tiles_of(int64_t M, int64_t N) { return ((M + MT - 1) / MT) * ((N + MT - 1) / MT); }
 
 // How a product is to be run: loader kinds of the two operands for the MFMA kernel, the vector
 // width the problem allows (0: use the shape-agnostic kernel), and whether the reduction may be
@@ -410,6 +454,7 @@ ph_status launch_mfma(const GemmPlan &plan, const Product *prods, int count, int
     batch.count = count;
     batch.p[0] = mfma_params(first, groups, ksplit, dual);
     batch.total_wg = batch.p[0].total_wg;
+    batch.first_wg = batch.p[0].total_wg;
     if (count == 2) {
         batch.p[1] = mfma_params(prods[1], groups, 1, dual);
         batch.total_wg += batch.p[1].total_wg;
@@ -495,6 +540,7 @@ ph_status launch_tail(const Product *head, const Product &tail0, const Product &
     tb.tail_first = (tb.head_wg + 7) & ~7;
     tb.tail[0] = mfma_params(tail0, groups, 1, dual);
     tb.tail_wg = tb.tail[0].total_wg;
+    tb.tail0_wg = tb.tail[0].total_wg;
     if (two) {
         tb.tail[1] = mfma_params(tail1, groups, 1, dual);
         tb.tail_wg += tb.tail[1].total_wg;
@@ -511,6 +557,67 @@ ph_status launch_tail(const Product *head, const Product &tail0, const Product &
     case 4: return launch_tail_kernel<4>(tb, total, st, what);
     default: return launch_tail_kernel<2>(tb, total, st, what);
     }
+}
+
+// One rank's backward launch (MfmaBwdBatch): layer l's input gradient and error compression (dx, send: NULL or
+// empty if there is none), the weight and compressor gradients of layer l + 1 cut into pieces as `pieces` says
+// (dw, dc: NULL if there are none), and the SGD update of layer l + 2 or the end of the loss on sgd_wg workgroups
+// (sgd: NULL if there is neither).  parts, arrived: see MfmaParams.
+// sgd_dw, sgd_dc: the update of layer l + 1 inside the epilogues that finish its cut gradients (NULL: none; only for
+// products that are cut).  sgd_wg == 0 with sgd: workgroup 0 does that work behind its products.
+ph_status launch_bwd_merged(const Product *dx, const Product *send, const Product *dw, const Product *dc, const PiecePlan &pieces,
+                            float *parts, unsigned *arrived, const SgdInPlace *sgd_dw, const SgdInPlace *sgd_dc,
+                            const SgdBatch *sgd, float lr, int sgd_wg, hipStream_t st, const char *what)
+{
+    auto present = [](const Product *pr) { return pr && pr->M > 0 && pr->N > 0; };
+    MfmaBwdBatch bb{};
+    int64_t first_tiles = 0;
+    if (present(dx)) first_tiles += tiles_of(dx->M, dx->N);
+    if (present(send)) first_tiles += tiles_of(send->M, send->N);
+    if (first_tiles * 8 > 0x7fffffff) return fail(PH_ERR_LAUNCH, "%s: internal error, too many tiles (make_geo admits none such)", what);
+    const bool dual = first_tiles > 256;               // as for a launch of the two alone
+    bb.dual = dual;
+    if (present(dx)) bb.dx = mfma_params(*dx, 1, 1, dual);
+    if (present(send)) bb.send = mfma_params(*send, 1, 1, dual);
+    bb.first_wg = bb.dx.total_wg + bb.send.total_wg;
+    if (present(dw)) {
+        const int64_t t_dw = tiles_of(dw->M, dw->N);
+        bb.dw = mfma_params(*dw, 1, pieces.split_dw, false);
+        if (bb.dw.ksplit > 1) { bb.dw.parts = parts; bb.dw.arrived = arrived; if (sgd_dw) bb.dw.sgd = *sgd_dw; }
+        else if (sgd_dw) return fail(PH_ERR_LAUNCH, "%s: internal error, update inside a weight gradient that is not cut", what);
+        if (present(dc)) {
+            bb.dc = mfma_params(*dc, 1, pieces.split_dc, false);
+            if (bb.dc.ksplit > 1) {
+                bb.dc.parts = parts + (pieces.split_dw > 1 ? (size_t)t_dw * pieces.split_dw * MT * MT : 0);
+                bb.dc.arrived = arrived + t_dw;
+                if (sgd_dc) bb.dc.sgd = *sgd_dc;
+            } else if (sgd_dc) return fail(PH_ERR_LAUNCH, "%s: internal error, update inside a compressor gradient that is not cut", what);
+        }
+    }
+    // the compressor gradient's pieces go to the workgroups that had the error compression if those are enough
+    bb.dc_by_id = bb.first_wg == 0 || bb.dc.total_wg > bb.send.total_wg;
+    const int most = std::max(std::max(bb.first_wg, bb.dw.total_wg), bb.dc_by_id ? bb.dc.total_wg : 0);
+    bb.main_wg = (most + 7) & ~7;
+    bb.dx_wg = bb.dx.total_wg; bb.send_wg = bb.send.total_wg; bb.dw_wg = bb.dw.total_wg; bb.dc_wg = bb.dc.total_wg;
+    bb.sgd_wg = sgd ? sgd_wg : 0;
+    if (sgd) { bb.sgd = *sgd; bb.lr = lr; }
+    auto dim = [&](const Product *pr, int which) -> int64_t { return present(pr) ? (which == 0 ? pr->M : which == 1 ? pr->N : pr->K) : 0; };
+    // shapes in the order weight gradients, compressor gradient, input gradient, error compression; without the
+    // first two, the input gradient and the error compression come first
+    const Product *order[4] = {dw, dc, dx, send};
+    if (!present(dw)) { order[0] = dx; order[1] = send; order[2] = order[3] = nullptr; }
+    ProfScope prof(what, dim(order[0], 0), dim(order[0], 1), dim(order[0], 2), 1, st, dim(order[1], 0), dim(order[1], 1), dim(order[1], 2),
+                   dim(order[2], 0), dim(order[2], 1), dim(order[2], 2), dim(order[3], 0), dim(order[3], 1), dim(order[3], 2));
+    auto kern = gemm_mfma_bwd_kernel<8>;
+    static thread_local bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, MFMA_LDS_BYTES);
+        if (e != hipSuccess) return fail(PH_ERR_LAUNCH, "%s: cannot reserve %d bytes of LDS: %s", what, MFMA_LDS_BYTES,
+                                         hipGetErrorString(e));
+        configured = true;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(bb.main_wg + bb.sgd_wg)), dim3(MFMA_THREADS), MFMA_LDS_BYTES, st, bb);
+    return check_launch(what);
 }
 
 // One rank's thin compression and layer update in one launch: see MfmaFwdBatch.
@@ -539,6 +646,7 @@ ph_status launch_fwd_pair(const Product &update, const Product &compress, int gr
     fb.X = (const __bf16 *)compress.a.p0; fb.C = (const __bf16 *)compress.b.p0; fb.G = (__bf16 *)compress.o.p0;
     fb.M = (int)compress.M; fb.N = (int)compress.N; fb.K = (int)compress.K;
     fb.x_g = compress.a.g0; fb.c_g = compress.b.g0; fb.o_g = compress.o.g0;
+    fb.update_wg = fb.update.total_wg;
     fb.wg_per_group = fb.update.total_wg / groups;
     fb.thin_rows = (int)(((compress.M + fb.wg_per_group - 1) / fb.wg_per_group + 15) / 16 * 16);
     const unsigned total = (unsigned)fb.update.total_wg;
@@ -766,10 +874,69 @@ ph_status tap_copy(void *dst, const void *src, int64_t count, hipStream_t st)
     return check_launch("tap copy");
 }
 
+// error compression: dG_send[i] = delta . D_i   ([B, so] x [so, k] for every peer, one product over N = q*k);
+// w_out, kk: the output width and phantom width of the layer whose delta (dl) and D these are
+Product error_compression_product(int64_t B, int64_t q, void *dG_send, const void *dl, const void *Dw, int64_t w_out, int64_t kk)
+{
+    Product send{};
+    send.a = view_plain(dl, w_out, B * w_out);
+    send.b.p0 = nullptr; send.b.p1 = const_cast<void *>(Dw); send.b.g0 = 0; send.b.g1 = q * w_out * kk;
+    send.b.r = axis_seg(0, (int)kk, 0, 1, w_out * kk); send.b.c = axis_plain(0, kk);
+    send.b.skip0 = NO_SKIP; send.b.skip_g = 0;
+    send.o.p0 = nullptr; send.o.p1 = dG_send; send.o.g0 = 0; send.o.g1 = q * B * kk;
+    send.o.r = axis_plain(0, kk); send.o.c = axis_seg(0, (int)kk, 0, 1, B * kk);
+    send.o.skip0 = NO_SKIP; send.o.skip_g = 0;
+    send.ep = epi_store();
+    send.M = q > 0 ? B : 0; send.N = q * kk; send.K = w_out;
+    return send;
+}
+
+// The four products of a layer's backward pass (Eq. (backprop), (bpL)-(bpD)) from its local error delta.
+struct BwdProducts {
+    Product send, dx, dw, dc;
+};
+
+BwdProducts make_bwd_products(const Geo &g, const BwdArgs &b, const void *delta)
+{
+    const int64_t B = g.B, si = g.si, so = g.so, k = g.k, q = g.q;
+    BwdProducts pr{};
+    pr.send = error_compression_product(B, q, b.dG_send, delta, b.Dw, so, k);
+
+    // dX = delta . L + dg_own . C: reduction index = [delta | dg_own] against [L ; C]
+    Product &dx = pr.dx;
+    dx.a = q > 0 ? view_rowseg(delta, so, (int)so, B * so, b.dg_own, (int)k, 0, B * k) : view_plain(delta, so, B * so);
+    dx.b = q > 0 ? view_colstack(b.Lw, si, (int)so, so * si, b.Cw, si, (int)k, k * si) : view_plain_t(b.Lw, si, so * si);
+    dx.o = view_plain(b.dX, si, B * si);
+    dx.ep = epi_store();
+    if (b.dx_S && g.act != PH_ACT_IDENTITY) {
+        dx.ep.mode = EPI_DACT; dx.ep.act = g.act; dx.ep.aux = const_cast<void *>(b.dx_S); dx.ep.aux_ld = si;
+        dx.ep.aux_g = B * si; dx.ep.aux_f32 = b.dx_S_f32; dx.ep.aux_deriv = b.dx_S_deriv; dx.ep.aux_bits = b.dx_S_bits;
+    } else if (b.dx_colsum) {
+        dx.ep.mode = EPI_DACT; dx.ep.act = g.act; dx.ep.aux = nullptr;      // identity: column sums only
+    }
+    dx.ep.colsum = b.dx_colsum; dx.ep.colsum_g = si;
+    dx.M = b.dX ? B : 0; dx.N = si; dx.K = so + k;
+
+    // weight gradients: [dL | dD_1 .. dD_{p-1}] = delta^T . [X | G_1 .. G_{p-1}], and dC = dg_own^T . X beside it
+    Product &dw = pr.dw;
+    dw.a = view_plain_t(delta, so, B * so);
+    dw.b = q > 0 ? view_rowseg_t(b.X, si, (int)si, B * si, b.G, (int)k, B * k, 0, g.all ? 0 : NO_SKIP, g.all ? 1 : 0)
+                 : view_plain_t(b.X, si, B * si);
+    dw.o.p0 = b.dLw; dw.o.p1 = b.dDw; dw.o.g0 = so * si; dw.o.g1 = q * so * k;
+    dw.o.r = axis_plain(si, k);
+    dw.o.c = q > 0 ? axis_seg((int)si, (int)k, 1, 1, so * k) : axis_plain(1, 0);
+    dw.o.skip0 = NO_SKIP; dw.o.skip_g = 0;
+    dw.ep = epi_store();
+    dw.M = so; dw.N = g.Kc; dw.K = B;
+    pr.dc = Product{view_plain_t(b.dg_own, k, B * k), view_plain_t(b.X, si, B * si), view_plain(b.dCw, si, k * si), epi_store(),
+                    q > 0 ? k : 0, si, B};
+    return pr;
+}
+
 template <typename T>
 ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t st)
 {
-    const int64_t B = g.B, si = g.si, so = g.so, k = g.k, q = g.q;
+    const int64_t B = g.B, so = g.so, k = g.k, q = g.q;
     const int64_t act_count = (int64_t)g.groups * B * so;
 
     // local error delta = dY * sigma'
@@ -812,51 +979,12 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
         }
     }
 
-    // error compression: dG_send[i] = delta . D_i   ([B, so] x [so, k] for every peer, one product over N = q*k);
-    // w, kk: the output width and phantom width of the layer whose delta and D these are
+    BwdProducts pr = make_bwd_products(g, b, delta);
+    const Product &send = pr.send, &dw = pr.dw, &dc = pr.dc;
+    Product &dx = pr.dx;
     auto error_compression = [&](const void *dl, const void *Dw, int64_t w_out, int64_t kk) {
-        Product send{};
-        send.a = view_plain(dl, w_out, B * w_out);
-        send.b.p0 = nullptr; send.b.p1 = const_cast<void *>(Dw); send.b.g0 = 0; send.b.g1 = q * w_out * kk;
-        send.b.r = axis_seg(0, (int)kk, 0, 1, w_out * kk); send.b.c = axis_plain(0, kk);
-        send.b.skip0 = NO_SKIP; send.b.skip_g = 0;
-        send.o.p0 = nullptr; send.o.p1 = b.dG_send; send.o.g0 = 0; send.o.g1 = q * B * kk;
-        send.o.r = axis_plain(0, kk); send.o.c = axis_seg(0, (int)kk, 0, 1, B * kk);
-        send.o.skip0 = NO_SKIP; send.o.skip_g = 0;
-        send.ep = epi_store();
-        send.M = q > 0 ? B : 0; send.N = q * kk; send.K = w_out;
-        return send;
+        return error_compression_product(B, q, b.dG_send, dl, Dw, w_out, kk);
     };
-    const Product send = error_compression(delta, b.Dw, so, k);
-
-    // dX = delta . L + dg_own . C: reduction index = [delta | dg_own] against [L ; C]
-    Product dx{};
-    dx.a = q > 0 ? view_rowseg(delta, so, (int)so, B * so, b.dg_own, (int)k, 0, B * k) : view_plain(delta, so, B * so);
-    dx.b = q > 0 ? view_colstack(b.Lw, si, (int)so, so * si, b.Cw, si, (int)k, k * si) : view_plain_t(b.Lw, si, so * si);
-    dx.o = view_plain(b.dX, si, B * si);
-    dx.ep = epi_store();
-    if (b.dx_S && g.act != PH_ACT_IDENTITY) {
-        dx.ep.mode = EPI_DACT; dx.ep.act = g.act; dx.ep.aux = const_cast<void *>(b.dx_S); dx.ep.aux_ld = si;
-        dx.ep.aux_g = B * si; dx.ep.aux_f32 = b.dx_S_f32; dx.ep.aux_deriv = b.dx_S_deriv; dx.ep.aux_bits = b.dx_S_bits;
-    } else if (b.dx_colsum) {
-        dx.ep.mode = EPI_DACT; dx.ep.act = g.act; dx.ep.aux = nullptr;      // identity: column sums only
-    }
-    dx.ep.colsum = b.dx_colsum; dx.ep.colsum_g = si;
-    dx.M = b.dX ? B : 0; dx.N = si; dx.K = so + k;
-
-    // weight gradients: [dL | dD_1 .. dD_{p-1}] = delta^T . [X | G_1 .. G_{p-1}], and dC = dg_own^T . X beside it
-    Product dw{};
-    dw.a = view_plain_t(delta, so, B * so);
-    dw.b = q > 0 ? view_rowseg_t(b.X, si, (int)si, B * si, b.G, (int)k, B * k, 0, g.all ? 0 : NO_SKIP, g.all ? 1 : 0)
-                 : view_plain_t(b.X, si, B * si);
-    dw.o.p0 = b.dLw; dw.o.p1 = b.dDw; dw.o.g0 = so * si; dw.o.g1 = q * so * k;
-    dw.o.r = axis_plain(si, k);
-    dw.o.c = q > 0 ? axis_seg((int)si, (int)k, 1, 1, so * k) : axis_plain(1, 0);
-    dw.o.skip0 = NO_SKIP; dw.o.skip_g = 0;
-    dw.ep = epi_store();
-    dw.M = so; dw.N = g.Kc; dw.K = B;
-    Product dc{view_plain_t(b.dg_own, k, B * k), view_plain_t(b.X, si, B * si), view_plain(b.dCw, si, k * si), epi_store(),
-               q > 0 ? k : 0, si, B};
     // Riders of the weight-gradient launch (MfmaTailBatch) exist on the matrix-core path for launches of at most one
     // tile per compute unit.  PHANTOM_TAIL=0 switches them off (for measurements).
     const int64_t tail_tiles = (tiles_of(dw.M, dw.N) + tiles_of(dc.M, dc.N)) * g.groups;
@@ -1027,8 +1155,9 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
             PH_TRY(check_launch("clear bias gradients"));
         }
     }
-    float *clear_at = a.dbias ? nullptr : w.dbias;
-    const int64_t clear_count = a.dbias ? 0 : w.dbias_at[(size_t)L];
+    // (the words for cut reductions lie right behind the workspace's block and are cleared with it)
+    float *clear_at = a.dbias ? (float *)w.arrived : w.dbias;
+    const int64_t clear_count = a.dbias ? PIECE_WORDS : w.dbias_at[(size_t)L] + PIECE_WORDS;
 
     // The output error of the MSE loss (Eq. (deltaL)) is elementwise in the last layer's output, so on the MFMA
     // path that layer's update forms it in its epilogue, together with the last bias gradient and one partial
@@ -1104,6 +1233,131 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
         hipLaunchKernelGGL((sgd_kernel<T>), dim3(blocks_for(largest, 256, 2048), (unsigned)tensors), dim3(256), 0, st, batch, a.lr);
         return check_launch("SGD update");
     };
+    // One rank, narrow shards (merged_backward): the backward pass in launches that each carry the input gradient and
+    // error compression of layer l, the weight + compressor gradients of layer l + 1 in pieces, and the SGD update of
+    // layer l + 2 (gemm_mfma_bwd_kernel).  Layer l + 1's delta is still read while layer l - 1's is written: three
+    // buffers in rotation.
+    if constexpr (std::is_same<T, bf16_t>::value) {
+        if (mse_in_update && w.parts && merged_backward(geos)) {
+            void *dbuf[3] = {w.dYa, w.dYb, w.bwd.delta};
+            auto args_of = [&](int l, void *delta_l, void *delta_below) {
+                BwdArgs b{};
+                b.delta_ready = delta_l; b.X = inputs[l];
+                b.dx_colsum = l > 0 ? dbias_of(l - 1) : nullptr;
+                b.dx_S_bits = l > 0 && w.relu_bits[(size_t)l - 1] != nullptr;
+                b.dx_S = l > 0 ? (b.dx_S_bits ? w.relu_bits[(size_t)l - 1] : g.act == PH_ACT_GELU ? w.A[l - 1] : w.Y[l - 1]) : nullptr;
+                b.dx_S_f32 = gelu && !save_deriv;
+                b.dx_S_deriv = save_deriv;
+                b.Lw = a.Lw[l]; b.Cw = a.Cw[l]; b.Dw = a.Dw[l];
+                b.G = a.G[l];
+                b.dg_own = const_cast<void *>(a.dg_own[l]);
+                b.dX = l > 0 ? delta_below : nullptr;
+                b.dLw = a.dLw ? a.dLw[l] : w.dLw[l & 1];
+                b.dCw = a.dCw ? a.dCw[l] : w.dCw[l & 1];
+                b.dDw = a.dDw ? a.dDw[l] : w.dDw[l & 1];
+                b.dbias = dbias_of(l);
+                b.dG_send = w.dG_send;
+                return b;
+            };
+            auto sgd_of = [&](int l, const BwdArgs &b, SgdBatch &batch, int64_t &largest, int64_t &total) {
+                const Geo &gl = geos[(size_t)l];
+                struct Upd { void *w; float *master; const float *grad; int64_t count; };
+                const Upd upd[4] = {
+                    {a.Lw[l], a.Lw_master ? a.Lw_master[l] : nullptr, b.dLw, gl.so * gl.si},
+                    {a.bias[l], a.bias_master ? a.bias_master[l] : nullptr, b.dbias, gl.so},
+                    {a.Cw[l], a.Cw_master ? a.Cw_master[l] : nullptr, b.dCw, gl.k * gl.si},
+                    {a.Dw[l], a.Dw_master ? a.Dw_master[l] : nullptr, b.dDw, gl.q * gl.so * gl.k},
+                };
+                batch = SgdBatch{};
+                largest = total = 0;
+                for (int i = 0; i < 4; ++i) {
+                    batch.t[i] = SgdTensor{upd[i].w, upd[i].master, upd[i].grad, upd[i].count};
+                    largest = std::max(largest, upd[i].count);
+                    total += upd[i].count;
+                }
+            };
+            const bool update = a.mode != PH_STEP_NO_UPDATE;
+            BwdArgs above{};                   // layer l + 1, whose weight gradients go out with layer l's input gradient
+            BwdProducts above_pr{};
+            SgdBatch riding{};                 // the update of layer l + 2 where it could not run inside the epilogues of
+            bool have_riding = false;          //   the launch before (gradients that are not cut)
+            int64_t riding_largest = 0, riding_total = 0;
+            int cur = 0;
+            for (int l = L - 1; l >= -1; --l) {
+                const bool first_here = l >= 0 && L > 1;          // a single layer: its error compression waits for the
+                const bool above_here = l + 1 <= L - 1 && (L > 1 || l < 0);   // launch of its weight gradients
+                if (L == 1 && l == 0) {        // nothing to launch yet: the layer's products all go out at l = -1
+                    above = args_of(0, dbuf[cur], nullptr);
+                    above_pr = make_bwd_products(geos[0], above, dbuf[cur]);
+                    continue;
+                }
+                BwdArgs b{};
+                BwdProducts pr{};
+                void *below = dbuf[(cur + 1) % 3];
+                if (l >= 0) {
+                    b = args_of(l, dbuf[cur], below);
+                    pr = make_bwd_products(geos[(size_t)l], b, dbuf[cur]);
+                }
+                const int ul = L == 1 ? 0 : l + 1;                // the layer whose weight gradients this launch carries
+                const Product *dxp = first_here ? &pr.dx : nullptr;
+                const Product *sendp = first_here ? &pr.send : (L == 1 ? &above_pr.send : nullptr);
+                const Product *dwp = above_here ? &above_pr.dw : nullptr, *dcp = above_here ? &above_pr.dc : nullptr;
+                const PiecePlan pieces = above_here ? plan_pieces(geos[(size_t)ul]) : PiecePlan{1, 1, 0};
+                // Layer ul's update: inside the epilogues that finish its gradients if both products are cut (nothing
+                // reads its weights any more: its input gradient and error compression went out a launch ago), the
+                // bias by workgroup 0; else as a rider of the next launch.
+                const bool inside = above_here && update && pieces.split_dw > 1 && pieces.split_dc > 1 &&
+                                    (geos[(size_t)ul].B + KT - 1) / KT >= 2 * std::max(pieces.split_dw, pieces.split_dc);
+                SgdInPlace in_dw{}, in_dc{};
+                SgdBatch small{};              // what workgroup 0 does behind its products: layer ul's bias, the loss
+                if (inside) {
+                    in_dw = SgdInPlace{a.Lw_master[ul], a.Dw_master[ul], (__bf16 *)a.Lw[ul], (__bf16 *)a.Dw[ul], a.lr, (a.dLw || a.dDw) ? 1 : 0};
+                    in_dc = SgdInPlace{a.Cw_master[ul], nullptr, (__bf16 *)a.Cw[ul], nullptr, a.lr, a.dCw ? 1 : 0};
+                    small.t[0] = SgdTensor{a.bias[ul], a.bias_master[ul], above.dbias, geos[(size_t)ul].so};
+                }
+                const SgdBatch *rider = nullptr;
+                int rider_wg = 0;
+                if (have_riding && inside) {   // both kinds in one launch (layers of different shapes): the older one goes first
+                    PH_TRY(launch_sgd(riding, 4, riding_largest, riding_total));
+                    have_riding = false;
+                }
+                if (have_riding) {
+                    rider = &riding; rider_wg = 64;
+                    if (loss_tail.partial) { riding.tail = loss_tail; loss_tail.partial = nullptr; }
+                } else if (inside || loss_tail.partial) {
+                    if (loss_tail.partial) { small.tail = loss_tail; loss_tail.partial = nullptr; }
+                    rider = &small; rider_wg = 0;
+                }
+                const char *what = !dwp ? "input gradient + error compression | loss"
+                                   : (l < 0 && L > 1) ? (inside ? "weight + compressor gradients + SGD" : "weight + compressor gradients")
+                                   : (l <= 0) ? (inside ? "weight + compressor gradients above + SGD | error compression"
+                                                        : "weight + compressor gradients above | error compression")
+                                   : (inside ? "weight + compressor gradients above + SGD | input gradient + error compression"
+                                             : "weight + compressor gradients above | input gradient + error compression");
+                PH_TRY(launch_bwd_merged(dxp, sendp, dwp, dcp, pieces, w.parts, w.arrived, inside ? &in_dw : nullptr,
+                                         inside ? &in_dc : nullptr, rider, a.lr, rider_wg, st, what));
+                have_riding = false;
+                const int send_layer = first_here ? l : (L == 1 ? 0 : -1);
+                if (a.taps && send_layer >= 0 && a.taps->dG_send)
+                    PH_TRY(tap_copy<T>(a.taps->dG_send[send_layer], w.dG_send,
+                                       geos[(size_t)send_layer].q * B * geos[(size_t)send_layer].k, st));
+                if (a.taps && a.taps->delta && l > 0) PH_TRY(tap_copy<T>(a.taps->delta[l - 1], below, B * geos[(size_t)l].si, st));
+                if (above_here && update && !inside) {   // layer ul has its gradients now; its update rides with the next launch
+                    sgd_of(ul, above, riding, riding_largest, riding_total);
+                    if (l >= 0) have_riding = true;
+                    else PH_TRY(launch_sgd(riding, 4, riding_largest, riding_total));
+                }
+                above = b; above_pr = pr;
+                cur = (cur + 1) % 3;
+            }
+            if (loss_tail.partial) {           // no launch carried the rider (cannot happen: the first launch takes it)
+                hipLaunchKernelGGL(loss_kernel, dim3(1), dim3(256), 0, st, loss_tail);
+                PH_TRY(check_launch("loss"));
+            }
+            return PH_OK;
+        }
+    }
+
     for (int l = L - 1; l >= 0; --l) {
         BwdArgs b{};
         b.send_done = send_done;
@@ -1206,7 +1460,7 @@ ph_status check_ptr_array(const void *const *arr, int L, const char *name)
 
 extern "C" {
 
-int32_t phantom_abi_version(void) { return 3; }
+int32_t phantom_abi_version(void) { return 4; }
 
 ph_status phantom_profile_begin(int32_t max_launches)
 {
@@ -1243,7 +1497,7 @@ ph_status phantom_profile_end(ph_profile_entry *entries, int32_t capacity, int32
             if (!strncmp(entries[j].name, r.name, sizeof entries[j].name - 1) && entries[j].M == r.M &&
                 entries[j].N == r.N && entries[j].K == r.K && entries[j].groups == r.groups && entries[j].M2 == r.M2 &&
                 entries[j].N2 == r.N2 && entries[j].K2 == r.K2 && entries[j].M3 == r.M3 && entries[j].N3 == r.N3 &&
-                entries[j].K3 == r.K3)
+                entries[j].K3 == r.K3 && entries[j].M4 == r.M4 && entries[j].N4 == r.N4 && entries[j].K4 == r.K4)
                 at = j;
         if (at < 0) {
             if (used >= capacity) continue;
@@ -1253,6 +1507,7 @@ ph_status phantom_profile_end(ph_profile_entry *entries, int32_t capacity, int32
             entries[at].M = r.M; entries[at].N = r.N; entries[at].K = r.K; entries[at].groups = r.groups;
             entries[at].M2 = r.M2; entries[at].N2 = r.N2; entries[at].K2 = r.K2;
             entries[at].M3 = r.M3; entries[at].N3 = r.N3; entries[at].K3 = r.K3;
+            entries[at].M4 = r.M4; entries[at].N4 = r.N4; entries[at].K4 = r.K4;
         }
         entries[at].calls += 1;
         entries[at].total_ms += ms;

@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
             "phantom_last_error"} <= set(names)
     for name in names:
         assert hasattr(lib, name), name
-    assert ph.abi_version() == 3
+    assert ph.abi_version() == 4
 
 
 def test_struct_layout_matches_header():
@@ -33,6 +33,8 @@ def test_struct_layout_matches_header():
     assert ctypes.sizeof(PhStepArgs) == 18 * 8 + 8 + 8
     from paper_2508_00960_amd.binding import PhStepTaps
     assert ctypes.sizeof(PhStepTaps) == 5 * 8
+    from paper_2508_00960_amd.binding import PhProfileEntry
+    assert ctypes.sizeof(PhProfileEntry) == 64 + 3 * 8 + 2 * 4 + 8 + 9 * 8
 
 
 @pytest.mark.parametrize("kwargs,fragment", [

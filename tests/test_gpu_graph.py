@@ -66,6 +66,7 @@ def assert_same(what, got, want, tol):
     (1024, 8, 32, 256, 3, "relu", "bf16", -1, "train"),       # all ranks: riders on the weight-gradient launches
     (1024, 8, 32, 256, 3, "relu", "bf16", -1, "no_update"),
     (2048, 16, 32, 384, 3, "gelu", "bf16", 0, "train"),        # one rank: forward pair, deferred SGD
+    (2048, 16, 32, 2304, 2, "gelu", "bf16", 0, "train"),       # one rank, long batch: weight gradients in pieces, SGD in their epilogues
     (288, 4, 5, 37, 2, "gelu", "f32", -1, "train"),            # fp32 kernels
 ])
 def test_graph_replays_match_eager_steps(n, p, k, B, L, act, dtype, rank, mode):
