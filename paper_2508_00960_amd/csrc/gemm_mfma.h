@@ -33,7 +33,7 @@
 //
 // Kernels in this file, all built on mfma_workgroup (one workgroup's work on one product):
 //   gemm_mfma_kernel       one product, or two of the same operand layout and output type
-//   gemm_mfma_bwd_kernel   one rank: input gradient + error compression, then pieces of the layer above's weight gradients
+//   gemm_mfma_table_kernel one rank: the weight + compressor gradients of all layers, parameter blocks in device memory
 //   gemm_mfma_tail_kernel  weight + compressor gradients with riders of other layouts (the error compression of
 //                          the layer below, the SGD update of the layer above)
 //   gemm_mfma_fwd_kernel   a rank's layer update with the thin compression shared out over its workgroups
@@ -327,8 +327,9 @@ struct SumOnRead {
     int p, k;
 };
 
-// SGD inside the epilogue that finishes a cut weight gradient (epilogue_pieces_from_lds): the parameters that the
-// gradient belongs to, laid out like the output View's two regions.  master0 == nullptr: none.
+// SGD inside the epilogue that finishes a weight gradient (float output with 8-element vectors, whole or cut into
+// pieces): the parameters that the gradient belongs to, laid out like the output View's two regions.
+// master0 == nullptr: none.
 struct SgdInPlace {
     float *master0, *master1;    // fp32 master copies: master -= lr * gradient
     __bf16 *w0, *w1;             // bf16 compute copies: w = bf16(master)
@@ -349,7 +350,7 @@ struct MfmaParams {
     float *parts;        // ksplit > 1 without atomics (float output, 8-element vectors, one group): room for ksplit
     unsigned *arrived;   //   tiles of 128 x 128 floats per output tile, and one word per output tile, zero on entry
                          //   and left zero (see epilogue_pieces_from_lds)
-    SgdInPlace sgd;      //   ... and what the piece that finishes a tile does with the gradient besides storing it
+    SgdInPlace sgd;      // what the epilogue that finishes a float output tile does besides storing it
 };
 
 // The vectors of a K-contiguous A tile (reduction start c0) that lie in the summed block: replaces what the loader
@@ -682,7 +683,25 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
             else aux_v[i].h = *(const BfV *)((const __bf16 *)ep.aux + aux_at);
         }
     }
-    constexpr int EPI_UNROLL = EPI == EPI_DACT ? PASSES : 2;     // EPI_DACT: unrolled, the prefetched vectors stay in registers
+    // the master weights of an update inside this epilogue (SgdInPlace), likewise ahead of the loop
+    constexpr bool SGD_INSIDE = EPI == EPI_STORE && sizeof(TOut) == 4 && VEC == 8;
+    constexpr int SGD_PASSES = SGD_INSIDE ? PASSES : 1;
+    FlV master_v[SGD_PASSES];
+    if constexpr (SGD_INSIDE) {
+        if (P.sgd.master0) {                           // uniform
+            const int n = n0 + (thread % PER_ROW) * VEC;
+            const Loc ln = locate(P.o.c, min(n, P.N - 1), skip_o);
+            const int region = ln.region > 0 ? 1 : 0;
+            const float *base = (region ? P.sgd.master1 + g * P.o.g1 + ln.off1 : P.sgd.master0 + g * P.o.g0 + ln.off0);
+#pragma unroll
+            for (int i = 0; i < SGD_PASSES; ++i) {
+                const int m = m0 + (thread + i * THREADS) / PER_ROW;
+                if (m >= P.M || n >= P.N) continue;
+                master_v[i] = *(const FlV *)(base + (int64_t)m * (region ? P.o.r.mult1 : P.o.r.mult0));
+            }
+        }
+    }
+    constexpr int EPI_UNROLL = (EPI == EPI_DACT || SGD_INSIDE) ? PASSES : 2;     // unrolled: the prefetched vectors stay in registers
 #pragma unroll EPI_UNROLL
     for (int i = 0; i < PASSES; ++i) {
         const int v = thread + i * THREADS;
@@ -782,6 +801,24 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
         OutV o;
 #pragma unroll
         for (int u = 0; u < VEC; ++u) o[u] = from_f32<TOut>(x[u]);
+        if constexpr (EPI == EPI_STORE && sizeof(TOut) == 4 && VEC == 8) {
+            if (P.sgd.master0) {                       // uniform: Section VI's plain SGD on the finished gradient
+                const int64_t at = dst - (region ? o1 : o0);
+                float *master = (region ? P.sgd.master1 : P.sgd.master0) + g * (region ? P.o.g1 : P.o.g0) + at;
+                __bf16 *w = (region ? P.sgd.w1 : P.sgd.w0) + g * (region ? P.o.g1 : P.o.g0) + at;
+                const FlV before = master_v[SGD_INSIDE ? i : 0];
+                FlV after;
+                BfV rounded;
+#pragma unroll
+                for (int u = 0; u < VEC; ++u) {
+                    after[u] = before[u] - P.sgd.lr * x[u];
+                    rounded[u] = (__bf16)after[u];
+                }
+                *(FlV *)master = after;
+                *(BfV *)w = rounded;
+                if (!P.sgd.keep_grad) continue;
+            }
+        }
         *(OutV *)dst = o;
         if constexpr (EPI == EPI_BIAS_ACT && VEC == 8) {
             if (ep.mode == EPI_BIAS_ACT && ep.aux && ep.aux_bits) {     // uniform
@@ -1389,61 +1426,72 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_tail_kernel(MfmaTailBatch tb
     }
 }
 
-// One rank's backward launch: up to three pieces of work per workgroup, one after the other.
-//  1. a tile (DUAL: two tiles) of the input gradient of layer l (dx, sigma' epilogue) or of its error compression
-//     (send): workgroups [0, first_wg), dx's before send's; either may be empty;
-//  2. a piece of the weight gradients of layer l + 1 (dw), whose launch of its own would leave half of the compute
-//     units idle (configuration 4: 128 tiles): cut along the batch into dw.ksplit pieces (MfmaParams::parts), so
-//     that every compute unit that has finished a tile of 1. goes on with a piece of about equal length;
-//  3. a piece of that layer's compressor gradient (dc), on the workgroups that had the error compression in 1.,
-//     which finish earlier than those of the input gradient (no sigma' to read), or on the first ones (dc_by_id).
-// Nothing in 2. and 3. depends on 1.: the deltas of both layers are there before the launch.  Behind the
-// main_wg workgroups of the products, sgd_wg more run the SGD update of layer l + 2 (or only finish the loss).
-struct MfmaBwdBatch {
-    MfmaParams dx, send, dw, dc;
-    SgdBatch sgd;
-    float lr;
-    int dx_wg, send_wg, dw_wg, dc_wg;      // = their total_wg (the kernel reads the blocks only where it needs them)
-    int first_wg;        // = dx_wg + send_wg
-    int dual;            // dx and send in two-tile workgroups
-    int dc_by_id;        // dc's pieces on the first workgroups instead (no error compression, or too few workgroups of it)
-    int main_wg;         // multiple of 8, >= first_wg, dw.total_wg, and dc.total_wg if dc_by_id
-    int sgd_wg;          // 0 with work in sgd: workgroup 0 does it behind its products (a bias, the loss: little)
+// One rank's weight and compressor gradients of ALL layers in one launch, at the end of the backward pass.
+// They depend on nothing but each layer's delta and input, one layer's cover few of the 256 compute units with
+// narrow shards (configuration 4: 128 + 8 tiles of 64 reduction steps), and a launch per layer ends when its
+// slowest tile does; together they are 1088 tiles that the hardware deals out as compute units come free
+// (8 launches of 41 us against one of 170 us).  The SGD update runs in the epilogues (SgdInPlace): every
+// launch that reads the weights has finished by then.
+// The products' parameter blocks do not fit the 4 KB of kernel arguments (16 blocks of some 600 bytes), so they sit in
+// a table in device memory that small launches fill beforehand (table_upload_kernel).  Product j has the
+// workgroups [first_wg[j], first_wg[j + 1]) (starts are multiples of 8; workgroups beyond a product's own do nothing).
+constexpr int TABLE_PRODUCTS = 32;
+constexpr int CHUNK_PRODUCTS = 6;          // parameter blocks per upload launch: kernel arguments hold 4 KB
+
+struct ProductTable {
+    int count;
+    int first_wg[TABLE_PRODUCTS + 1];
+    int wgs[TABLE_PRODUCTS];               // = p[j].total_wg
+    MfmaParams p[TABLE_PRODUCTS];
 };
 
-template <int VEC>
-__global__ __launch_bounds__(512, 1) void gemm_mfma_bwd_kernel(MfmaBwdBatch bb)
+struct TableChunk {
+    int at, n;                             // blocks p[0 .. n) go to the table's entries at .. at + n
+    int count;                             // the table's count once every chunk is there
+    int first_wg[CHUNK_PRODUCTS + 1];      // first_wg[at .. at + n]
+    int wgs[CHUNK_PRODUCTS];
+    MfmaParams p[CHUNK_PRODUCTS];
+};
+static_assert(sizeof(TableChunk) + sizeof(void *) <= 3840, "a chunk travels as kernel arguments (4 KB with the hidden ones)");
+
+// one workgroup of 256 threads copies a chunk from the kernel arguments into the table
+__global__ __launch_bounds__(256) void table_upload_kernel(TableChunk c, ProductTable *table)
 {
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef const uint32_t __attribute__((address_space(4))) *ArgWords;
+    const ArgWords in = (ArgWords)((const char __attribute__((address_space(4))) *)__builtin_amdgcn_kernarg_segment_ptr() + offsetof(TableChunk, p));
+    uint32_t *out = (uint32_t *)(table->p + c.at);
+    const int words = c.n * (int)(sizeof(MfmaParams) / 4);
+    for (int i = (int)threadIdx.x; i < words; i += 256) out[i] = in[i];
+#endif
+    if ((int)threadIdx.x <= c.n) table->first_wg[c.at + threadIdx.x] = c.first_wg[threadIdx.x];
+    if ((int)threadIdx.x < c.n) table->wgs[c.at + threadIdx.x] = c.wgs[threadIdx.x];
+    if (threadIdx.x == 0) table->count = c.count;
+}
+
+template <int VEC>
+__global__ __launch_bounds__(512, 1) void gemm_mfma_table_kernel(const ProductTable *table)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    // read through the constant address space: the table is not written during this launch, and its entries are
+    // the same for every lane (scalar loads)
+    typedef const ProductTable __attribute__((address_space(4))) *TablePtr;
+    const TablePtr t = (TablePtr)(uintptr_t)table;
     const int id = (int)blockIdx.x;
-    if (id >= bb.main_wg) {
-        extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-        sgd_rider<__bf16>(bb.sgd, bb.lr, id - bb.main_wg, bb.sgd_wg, MFMA_THREADS, (float *)smem_raw);
-        return;
-    }
-    int on_send = -1;                                  // this workgroup's number among those of the error compression
-    if (id < bb.first_wg) {                            // uniform, like every branch here
-        int wg = xcd_order(id, 0, bb.first_wg);
-        const bool second = wg >= bb.dx_wg;
-        if (second) { wg -= bb.dx_wg; on_send = wg; }
-        const MfmaParams P = params_at(second ? offsetof(MfmaBwdBatch, send) : offsetof(MfmaBwdBatch, dx));
-        if (bb.dual) mfma_workgroup<LD_KC, LD_KM, VEC, VEC, __bf16, false, true, EPI_DACT>(P, wg);
-        else mfma_workgroup<LD_KC, LD_KM, VEC, VEC, __bf16, false, false, EPI_DACT>(P, wg);
-    }
-    for (int item = 0; item < 2; ++item) {
-        const int count = item ? bb.dc_wg : bb.dw_wg;
-        int wg;
-        if (item == 0 || bb.dc_by_id) wg = id < count ? xcd_order(id, 0, count) : -1;
-        else wg = on_send;
-        if (wg < 0 || wg >= count) continue;
-        __syncthreads();                               // whatever ran before is done with LDS
-        const MfmaParams P = params_at(item ? offsetof(MfmaBwdBatch, dc) : offsetof(MfmaBwdBatch, dw));
-        mfma_workgroup<LD_KM, LD_KM, VEC, VEC, float, false, false, EPI_STORE>(P, wg);
-    }
-    if (id == 0 && bb.sgd_wg == 0 && (bb.sgd.tail.partial || bb.sgd.t[0].count > 0)) {
-        extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-        __syncthreads();
-        sgd_rider<__bf16>(bb.sgd, bb.lr, 0, 1, MFMA_THREADS, (float *)smem_raw);
-    }
+    const int count = t->count;
+    int j = 0;
+    while (j + 1 < count && id >= t->first_wg[j + 1]) ++j;      // uniform
+    const int local = id - t->first_wg[j], wgs = t->wgs[j];
+    if (local >= wgs) return;
+    constexpr int WORDS = sizeof(MfmaParams) / 4;
+    union Words { MfmaParams p; uint32_t w[WORDS]; __device__ Words() {} };
+    Words blk;
+    typedef const uint32_t __attribute__((address_space(4))) *ArgWords;
+    const ArgWords in = (ArgWords)&t->p[j];
+#pragma unroll
+    for (int i = 0; i < WORDS; ++i) blk.w[i] = in[i];
+    mfma_workgroup<LD_KM, LD_KM, VEC, VEC, float, false, false, EPI_STORE>(blk.p, xcd_order(local, 0, wgs));
+#endif
 }
 
 // One rank's forward of a layer in one launch: the layer update, and the thin compression g = C y (see

@@ -247,7 +247,9 @@ struct StepWs {
     std::vector<int64_t> dbias_at;                  // float offsets into dbias; dbias_at[layers] = the block's length
     unsigned *arrived;                              // PIECE_WORDS words right behind the dbias block: cleared with it at the
                                                     //   start of a step, left zero by every launch that uses them
-    float *parts;                                   // one rank: the pieces' results of cut weight gradients (plan_pieces)
+    float *parts;                                   // deferred weight gradients (one rank): the pieces' results of the cut
+    ProductTable *table;                            //   compressor gradients, the launch's parameter table, and every
+    std::vector<void *> delta_of;                   //   layer's delta [B, so_l]
     BwdWs bwd;
 };
 
@@ -263,37 +265,26 @@ bool relu_bits_ok(const std::vector<Geo> &geos, size_t l)
 
 inline int64_t tiles_of(int64_t M, int64_t N) { return ((M + MT - 1) / MT) * ((N + MT - 1) / MT); }
 
-// One rank's weight gradients [so, si + q k] and compressor gradient [k, si] cover few of the 256 compute units when
-// the shard is narrow (configuration 4: 128 + 8 tiles of 64 reduction steps each).  They are cut along the batch
-// into pieces that add up without atomics (MfmaParams::parts): the weight gradients towards one piece per compute
-// unit with at least 16 steps each, the compressor gradient into pieces of at least 8 steps.
-struct PiecePlan {
-    int split_dw, split_dc;
-    size_t slots;        // 128 x 128 float tiles for the pieces' results
-};
-
-PiecePlan plan_pieces(const Geo &g)
+// One rank's backward pass over two or more layers keeps every layer's delta and runs all weight + compressor
+// gradients in one launch at its end (gemm_mfma_table_kernel) where a layer's own would leave compute units idle:
+// bf16 with 8-element vectors and at most 256 weight-gradient tiles in every layer.  (All ranks on the device:
+// the weight gradients' launches carry the next error compression and the update on the compute units they leave
+// idle, and putting them off made configuration 2 slower, 0.272 against 0.260 ms; a single layer has nothing to gain.)
+bool deferred_weight_gradients(const std::vector<Geo> &geos)
 {
-    const int64_t ksteps = (g.B + KT - 1) / KT;
-    const int64_t t_dw = tiles_of(g.so, g.Kc), t_dc = g.q > 0 ? tiles_of(g.k, g.si) : 0;
-    PiecePlan pl{1, 1, 0};
-    pl.split_dw = (int)std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(256 / t_dw, ksteps / 16), 4));
-    pl.split_dc = (int)std::max<int64_t>(1, std::min<int64_t>(ksteps / 8, 8));
-    if (pl.split_dw > 1) pl.slots += (size_t)t_dw * pl.split_dw;
-    if (pl.split_dc > 1) pl.slots += (size_t)t_dc * pl.split_dc;
-    return pl;
+    if (geos.size() < 2) return false;
+    for (const Geo &g : geos)
+        if (g.all || g.dtype != PH_BF16 || g.vec != 8 || tiles_of(g.so, g.Kc) > 256) return false;
+    return true;
 }
 
-// Does the step run its backward pass in one rank's merged launches (gemm_mfma_bwd_kernel)?  One rank with peers,
-// bf16 with 8-element vectors in every layer, and weight gradients that leave compute units idle.
-bool merged_backward(const std::vector<Geo> &geos)
+// The compressor gradient [k, si] of a layer has few tiles with a long reduction (configuration 4: 8 tiles of 64
+// steps, half of their rows empty).  In that launch they are cut along the batch into pieces of at least 16 steps,
+// at most 4, which go out first and add up without atomics (MfmaParams::parts).
+int compressor_gradient_pieces(const Geo &g)
 {
-    for (const Geo &g : geos) {
-        if (g.all || g.dtype != PH_BF16 || g.vec != 8 || g.q <= 0) return false;
-        const int64_t t_dw = tiles_of(g.so, g.Kc), t_dc = tiles_of(g.k, g.si);
-        if (t_dw > 192 || t_dw + t_dc > PIECE_WORDS) return false;
-    }
-    return true;
+    const int64_t ksteps = (g.B + KT - 1) / KT;
+    return (int)std::max<int64_t>(1, std::min<int64_t>(ksteps / 16, 4));
 }
 
 // geos: every layer's shapes.  Buffers that are reused from layer to layer take the largest layer's size.
@@ -332,10 +323,18 @@ StepWs carve_step(Arena &a, const std::vector<Geo> &geos)
     }
     w.dbias = (float *)a.take((size_t)(dbias_total + PIECE_WORDS) * 4);
     w.arrived = w.dbias ? (unsigned *)(w.dbias + dbias_total) : nullptr;
-    size_t parts_bytes = 0;
-    if (merged_backward(geos))
-        for (const Geo &g : geos) parts_bytes = std::max(parts_bytes, plan_pieces(g).slots * (size_t)MT * MT * sizeof(float));
-    w.parts = parts_bytes ? (float *)a.take(parts_bytes) : nullptr;
+    if (deferred_weight_gradients(geos)) {
+        size_t slots = 0;
+        for (const Geo &g : geos) {
+            w.delta_of.push_back(a.take((size_t)g.B * g.so * g.esz));
+            if (g.q > 0) slots += (size_t)tiles_of(g.k, g.si) * compressor_gradient_pieces(g);
+        }
+        w.parts = (float *)a.take(std::max<size_t>(slots, 1) * MT * MT * sizeof(float));
+        w.table = (ProductTable *)a.take(sizeof(ProductTable));
+    } else {
+        w.parts = nullptr;
+        w.table = nullptr;
+    }
     w.mse_partial = (float *)a.take(MSE_BLOCKS * sizeof(float));
     w.bwd.delta = a.take(groups * B * act_max * g0.esz);
     return w;
@@ -559,56 +558,15 @@ ph_status launch_tail(const Product *head, const Product &tail0, const Product &
     }
 }
 
-// One rank's backward launch (MfmaBwdBatch): layer l's input gradient and error compression (dx, send: NULL or
-// empty if there is none), the weight and compressor gradients of layer l + 1 cut into pieces as `pieces` says
-// (dw, dc: NULL if there are none), and the SGD update of layer l + 2 or the end of the loss on sgd_wg workgroups
-// (sgd: NULL if there is neither).  parts, arrived: see MfmaParams.
-// sgd_dw, sgd_dc: the update of layer l + 1 inside the epilogues that finish its cut gradients (NULL: none; only for
-// products that are cut).  sgd_wg == 0 with sgd: workgroup 0 does that work behind its products.
-ph_status launch_bwd_merged(const Product *dx, const Product *send, const Product *dw, const Product *dc, const PiecePlan &pieces,
-                            float *parts, unsigned *arrived, const SgdInPlace *sgd_dw, const SgdInPlace *sgd_dc,
-                            const SgdBatch *sgd, float lr, int sgd_wg, hipStream_t st, const char *what)
+// The weight-gradient-layout products `prods` (float out, 8-element vectors, one group each) in one launch through a
+// parameter table in device memory: see gemm_mfma_table_kernel.  splits[j] > 1 cuts product j's reduction into
+// pieces (parts, arrived: room for all of them, see MfmaParams); sgd[j].master0 != NULL puts the SGD update into
+// product j's epilogue.  More than TABLE_PRODUCTS products go out in several launches.
+ph_status launch_product_table(const std::vector<Product> &prods, const std::vector<int> &splits, const std::vector<SgdInPlace> &sgd,
+                               ProductTable *table, float *parts, unsigned *arrived, hipStream_t st, const char *what,
+                               const Product &prof_a, const Product &prof_b, int prof_groups)
 {
-    auto present = [](const Product *pr) { return pr && pr->M > 0 && pr->N > 0; };
-    MfmaBwdBatch bb{};
-    int64_t first_tiles = 0;
-    if (present(dx)) first_tiles += tiles_of(dx->M, dx->N);
-    if (present(send)) first_tiles += tiles_of(send->M, send->N);
-    if (first_tiles * 8 > 0x7fffffff) return fail(PH_ERR_LAUNCH, "%s: internal error, too many tiles (make_geo admits none such)", what);
-    const bool dual = first_tiles > 256;               // as for a launch of the two alone
-    bb.dual = dual;
-    if (present(dx)) bb.dx = mfma_params(*dx, 1, 1, dual);
-    if (present(send)) bb.send = mfma_params(*send, 1, 1, dual);
-    bb.first_wg = bb.dx.total_wg + bb.send.total_wg;
-    if (present(dw)) {
-        const int64_t t_dw = tiles_of(dw->M, dw->N);
-        bb.dw = mfma_params(*dw, 1, pieces.split_dw, false);
-        if (bb.dw.ksplit > 1) { bb.dw.parts = parts; bb.dw.arrived = arrived; if (sgd_dw) bb.dw.sgd = *sgd_dw; }
-        else if (sgd_dw) return fail(PH_ERR_LAUNCH, "%s: internal error, update inside a weight gradient that is not cut", what);
-        if (present(dc)) {
-            bb.dc = mfma_params(*dc, 1, pieces.split_dc, false);
-            if (bb.dc.ksplit > 1) {
-                bb.dc.parts = parts + (pieces.split_dw > 1 ? (size_t)t_dw * pieces.split_dw * MT * MT : 0);
-                bb.dc.arrived = arrived + t_dw;
-                if (sgd_dc) bb.dc.sgd = *sgd_dc;
-            } else if (sgd_dc) return fail(PH_ERR_LAUNCH, "%s: internal error, update inside a compressor gradient that is not cut", what);
-        }
-    }
-    // the compressor gradient's pieces go to the workgroups that had the error compression if those are enough
-    bb.dc_by_id = bb.first_wg == 0 || bb.dc.total_wg > bb.send.total_wg;
-    const int most = std::max(std::max(bb.first_wg, bb.dw.total_wg), bb.dc_by_id ? bb.dc.total_wg : 0);
-    bb.main_wg = (most + 7) & ~7;
-    bb.dx_wg = bb.dx.total_wg; bb.send_wg = bb.send.total_wg; bb.dw_wg = bb.dw.total_wg; bb.dc_wg = bb.dc.total_wg;
-    bb.sgd_wg = sgd ? sgd_wg : 0;
-    if (sgd) { bb.sgd = *sgd; bb.lr = lr; }
-    auto dim = [&](const Product *pr, int which) -> int64_t { return present(pr) ? (which == 0 ? pr->M : which == 1 ? pr->N : pr->K) : 0; };
-    // shapes in the order weight gradients, compressor gradient, input gradient, error compression; without the
-    // first two, the input gradient and the error compression come first
-    const Product *order[4] = {dw, dc, dx, send};
-    if (!present(dw)) { order[0] = dx; order[1] = send; order[2] = order[3] = nullptr; }
-    ProfScope prof(what, dim(order[0], 0), dim(order[0], 1), dim(order[0], 2), 1, st, dim(order[1], 0), dim(order[1], 1), dim(order[1], 2),
-                   dim(order[2], 0), dim(order[2], 1), dim(order[2], 2), dim(order[3], 0), dim(order[3], 1), dim(order[3], 2));
-    auto kern = gemm_mfma_bwd_kernel<8>;
+    auto kern = gemm_mfma_table_kernel<8>;
     static thread_local bool configured = false;
     if (!configured) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, MFMA_LDS_BYTES);
@@ -616,8 +574,42 @@ ph_status launch_bwd_merged(const Product *dx, const Product *send, const Produc
                                          hipGetErrorString(e));
         configured = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(bb.main_wg + bb.sgd_wg)), dim3(MFMA_THREADS), MFMA_LDS_BYTES, st, bb);
-    return check_launch(what);
+    size_t slot = 0, word = 0;
+    for (size_t begin = 0; begin < prods.size(); begin += TABLE_PRODUCTS) {
+        const size_t end = std::min(prods.size(), begin + TABLE_PRODUCTS);
+        std::vector<MfmaParams> blocks;
+        std::vector<int> first;
+        int next = 0;
+        for (size_t j = begin; j < end; ++j) {
+            const Product &pr = prods[j];
+            if (tiles_of(pr.M, pr.N) * 8 > 0x7fffffff) return fail(PH_ERR_LAUNCH, "%s: internal error, too many tiles (make_geo admits none such)", what);
+            MfmaParams P = mfma_params(pr, 1, splits[j], false);
+            const int64_t tiles = tiles_of(pr.M, pr.N);
+            if (P.ksplit > 1) {
+                P.parts = parts + slot * MT * MT; P.arrived = arrived + word;
+                slot += (size_t)tiles * splits[j]; word += (size_t)tiles;
+            }
+            P.sgd = sgd[j];
+            first.push_back(next);
+            next += (P.total_wg + 7) & ~7;
+            blocks.push_back(P);
+        }
+        first.push_back(next);
+        const int count = (int)blocks.size();
+        for (int at = 0; at < count; at += CHUNK_PRODUCTS) {
+            TableChunk c{};
+            c.at = at; c.n = std::min(CHUNK_PRODUCTS, count - at); c.count = count;
+            for (int i = 0; i < c.n; ++i) { c.p[i] = blocks[(size_t)(at + i)]; c.wgs[i] = blocks[(size_t)(at + i)].total_wg; }
+            for (int i = 0; i <= c.n; ++i) c.first_wg[i] = first[(size_t)(at + i)];
+            hipLaunchKernelGGL(table_upload_kernel, dim3(1), dim3(256), 0, st, c, table);
+            PH_TRY(check_launch("parameter table"));
+        }
+        // the profile entry: the caller's two shapes, prof_groups of each (exact when all layers have the same shapes)
+        ProfScope prof(what, prof_a.M, prof_a.N, prof_a.K, prof_groups, st, prof_b.M, prof_b.N, prof_b.K);
+        hipLaunchKernelGGL(kern, dim3((unsigned)next), dim3(MFMA_THREADS), MFMA_LDS_BYTES, st, (const ProductTable *)table);
+        PH_TRY(check_launch(what));
+    }
+    return PH_OK;
 }
 
 // One rank's thin compression and layer update in one launch: see MfmaFwdBatch.
@@ -863,6 +855,12 @@ struct BwdArgs {
                                //   the loss as a rider and clears loss_tail->partial; left alone if there is none
     void *tap_dG_send;         // step only, optional: copies of this layer's dG_send / (all ranks) dg_own, taken right
     void *tap_dg_own;          //   after the launch that finishes each
+    struct DeferredProducts *defer;   // step only: the weight + compressor gradients are not launched but added to this list
+};
+
+// weight and compressor gradient products of the layers whose backward pass has run, in that order (see BwdArgs::defer)
+struct DeferredProducts {
+    std::vector<Product> dw, dc;
 };
 
 // copy of a tensor for a tap of the step (count elements of the storage type)
@@ -992,7 +990,7 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
     const bool riders = std::is_same<T, bf16_t>::value && g.vec > 0 && tail_tiles <= 256 && !(tail_force && tail_force[0] == '0');
     // One rank, no input gradient wanted (the first layer): this layer's error compression has no launch to share
     // with the input gradient and nothing waits for it, so it rides with the weight gradients.
-    const bool send_rides = riders && !g.all && !b.dX && q > 0;
+    const bool send_rides = riders && !g.all && !b.dX && q > 0 && !b.defer;
 
     const GemmPlan plan_x{LD_KC, LD_KM, g.vec, false};
     const int64_t send_count = (int64_t)g.groups * q * B * k;
@@ -1038,6 +1036,11 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
     Product grads[2] = {dw, dc};
     if (b.below_done) *b.below_done = false;
     if (b.ride_sgd_done) *b.ride_sgd_done = false;
+    if (b.defer) {                 // the step launches them with the other layers' at the end of the backward pass
+        b.defer->dw.push_back(dw);
+        b.defer->dc.push_back(dc);
+        return PH_OK;
+    }
     if constexpr (std::is_same<T, bf16_t>::value) {
         if (riders) {
             // The layer below starts its backward with an error compression that fills half of the device or less
@@ -1172,7 +1175,11 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
         hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks_for(clear_count)), dim3(256), 0, st, clear_at, clear_count);
         PH_TRY(check_launch("clear bias gradients"));
     }
-    OutputError oe{a.T, w.dYa, w.mse_partial, 1.0f / (float)B, dbias_of(L - 1), clear_in_compression ? clear_at : nullptr,
+    // (one rank with deferred weight gradients keeps every layer's delta: the last layer's goes to its own buffer)
+    bool deferred = false;
+    if constexpr (std::is_same<T, bf16_t>::value) deferred = mse_in_update && w.table && deferred_weight_gradients(geos);
+    void *delta_top = deferred ? w.delta_of[(size_t)L - 1] : w.dYa;
+    OutputError oe{a.T, delta_top, w.mse_partial, 1.0f / (float)B, dbias_of(L - 1), clear_in_compression ? clear_at : nullptr,
                    clear_in_compression ? clear_count : 0};
 
     // forward through every layer; y_l stays in the storage type between layers
@@ -1221,7 +1228,7 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
         PH_TRY(check_launch("output error"));
     }
 
-    if (a.taps && a.taps->delta) PH_TRY(tap_copy<T>(a.taps->delta[L - 1], w.dYa, act_count, st));   // delta_L, Eq. (deltaL)
+    if (a.taps && a.taps->delta) PH_TRY(tap_copy<T>(a.taps->delta[L - 1], delta_top, act_count, st));   // delta_L, Eq. (deltaL)
 
     void *dY = w.dYa, *dX = w.dYb;    // delta of the current layer / of the layer below
     bool send_done = false;           // the current layer's error compression went out with the layer above
@@ -1233,131 +1240,10 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
         hipLaunchKernelGGL((sgd_kernel<T>), dim3(blocks_for(largest, 256, 2048), (unsigned)tensors), dim3(256), 0, st, batch, a.lr);
         return check_launch("SGD update");
     };
-    // One rank, narrow shards (merged_backward): the backward pass in launches that each carry the input gradient and
-    // error compression of layer l, the weight + compressor gradients of layer l + 1 in pieces, and the SGD update of
-    // layer l + 2 (gemm_mfma_bwd_kernel).  Layer l + 1's delta is still read while layer l - 1's is written: three
-    // buffers in rotation.
-    if constexpr (std::is_same<T, bf16_t>::value) {
-        if (mse_in_update && w.parts && merged_backward(geos)) {
-            void *dbuf[3] = {w.dYa, w.dYb, w.bwd.delta};
-            auto args_of = [&](int l, void *delta_l, void *delta_below) {
-                BwdArgs b{};
-                b.delta_ready = delta_l; b.X = inputs[l];
-                b.dx_colsum = l > 0 ? dbias_of(l - 1) : nullptr;
-                b.dx_S_bits = l > 0 && w.relu_bits[(size_t)l - 1] != nullptr;
-                b.dx_S = l > 0 ? (b.dx_S_bits ? w.relu_bits[(size_t)l - 1] : g.act == PH_ACT_GELU ? w.A[l - 1] : w.Y[l - 1]) : nullptr;
-                b.dx_S_f32 = gelu && !save_deriv;
-                b.dx_S_deriv = save_deriv;
-                b.Lw = a.Lw[l]; b.Cw = a.Cw[l]; b.Dw = a.Dw[l];
-                b.G = a.G[l];
-                b.dg_own = const_cast<void *>(a.dg_own[l]);
-                b.dX = l > 0 ? delta_below : nullptr;
-                b.dLw = a.dLw ? a.dLw[l] : w.dLw[l & 1];
-                b.dCw = a.dCw ? a.dCw[l] : w.dCw[l & 1];
-                b.dDw = a.dDw ? a.dDw[l] : w.dDw[l & 1];
-                b.dbias = dbias_of(l);
-                b.dG_send = w.dG_send;
-                return b;
-            };
-            auto sgd_of = [&](int l, const BwdArgs &b, SgdBatch &batch, int64_t &largest, int64_t &total) {
-                const Geo &gl = geos[(size_t)l];
-                struct Upd { void *w; float *master; const float *grad; int64_t count; };
-                const Upd upd[4] = {
-                    {a.Lw[l], a.Lw_master ? a.Lw_master[l] : nullptr, b.dLw, gl.so * gl.si},
-                    {a.bias[l], a.bias_master ? a.bias_master[l] : nullptr, b.dbias, gl.so},
-                    {a.Cw[l], a.Cw_master ? a.Cw_master[l] : nullptr, b.dCw, gl.k * gl.si},
-                    {a.Dw[l], a.Dw_master ? a.Dw_master[l] : nullptr, b.dDw, gl.q * gl.so * gl.k},
-                };
-                batch = SgdBatch{};
-                largest = total = 0;
-                for (int i = 0; i < 4; ++i) {
-                    batch.t[i] = SgdTensor{upd[i].w, upd[i].master, upd[i].grad, upd[i].count};
-                    largest = std::max(largest, upd[i].count);
-                    total += upd[i].count;
-                }
-            };
-            const bool update = a.mode != PH_STEP_NO_UPDATE;
-            BwdArgs above{};                   // layer l + 1, whose weight gradients go out with layer l's input gradient
-            BwdProducts above_pr{};
-            SgdBatch riding{};                 // the update of layer l + 2 where it could not run inside the epilogues of
-            bool have_riding = false;          //   the launch before (gradients that are not cut)
-            int64_t riding_largest = 0, riding_total = 0;
-            int cur = 0;
-            for (int l = L - 1; l >= -1; --l) {
-                const bool first_here = l >= 0 && L > 1;          // a single layer: its error compression waits for the
-                const bool above_here = l + 1 <= L - 1 && (L > 1 || l < 0);   // launch of its weight gradients
-                if (L == 1 && l == 0) {        // nothing to launch yet: the layer's products all go out at l = -1
-                    above = args_of(0, dbuf[cur], nullptr);
-                    above_pr = make_bwd_products(geos[0], above, dbuf[cur]);
-                    continue;
-                }
-                BwdArgs b{};
-                BwdProducts pr{};
-                void *below = dbuf[(cur + 1) % 3];
-                if (l >= 0) {
-                    b = args_of(l, dbuf[cur], below);
-                    pr = make_bwd_products(geos[(size_t)l], b, dbuf[cur]);
-                }
-                const int ul = L == 1 ? 0 : l + 1;                // the layer whose weight gradients this launch carries
-                const Product *dxp = first_here ? &pr.dx : nullptr;
-                const Product *sendp = first_here ? &pr.send : (L == 1 ? &above_pr.send : nullptr);
-                const Product *dwp = above_here ? &above_pr.dw : nullptr, *dcp = above_here ? &above_pr.dc : nullptr;
-                const PiecePlan pieces = above_here ? plan_pieces(geos[(size_t)ul]) : PiecePlan{1, 1, 0};
-                // Layer ul's update: inside the epilogues that finish its gradients if both products are cut (nothing
-                // reads its weights any more: its input gradient and error compression went out a launch ago), the
-                // bias by workgroup 0; else as a rider of the next launch.
-                const bool inside = above_here && update && pieces.split_dw > 1 && pieces.split_dc > 1 &&
-                                    (geos[(size_t)ul].B + KT - 1) / KT >= 2 * std::max(pieces.split_dw, pieces.split_dc);
-                SgdInPlace in_dw{}, in_dc{};
-                SgdBatch small{};              // what workgroup 0 does behind its products: layer ul's bias, the loss
-                if (inside) {
-                    in_dw = SgdInPlace{a.Lw_master[ul], a.Dw_master[ul], (__bf16 *)a.Lw[ul], (__bf16 *)a.Dw[ul], a.lr, (a.dLw || a.dDw) ? 1 : 0};
-                    in_dc = SgdInPlace{a.Cw_master[ul], nullptr, (__bf16 *)a.Cw[ul], nullptr, a.lr, a.dCw ? 1 : 0};
-                    small.t[0] = SgdTensor{a.bias[ul], a.bias_master[ul], above.dbias, geos[(size_t)ul].so};
-                }
-                const SgdBatch *rider = nullptr;
-                int rider_wg = 0;
-                if (have_riding && inside) {   // both kinds in one launch (layers of different shapes): the older one goes first
-                    PH_TRY(launch_sgd(riding, 4, riding_largest, riding_total));
-                    have_riding = false;
-                }
-                if (have_riding) {
-                    rider = &riding; rider_wg = 64;
-                    if (loss_tail.partial) { riding.tail = loss_tail; loss_tail.partial = nullptr; }
-                } else if (inside || loss_tail.partial) {
-                    if (loss_tail.partial) { small.tail = loss_tail; loss_tail.partial = nullptr; }
-                    rider = &small; rider_wg = 0;
-                }
-                const char *what = !dwp ? "input gradient + error compression | loss"
-                                   : (l < 0 && L > 1) ? (inside ? "weight + compressor gradients + SGD" : "weight + compressor gradients")
-                                   : (l <= 0) ? (inside ? "weight + compressor gradients above + SGD | error compression"
-                                                        : "weight + compressor gradients above | error compression")
-                                   : (inside ? "weight + compressor gradients above + SGD | input gradient + error compression"
-                                             : "weight + compressor gradients above | input gradient + error compression");
-                PH_TRY(launch_bwd_merged(dxp, sendp, dwp, dcp, pieces, w.parts, w.arrived, inside ? &in_dw : nullptr,
-                                         inside ? &in_dc : nullptr, rider, a.lr, rider_wg, st, what));
-                have_riding = false;
-                const int send_layer = first_here ? l : (L == 1 ? 0 : -1);
-                if (a.taps && send_layer >= 0 && a.taps->dG_send)
-                    PH_TRY(tap_copy<T>(a.taps->dG_send[send_layer], w.dG_send,
-                                       geos[(size_t)send_layer].q * B * geos[(size_t)send_layer].k, st));
-                if (a.taps && a.taps->delta && l > 0) PH_TRY(tap_copy<T>(a.taps->delta[l - 1], below, B * geos[(size_t)l].si, st));
-                if (above_here && update && !inside) {   // layer ul has its gradients now; its update rides with the next launch
-                    sgd_of(ul, above, riding, riding_largest, riding_total);
-                    if (l >= 0) have_riding = true;
-                    else PH_TRY(launch_sgd(riding, 4, riding_largest, riding_total));
-                }
-                above = b; above_pr = pr;
-                cur = (cur + 1) % 3;
-            }
-            if (loss_tail.partial) {           // no launch carried the rider (cannot happen: the first launch takes it)
-                hipLaunchKernelGGL(loss_kernel, dim3(1), dim3(256), 0, st, loss_tail);
-                PH_TRY(check_launch("loss"));
-            }
-            return PH_OK;
-        }
-    }
-
+    // Deferred weight gradients (deferred_weight_gradients): every layer's delta stays in a buffer of its own, the
+    // layers' backward launches stop after the input gradient, and the weight + compressor gradients of all layers
+    // go out in one launch at the end, the SGD update of L, C and D in its epilogues; then the biases and the loss.
+    DeferredProducts defer_list;
     for (int l = L - 1; l >= 0; --l) {
         BwdArgs b{};
         b.send_done = send_done;
@@ -1369,6 +1255,7 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
         // the layer's bias gradient is there already if the product that wrote its delta took the column sums
         b.dbias_ready = l < L - 1 ? on_mfma(l + 1) : mse_in_update;
         b.dx_colsum = (on_mfma(l) && l > 0) ? dbias_of(l - 1) : nullptr;
+        if (deferred) { dY = w.delta_of[(size_t)l]; dX = l > 0 ? w.delta_of[(size_t)l - 1] : nullptr; b.defer = &defer_list; }
         b.delta_ready = dY; b.X = inputs[l];
         b.dx_S_bits = l > 0 && w.relu_bits[(size_t)l - 1] != nullptr;
         b.dx_S = l > 0 ? (b.dx_S_bits ? w.relu_bits[(size_t)l - 1] : g.act == PH_ACT_GELU ? w.A[l - 1] : w.Y[l - 1]) : nullptr;
@@ -1398,6 +1285,7 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
         if (a.taps && a.taps->delta && l > 0) PH_TRY(tap_copy<T>(a.taps->delta[l - 1], dX, (int64_t)g.groups * B * si, st));
         if (have_pending && !sgd_rode) PH_TRY(launch_sgd(pending, 4, pending_largest, pending_elems));
         have_pending = false;
+        if (deferred) continue;
 
         if (a.mode == PH_STEP_NO_UPDATE) {
             if (loss_tail.partial) {                   // no kernel of this layer's backward could carry the rider
@@ -1441,6 +1329,51 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
             }
         }
         void *t = dY; dY = dX; dX = t;
+    }
+    if (deferred) {
+        const bool update = a.mode != PH_STEP_NO_UPDATE;
+        std::vector<Product> later;
+        std::vector<int> splits;
+        std::vector<SgdInPlace> inside;
+        // the compressor gradients first (few tiles with half of their rows empty; one rank's cut into pieces): the
+        // weight gradients' tiles then fill the compute units as those come free
+        for (int pass = 0; pass < 2; ++pass)
+            for (int i = 0; i < L; ++i) {
+                const int l = L - 1 - i;           // the order in which the layers' backward passes ran
+                const Product &pr = pass ? defer_list.dw[(size_t)i] : defer_list.dc[(size_t)i];
+                if (pr.M <= 0 || pr.N <= 0) continue;
+                SgdInPlace in{};
+                if (update && pass) in = SgdInPlace{a.Lw_master[l], q ? a.Dw_master[l] : nullptr, (__bf16 *)a.Lw[l], q ? (__bf16 *)a.Dw[l] : nullptr, a.lr, (a.dLw || a.dDw) ? 1 : 0};
+                if (update && !pass) in = SgdInPlace{a.Cw_master[l], nullptr, (__bf16 *)a.Cw[l], nullptr, a.lr, a.dCw ? 1 : 0};
+                later.push_back(pr);
+                splits.push_back(pass ? 1 : compressor_gradient_pieces(geos[(size_t)l]));
+                inside.push_back(in);
+            }
+        PH_TRY(launch_product_table(later, splits, inside, w.table, w.parts, w.arrived, st,
+                                    update ? "weight + compressor gradients of all layers + SGD" : "weight + compressor gradients of all layers",
+                                    defer_list.dw[0], defer_list.dc[0], L));
+        if (update) {
+            // what is left of the update: the biases, four tensors per launch; the first launch finishes the loss if
+            // no kernel before has
+            for (int l0 = 0; l0 < L; l0 += 4) {
+                SgdBatch batch{};
+                int tensors = 0;
+                int64_t largest = 0, total = 0;
+                for (int l = l0; l < std::min(L, l0 + 4); ++l) {
+                    const int64_t count = geos[(size_t)l].so;
+                    batch.t[tensors++] = SgdTensor{a.bias[l], a.bias_master[l], dbias_of(l), count};
+                    largest = std::max(largest, count);
+                    total += count;
+                }
+                if (loss_tail.partial) { batch.tail = loss_tail; loss_tail.partial = nullptr; }
+                PH_TRY(launch_sgd(batch, tensors, largest, total));
+            }
+        } else if (loss_tail.partial) {                // no kernel of the backward pass could carry the rider
+            ProfScope prof("loss", 0, loss_tail.n, 0, 1, st);
+            hipLaunchKernelGGL(loss_kernel, dim3(1), dim3(256), 0, st, loss_tail);
+            PH_TRY(check_launch("loss"));
+            loss_tail.partial = nullptr;
+        }
     }
     return PH_OK;
 }
