@@ -683,25 +683,7 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
             else aux_v[i].h = *(const BfV *)((const __bf16 *)ep.aux + aux_at);
         }
     }
-    // the master weights of an update inside this epilogue (SgdInPlace), likewise ahead of the loop
-    constexpr bool SGD_INSIDE = EPI == EPI_STORE && sizeof(TOut) == 4 && VEC == 8;
-    constexpr int SGD_PASSES = SGD_INSIDE ? PASSES : 1;
-    FlV master_v[SGD_PASSES];
-    if constexpr (SGD_INSIDE) {
-        if (P.sgd.master0) {                           // uniform
-            const int n = n0 + (thread % PER_ROW) * VEC;
-            const Loc ln = locate(P.o.c, min(n, P.N - 1), skip_o);
-            const int region = ln.region > 0 ? 1 : 0;
-            const float *base = (region ? P.sgd.master1 + g * P.o.g1 + ln.off1 : P.sgd.master0 + g * P.o.g0 + ln.off0);
-#pragma unroll
-            for (int i = 0; i < SGD_PASSES; ++i) {
-                const int m = m0 + (thread + i * THREADS) / PER_ROW;
-                if (m >= P.M || n >= P.N) continue;
-                master_v[i] = *(const FlV *)(base + (int64_t)m * (region ? P.o.r.mult1 : P.o.r.mult0));
-            }
-        }
-    }
-    constexpr int EPI_UNROLL = (EPI == EPI_DACT || SGD_INSIDE) ? PASSES : 2;     // unrolled: the prefetched vectors stay in registers
+    constexpr int EPI_UNROLL = EPI == EPI_DACT ? PASSES : 2;     // EPI_DACT: unrolled, the prefetched vectors stay in registers
 #pragma unroll EPI_UNROLL
     for (int i = 0; i < PASSES; ++i) {
         const int v = thread + i * THREADS;
@@ -806,7 +788,7 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
                 const int64_t at = dst - (region ? o1 : o0);
                 float *master = (region ? P.sgd.master1 : P.sgd.master0) + g * (region ? P.o.g1 : P.o.g0) + at;
                 __bf16 *w = (region ? P.sgd.w1 : P.sgd.w0) + g * (region ? P.o.g1 : P.o.g0) + at;
-                const FlV before = master_v[SGD_INSIDE ? i : 0];
+                const FlV before = *(const FlV *)master;     // (requested ahead of the loop like sigma', the launch got 4 % slower)
                 FlV after;
                 BfV rounded;
 #pragma unroll
@@ -1442,6 +1424,7 @@ struct ProductTable {
     int count;
     int first_wg[TABLE_PRODUCTS + 1];
     int wgs[TABLE_PRODUCTS];               // = p[j].total_wg
+    int dual[TABLE_PRODUCTS];              // product j in two-tile workgroups (DUAL of mfma_workgroup)
     MfmaParams p[TABLE_PRODUCTS];
 };
 
@@ -1450,6 +1433,7 @@ struct TableChunk {
     int count;                             // the table's count once every chunk is there
     int first_wg[CHUNK_PRODUCTS + 1];      // first_wg[at .. at + n]
     int wgs[CHUNK_PRODUCTS];
+    int dual[CHUNK_PRODUCTS];
     MfmaParams p[CHUNK_PRODUCTS];
 };
 static_assert(sizeof(TableChunk) + sizeof(void *) <= 3840, "a chunk travels as kernel arguments (4 KB with the hidden ones)");
@@ -1465,7 +1449,7 @@ __global__ __launch_bounds__(256) void table_upload_kernel(TableChunk c, Product
     for (int i = (int)threadIdx.x; i < words; i += 256) out[i] = in[i];
 #endif
     if ((int)threadIdx.x <= c.n) table->first_wg[c.at + threadIdx.x] = c.first_wg[threadIdx.x];
-    if ((int)threadIdx.x < c.n) table->wgs[c.at + threadIdx.x] = c.wgs[threadIdx.x];
+    if ((int)threadIdx.x < c.n) { table->wgs[c.at + threadIdx.x] = c.wgs[threadIdx.x]; table->dual[c.at + threadIdx.x] = c.dual[threadIdx.x]; }
     if (threadIdx.x == 0) table->count = c.count;
 }
 
@@ -1490,7 +1474,8 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_table_kernel(const ProductTa
     const ArgWords in = (ArgWords)&t->p[j];
 #pragma unroll
     for (int i = 0; i < WORDS; ++i) blk.w[i] = in[i];
-    mfma_workgroup<LD_KM, LD_KM, VEC, VEC, float, false, false, EPI_STORE>(blk.p, xcd_order(local, 0, wgs));
+    if (t->dual[j]) mfma_workgroup<LD_KM, LD_KM, VEC, VEC, float, false, true, EPI_STORE>(blk.p, xcd_order(local, 0, wgs));
+    else mfma_workgroup<LD_KM, LD_KM, VEC, VEC, float, false, false, EPI_STORE>(blk.p, xcd_order(local, 0, wgs));
 #endif
 }
 

@@ -578,12 +578,18 @@ ph_status launch_product_table(const std::vector<Product> &prods, const std::vec
     for (size_t begin = 0; begin < prods.size(); begin += TABLE_PRODUCTS) {
         const size_t end = std::min(prods.size(), begin + TABLE_PRODUCTS);
         std::vector<MfmaParams> blocks;
-        std::vector<int> first;
+        std::vector<int> first, duals;
+        int64_t all_tiles = 0;
+        for (size_t j = begin; j < end; ++j) all_tiles += tiles_of(prods[j].M, prods[j].N);
+        const bool many_tiles = all_tiles > 256;
         int next = 0;
         for (size_t j = begin; j < end; ++j) {
             const Product &pr = prods[j];
             if (tiles_of(pr.M, pr.N) * 8 > 0x7fffffff) return fail(PH_ERR_LAUNCH, "%s: internal error, too many tiles (make_geo admits none such)", what);
-            MfmaParams P = mfma_params(pr, 1, splits[j], false);
+            // with more than 256 tiles in the launch, the uncut products run in two-tile workgroups like a launch of their own
+            const bool dual = splits[j] == 1 && many_tiles;
+            MfmaParams P = mfma_params(pr, 1, splits[j], dual);
+            duals.push_back(dual ? 1 : 0);
             const int64_t tiles = tiles_of(pr.M, pr.N);
             if (P.ksplit > 1) {
                 P.parts = parts + slot * MT * MT; P.arrived = arrived + word;
@@ -599,7 +605,7 @@ ph_status launch_product_table(const std::vector<Product> &prods, const std::vec
         for (int at = 0; at < count; at += CHUNK_PRODUCTS) {
             TableChunk c{};
             c.at = at; c.n = std::min(CHUNK_PRODUCTS, count - at); c.count = count;
-            for (int i = 0; i < c.n; ++i) { c.p[i] = blocks[(size_t)(at + i)]; c.wgs[i] = blocks[(size_t)(at + i)].total_wg; }
+            for (int i = 0; i < c.n; ++i) { c.p[i] = blocks[(size_t)(at + i)]; c.wgs[i] = blocks[(size_t)(at + i)].total_wg; c.dual[i] = duals[(size_t)(at + i)]; }
             for (int i = 0; i <= c.n; ++i) c.first_wg[i] = first[(size_t)(at + i)];
             hipLaunchKernelGGL(table_upload_kernel, dim3(1), dim3(256), 0, st, c, table);
             PH_TRY(check_launch("parameter table"));
