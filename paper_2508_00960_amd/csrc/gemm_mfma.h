@@ -335,6 +335,9 @@ struct SgdInPlace {
     __bf16 *w0, *w1;             // bf16 compute copies: w = bf16(master)
     float lr;
     int keep_grad;               // also store the gradient (the caller wants to see it)
+    float *bias_master;          // weight gradients only: the layer's bias [M], its bf16 copy and its finished gradient
+    __bf16 *bias_w;              //   (Eq. (bpb): column sums of delta, left by earlier launches); the tiles of the
+    const float *bias_grad;      //   first tile column update the rows they cover.  NULL: none
 };
 
 struct MfmaParams {
@@ -827,6 +830,14 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
         } else {
 #pragma unroll
             for (int u = 0; u < VEC; ++u) csum[u] += (float)o[u];
+        }
+    }
+    if constexpr (EPI == EPI_STORE && sizeof(TOut) == 4 && VEC == 8) {
+        if (P.sgd.bias_master && n0 == 0 && thread < MT && m0 + thread < P.M) {
+            const int64_t at = g * (int64_t)P.M + m0 + thread;
+            const float nb = P.sgd.bias_master[at] - P.sgd.lr * P.sgd.bias_grad[at];
+            P.sgd.bias_master[at] = nb;
+            P.sgd.bias_w[at] = (__bf16)nb;
         }
     }
     if (EPI == EPI_BIAS_ACT && sizeof(TOut) == 2 && ep.mode == EPI_BIAS_ACT && ep.mse_target) {          // uniform
@@ -1425,6 +1436,7 @@ struct ProductTable {
     int first_wg[TABLE_PRODUCTS + 1];
     int wgs[TABLE_PRODUCTS];               // = p[j].total_wg
     int dual[TABLE_PRODUCTS];              // product j in two-tile workgroups (DUAL of mfma_workgroup)
+    LossTail tail;                         // workgroup 0 finishes the loss first (partial == NULL: nothing to do)
     MfmaParams p[TABLE_PRODUCTS];
 };
 
@@ -1434,6 +1446,9 @@ struct TableChunk {
     int first_wg[CHUNK_PRODUCTS + 1];      // first_wg[at .. at + n]
     int wgs[CHUNK_PRODUCTS];
     int dual[CHUNK_PRODUCTS];
+    LossTail tail;
+    float *clear_at;                       // the upload also clears clear_count floats there (the step's buffers that
+    int clear_count;                       //   are added into: one launch less)
     MfmaParams p[CHUNK_PRODUCTS];
 };
 static_assert(sizeof(TableChunk) + sizeof(void *) <= 3840, "a chunk travels as kernel arguments (4 KB with the hidden ones)");
@@ -1450,7 +1465,8 @@ __global__ __launch_bounds__(256) void table_upload_kernel(TableChunk c, Product
 #endif
     if ((int)threadIdx.x <= c.n) table->first_wg[c.at + threadIdx.x] = c.first_wg[threadIdx.x];
     if ((int)threadIdx.x < c.n) { table->wgs[c.at + threadIdx.x] = c.wgs[threadIdx.x]; table->dual[c.at + threadIdx.x] = c.dual[threadIdx.x]; }
-    if (threadIdx.x == 0) table->count = c.count;
+    if (threadIdx.x == 0) { table->count = c.count; table->tail = c.tail; }
+    for (int i = (int)threadIdx.x; i < c.clear_count; i += 256) c.clear_at[i] = 0.f;
 }
 
 template <int VEC>
@@ -1462,6 +1478,13 @@ __global__ __launch_bounds__(512, 1) void gemm_mfma_table_kernel(const ProductTa
     typedef const ProductTable __attribute__((address_space(4))) *TablePtr;
     const TablePtr t = (TablePtr)(uintptr_t)table;
     const int id = (int)blockIdx.x;
+    if (id == 0 && t->tail.partial) {                           // uniform
+        extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+        LossTail tail;
+        tail.partial = t->tail.partial; tail.n = t->tail.n; tail.scale = t->tail.scale; tail.loss = t->tail.loss;
+        finish_loss(tail, (float *)smem_raw);
+        __syncthreads();
+    }
     const int count = t->count;
     int j = 0;
     while (j + 1 < count && id >= t->first_wg[j + 1]) ++j;      // uniform

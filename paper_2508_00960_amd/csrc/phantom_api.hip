@@ -272,7 +272,7 @@ inline int64_t tiles_of(int64_t M, int64_t N) { return ((M + MT - 1) / MT) * ((N
 // idle, and putting them off made configuration 2 slower, 0.272 against 0.260 ms; a single layer has nothing to gain.)
 bool deferred_weight_gradients(const std::vector<Geo> &geos)
 {
-    if (geos.size() < 2) return false;
+    if (geos.size() < 2 || 2 * geos.size() > (size_t)TABLE_PRODUCTS) return false;
     for (const Geo &g : geos)
         if (g.all || g.dtype != PH_BF16 || g.vec != 8 || tiles_of(g.so, g.Kc) > 256) return false;
     return true;
@@ -558,13 +558,63 @@ ph_status launch_tail(const Product *head, const Product &tail0, const Product &
     }
 }
 
-// The weight-gradient-layout products `prods` (float out, 8-element vectors, one group each) in one launch through a
-// parameter table in device memory: see gemm_mfma_table_kernel.  splits[j] > 1 cuts product j's reduction into
-// pieces (parts, arrived: room for all of them, see MfmaParams); sgd[j].master0 != NULL puts the SGD update into
-// product j's epilogue.  More than TABLE_PRODUCTS products go out in several launches.
-ph_status launch_product_table(const std::vector<Product> &prods, const std::vector<int> &splits, const std::vector<SgdInPlace> &sgd,
-                               ProductTable *table, float *parts, unsigned *arrived, hipStream_t st, const char *what,
-                               const Product &prof_a, const Product &prof_b, int prof_groups)
+// The weight-gradient-layout products `prods` (float out, 8-element vectors, one group each; at most TABLE_PRODUCTS)
+// in one launch through a parameter table in device memory: see gemm_mfma_table_kernel.  upload_product_table
+// fills the table (small launches, any time before); launch_product_table runs the products.
+// splits[j] > 1 cuts product j's reduction into pieces (parts, arrived: room for all of them, see MfmaParams);
+// sgd[j].master0 != NULL puts the SGD update into product j's epilogue.  tail: the launch's first workgroup finishes
+// the loss.  clear_at, clear_count: floats that the first upload launch clears on its way.  *grid: the launch's size.
+ph_status upload_product_table(const std::vector<Product> &prods, const std::vector<int> &splits, const std::vector<SgdInPlace> &sgd,
+                               ProductTable *table, float *parts, unsigned *arrived, const LossTail &tail, float *clear_at,
+                               int64_t clear_count, hipStream_t st, int *grid)
+{
+    const char *what = "parameter table";
+    if (prods.size() > (size_t)TABLE_PRODUCTS) return fail(PH_ERR_LAUNCH, "%s: internal error, more products than the table holds", what);
+    size_t slot = 0, word = 0;
+    std::vector<MfmaParams> blocks;
+    std::vector<int> first, duals;
+    int64_t all_tiles = 0;
+    for (const Product &pr : prods) all_tiles += tiles_of(pr.M, pr.N);
+    const bool many_tiles = all_tiles > 256;
+    int next = 0;
+    for (size_t j = 0; j < prods.size(); ++j) {
+        const Product &pr = prods[j];
+        if (tiles_of(pr.M, pr.N) * 8 > 0x7fffffff) return fail(PH_ERR_LAUNCH, "%s: internal error, too many tiles (make_geo admits none such)", what);
+        // with more than 256 tiles in the launch, the uncut products run in two-tile workgroups like a launch of their own
+        const bool dual = splits[j] == 1 && many_tiles;
+        MfmaParams P = mfma_params(pr, 1, splits[j], dual);
+        duals.push_back(dual ? 1 : 0);
+        const int64_t tiles = tiles_of(pr.M, pr.N);
+        if (P.ksplit > 1) {
+            P.parts = parts + slot * MT * MT; P.arrived = arrived + word;
+            slot += (size_t)tiles * splits[j]; word += (size_t)tiles;
+        }
+        P.sgd = sgd[j];
+        first.push_back(next);
+        next += (P.total_wg + 7) & ~7;
+        blocks.push_back(P);
+    }
+    first.push_back(next);
+    if (word > (size_t)PIECE_WORDS) return fail(PH_ERR_LAUNCH, "%s: internal error, more cut tiles than words to count them", what);
+    const int count = (int)blocks.size();
+    for (int at = 0; at < count; at += CHUNK_PRODUCTS) {
+        TableChunk c{};
+        c.at = at; c.n = std::min(CHUNK_PRODUCTS, count - at); c.count = count; c.tail = tail;
+        if (at == 0) { c.clear_at = clear_at; c.clear_count = (int)clear_count; }
+        for (int i = 0; i < c.n; ++i) { c.p[i] = blocks[(size_t)(at + i)]; c.wgs[i] = blocks[(size_t)(at + i)].total_wg; c.dual[i] = duals[(size_t)(at + i)]; }
+        for (int i = 0; i <= c.n; ++i) c.first_wg[i] = first[(size_t)(at + i)];
+        ProfScope prof(what, 0, (int64_t)c.n * (int64_t)(sizeof(MfmaParams) / 4) + c.clear_count, 0, 1, st);
+        hipLaunchKernelGGL(table_upload_kernel, dim3(1), dim3(256), 0, st, c, table);
+        PH_TRY(check_launch(what));
+    }
+    *grid = next;
+    return PH_OK;
+}
+
+// prof_a, prof_b, prof_groups: the profile entry's two shapes and how many products of each the table holds (exact
+// when all layers have the same shapes)
+ph_status launch_product_table(const ProductTable *table, int grid, hipStream_t st, const char *what, const Product &prof_a,
+                               const Product &prof_b, int prof_groups)
 {
     auto kern = gemm_mfma_table_kernel<8>;
     static thread_local bool configured = false;
@@ -574,48 +624,9 @@ ph_status launch_product_table(const std::vector<Product> &prods, const std::vec
                                          hipGetErrorString(e));
         configured = true;
     }
-    size_t slot = 0, word = 0;
-    for (size_t begin = 0; begin < prods.size(); begin += TABLE_PRODUCTS) {
-        const size_t end = std::min(prods.size(), begin + TABLE_PRODUCTS);
-        std::vector<MfmaParams> blocks;
-        std::vector<int> first, duals;
-        int64_t all_tiles = 0;
-        for (size_t j = begin; j < end; ++j) all_tiles += tiles_of(prods[j].M, prods[j].N);
-        const bool many_tiles = all_tiles > 256;
-        int next = 0;
-        for (size_t j = begin; j < end; ++j) {
-            const Product &pr = prods[j];
-            if (tiles_of(pr.M, pr.N) * 8 > 0x7fffffff) return fail(PH_ERR_LAUNCH, "%s: internal error, too many tiles (make_geo admits none such)", what);
-            // with more than 256 tiles in the launch, the uncut products run in two-tile workgroups like a launch of their own
-            const bool dual = splits[j] == 1 && many_tiles;
-            MfmaParams P = mfma_params(pr, 1, splits[j], dual);
-            duals.push_back(dual ? 1 : 0);
-            const int64_t tiles = tiles_of(pr.M, pr.N);
-            if (P.ksplit > 1) {
-                P.parts = parts + slot * MT * MT; P.arrived = arrived + word;
-                slot += (size_t)tiles * splits[j]; word += (size_t)tiles;
-            }
-            P.sgd = sgd[j];
-            first.push_back(next);
-            next += (P.total_wg + 7) & ~7;
-            blocks.push_back(P);
-        }
-        first.push_back(next);
-        const int count = (int)blocks.size();
-        for (int at = 0; at < count; at += CHUNK_PRODUCTS) {
-            TableChunk c{};
-            c.at = at; c.n = std::min(CHUNK_PRODUCTS, count - at); c.count = count;
-            for (int i = 0; i < c.n; ++i) { c.p[i] = blocks[(size_t)(at + i)]; c.wgs[i] = blocks[(size_t)(at + i)].total_wg; c.dual[i] = duals[(size_t)(at + i)]; }
-            for (int i = 0; i <= c.n; ++i) c.first_wg[i] = first[(size_t)(at + i)];
-            hipLaunchKernelGGL(table_upload_kernel, dim3(1), dim3(256), 0, st, c, table);
-            PH_TRY(check_launch("parameter table"));
-        }
-        // the profile entry: the caller's two shapes, prof_groups of each (exact when all layers have the same shapes)
-        ProfScope prof(what, prof_a.M, prof_a.N, prof_a.K, prof_groups, st, prof_b.M, prof_b.N, prof_b.K);
-        hipLaunchKernelGGL(kern, dim3((unsigned)next), dim3(MFMA_THREADS), MFMA_LDS_BYTES, st, (const ProductTable *)table);
-        PH_TRY(check_launch(what));
-    }
-    return PH_OK;
+    ProfScope prof(what, prof_a.M, prof_a.N, prof_a.K, prof_groups, st, prof_b.M, prof_b.N, prof_b.K);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(MFMA_THREADS), MFMA_LDS_BYTES, st, table);
+    return check_launch(what);
 }
 
 // One rank's thin compression and layer update in one launch: see MfmaFwdBatch.
@@ -861,12 +872,8 @@ struct BwdArgs {
                                //   the loss as a rider and clears loss_tail->partial; left alone if there is none
     void *tap_dG_send;         // step only, optional: copies of this layer's dG_send / (all ranks) dg_own, taken right
     void *tap_dg_own;          //   after the launch that finishes each
-    struct DeferredProducts *defer;   // step only: the weight + compressor gradients are not launched but added to this list
-};
-
-// weight and compressor gradient products of the layers whose backward pass has run, in that order (see BwdArgs::defer)
-struct DeferredProducts {
-    std::vector<Product> dw, dc;
+    bool defer;                // step only: the weight + compressor gradients are not launched here (the step runs all
+                               //   layers' in one launch at the end of the backward pass)
 };
 
 // copy of a tensor for a tap of the step (count elements of the storage type)
@@ -1042,11 +1049,7 @@ ph_status bwd_impl(const Geo &g, const BwdArgs &b, const BwdWs &w, hipStream_t s
     Product grads[2] = {dw, dc};
     if (b.below_done) *b.below_done = false;
     if (b.ride_sgd_done) *b.ride_sgd_done = false;
-    if (b.defer) {                 // the step launches them with the other layers' at the end of the backward pass
-        b.defer->dw.push_back(dw);
-        b.defer->dc.push_back(dc);
-        return PH_OK;
-    }
+    if (b.defer) return PH_OK;
     if constexpr (std::is_same<T, bf16_t>::value) {
         if (riders) {
             // The layer below starts its backward with an error compression that fills half of the device or less
@@ -1176,17 +1179,59 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
     const int64_t out_tiles = tiles_of(B, g.so) * g.groups;
     const bool mse_in_update = train && on_mfma(L - 1) && out_tiles <= MSE_BLOCKS;
     const bool clear_in_compression = mse_in_update && thin_launch_before_update(g);
-    if (mse_in_update && !clear_in_compression && clear_count > 0) {
+    // (one rank with deferred weight gradients keeps every layer's delta: the last layer's goes to its own buffer)
+    bool deferred = false;
+    if constexpr (std::is_same<T, bf16_t>::value) deferred = mse_in_update && w.table && deferred_weight_gradients(geos);
+    if (mse_in_update && !clear_in_compression && !deferred && clear_count > 0) {
         ProfScope prof("clear bias gradients", 0, clear_count, 0, 1, st);
         hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks_for(clear_count)), dim3(256), 0, st, clear_at, clear_count);
         PH_TRY(check_launch("clear bias gradients"));
     }
-    // (one rank with deferred weight gradients keeps every layer's delta: the last layer's goes to its own buffer)
-    bool deferred = false;
-    if constexpr (std::is_same<T, bf16_t>::value) deferred = mse_in_update && w.table && deferred_weight_gradients(geos);
     void *delta_top = deferred ? w.delta_of[(size_t)L - 1] : w.dYa;
     OutputError oe{a.T, delta_top, w.mse_partial, 1.0f / (float)B, dbias_of(L - 1), clear_in_compression ? clear_at : nullptr,
                    clear_in_compression ? clear_count : 0};
+
+    // Deferred weight gradients: the products of all layers are known from the buffers alone.  Their parameter table
+    // goes up now, ahead of the forward pass (the first of those small launches also clears what the step adds
+    // into), and the launch itself comes at the end of the backward pass: the compressor gradients first (few
+    // tiles with half of their rows empty, cut into pieces), then the weight gradients' tiles, which fill the compute
+    // units as those come free; the SGD update of L, C, D and the bias in the epilogues, the loss by the first workgroup.
+    int table_grid = 0;
+    Product table_dw{}, table_dc{};
+    if (deferred) {
+        const bool update = a.mode != PH_STEP_NO_UPDATE;
+        std::vector<Product> later;
+        std::vector<int> splits;
+        std::vector<SgdInPlace> inside;
+        for (int pass = 0; pass < 2; ++pass)
+            for (int l = L - 1; l >= 0; --l) {
+                const Geo &gl = geos[(size_t)l];
+                BwdArgs b{};
+                b.X = l > 0 ? w.Y[l - 1] : a.X0;
+                b.G = q ? a.G[l] : nullptr;
+                b.dg_own = q ? const_cast<void *>(a.dg_own[l]) : nullptr;
+                // (gradients that the caller does not want: a training step has the update in the epilogues and stores
+                // none; a step without update stores every layer's in the same place, where nobody reads them)
+                b.dLw = a.dLw ? a.dLw[l] : w.dLw[0];
+                b.dCw = q ? (a.dCw ? a.dCw[l] : w.dCw[0]) : nullptr;
+                b.dDw = q ? (a.dDw ? a.dDw[l] : w.dDw[0]) : nullptr;
+                const BwdProducts all = make_bwd_products(gl, b, w.delta_of[(size_t)l]);
+                const Product &pr = pass ? all.dw : all.dc;
+                if (l == L - 1) (pass ? table_dw : table_dc) = pr;
+                if (pr.M <= 0 || pr.N <= 0) continue;
+                SgdInPlace in{};
+                if (update && pass)
+                    in = SgdInPlace{a.Lw_master[l], q ? a.Dw_master[l] : nullptr, (__bf16 *)a.Lw[l], q ? (__bf16 *)a.Dw[l] : nullptr, a.lr,
+                                    (a.dLw || a.dDw) ? 1 : 0, a.bias_master[l], (__bf16 *)a.bias[l], dbias_of(l)};
+                if (update && !pass)
+                    in = SgdInPlace{a.Cw_master[l], nullptr, (__bf16 *)a.Cw[l], nullptr, a.lr, a.dCw ? 1 : 0, nullptr, nullptr, nullptr};
+                later.push_back(pr);
+                splits.push_back(pass ? 1 : compressor_gradient_pieces(gl));
+                inside.push_back(in);
+            }
+        const LossTail tail{w.mse_partial, (int)out_tiles, 0.5f / (float)B, a.loss};
+        PH_TRY(upload_product_table(later, splits, inside, w.table, w.parts, w.arrived, tail, clear_at, clear_count, st, &table_grid));
+    }
 
     // forward through every layer; y_l stays in the storage type between layers
     const void *in = a.X0;
@@ -1246,10 +1291,6 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
         hipLaunchKernelGGL((sgd_kernel<T>), dim3(blocks_for(largest, 256, 2048), (unsigned)tensors), dim3(256), 0, st, batch, a.lr);
         return check_launch("SGD update");
     };
-    // Deferred weight gradients (deferred_weight_gradients): every layer's delta stays in a buffer of its own, the
-    // layers' backward launches stop after the input gradient, and the weight + compressor gradients of all layers
-    // go out in one launch at the end, the SGD update of L, C and D in its epilogues; then the biases and the loss.
-    DeferredProducts defer_list;
     for (int l = L - 1; l >= 0; --l) {
         BwdArgs b{};
         b.send_done = send_done;
@@ -1261,7 +1302,7 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
         // the layer's bias gradient is there already if the product that wrote its delta took the column sums
         b.dbias_ready = l < L - 1 ? on_mfma(l + 1) : mse_in_update;
         b.dx_colsum = (on_mfma(l) && l > 0) ? dbias_of(l - 1) : nullptr;
-        if (deferred) { dY = w.delta_of[(size_t)l]; dX = l > 0 ? w.delta_of[(size_t)l - 1] : nullptr; b.defer = &defer_list; }
+        if (deferred) { dY = w.delta_of[(size_t)l]; dX = l > 0 ? w.delta_of[(size_t)l - 1] : nullptr; b.defer = true; b.loss_tail = nullptr; }
         b.delta_ready = dY; b.X = inputs[l];
         b.dx_S_bits = l > 0 && w.relu_bits[(size_t)l - 1] != nullptr;
         b.dx_S = l > 0 ? (b.dx_S_bits ? w.relu_bits[(size_t)l - 1] : g.act == PH_ACT_GELU ? w.A[l - 1] : w.Y[l - 1]) : nullptr;
@@ -1336,51 +1377,11 @@ ph_status step_impl(const std::vector<Geo> &geos, const ph_step_args &a, const S
         }
         void *t = dY; dY = dX; dX = t;
     }
-    if (deferred) {
-        const bool update = a.mode != PH_STEP_NO_UPDATE;
-        std::vector<Product> later;
-        std::vector<int> splits;
-        std::vector<SgdInPlace> inside;
-        // the compressor gradients first (few tiles with half of their rows empty; one rank's cut into pieces): the
-        // weight gradients' tiles then fill the compute units as those come free
-        for (int pass = 0; pass < 2; ++pass)
-            for (int i = 0; i < L; ++i) {
-                const int l = L - 1 - i;           // the order in which the layers' backward passes ran
-                const Product &pr = pass ? defer_list.dw[(size_t)i] : defer_list.dc[(size_t)i];
-                if (pr.M <= 0 || pr.N <= 0) continue;
-                SgdInPlace in{};
-                if (update && pass) in = SgdInPlace{a.Lw_master[l], q ? a.Dw_master[l] : nullptr, (__bf16 *)a.Lw[l], q ? (__bf16 *)a.Dw[l] : nullptr, a.lr, (a.dLw || a.dDw) ? 1 : 0};
-                if (update && !pass) in = SgdInPlace{a.Cw_master[l], nullptr, (__bf16 *)a.Cw[l], nullptr, a.lr, a.dCw ? 1 : 0};
-                later.push_back(pr);
-                splits.push_back(pass ? 1 : compressor_gradient_pieces(geos[(size_t)l]));
-                inside.push_back(in);
-            }
-        PH_TRY(launch_product_table(later, splits, inside, w.table, w.parts, w.arrived, st,
-                                    update ? "weight + compressor gradients of all layers + SGD" : "weight + compressor gradients of all layers",
-                                    defer_list.dw[0], defer_list.dc[0], L));
-        if (update) {
-            // what is left of the update: the biases, four tensors per launch; the first launch finishes the loss if
-            // no kernel before has
-            for (int l0 = 0; l0 < L; l0 += 4) {
-                SgdBatch batch{};
-                int tensors = 0;
-                int64_t largest = 0, total = 0;
-                for (int l = l0; l < std::min(L, l0 + 4); ++l) {
-                    const int64_t count = geos[(size_t)l].so;
-                    batch.t[tensors++] = SgdTensor{a.bias[l], a.bias_master[l], dbias_of(l), count};
-                    largest = std::max(largest, count);
-                    total += count;
-                }
-                if (loss_tail.partial) { batch.tail = loss_tail; loss_tail.partial = nullptr; }
-                PH_TRY(launch_sgd(batch, tensors, largest, total));
-            }
-        } else if (loss_tail.partial) {                // no kernel of the backward pass could carry the rider
-            ProfScope prof("loss", 0, loss_tail.n, 0, 1, st);
-            hipLaunchKernelGGL(loss_kernel, dim3(1), dim3(256), 0, st, loss_tail);
-            PH_TRY(check_launch("loss"));
-            loss_tail.partial = nullptr;
-        }
-    }
+    if (deferred)
+        PH_TRY(launch_product_table(w.table, table_grid, st,
+                                    a.mode != PH_STEP_NO_UPDATE ? "weight + compressor gradients of all layers + SGD | loss"
+                                                                : "weight + compressor gradients of all layers | loss",
+                                    table_dw, table_dc, L));
     return PH_OK;
 }
 
