@@ -27,6 +27,8 @@ FAMILIES = [
     # (substrings of the kernel's name, demangled or not, family, prefixes of the bench names it can carry)
     (("gemm_mfma_fwd_kernel",), "fwd", ("layer update + thin compression",)),
     (("gemm_mfma_tail_kernel",), "tail", ("weight + compressor gradients |",)),
+    (("gemm_mfma_table_kernel",), "table", ("weight + compressor gradients of all layers",)),
+    (("table_upload_kernel",), "upload", ("parameter table",)),
     (("gemm_mfma_kernel<0, 0", "gemm_mfma_kernelILi0ELi0E"), "kc_kc", ("layer update", "compression")),
     (("gemm_mfma_kernel<0, 1", "gemm_mfma_kernelILi0ELi1E"), "kc_km", ("input gradient", "error compression")),
     (("gemm_mfma_kernel<1, 1", "gemm_mfma_kernelILi1ELi1E"), "km_km", ("weight + compressor gradients", "weight gradients", "compressor gradient")),
@@ -86,6 +88,16 @@ def expected_workgroups(row):
     return single, {single, dual, thin, first_dual, -(-row.get("M", 0) // 128) * -(-row.get("N", 0) // 128) * row["groups"]}
 
 
+def carries_pair(kernel_name):
+    """Is this an instance of gemm_mfma_kernel built for two products in one launch (template argument PAIR)?"""
+    import re
+    m = re.search(r"gemm_mfma_kernel<([^>]*)>", short(kernel_name))
+    if not m:
+        return None
+    args = [a.strip() for a in m.group(1).split(",")]
+    return len(args) >= 7 and args[6] in ("1", "true")
+
+
 def match_rows(groups, rows):
     """groups: {(kernel name, workgroups): calls}; rows: bench.py's kernel table.  Returns {(kernel, wgs): row}."""
     out = {}
@@ -104,6 +116,9 @@ def match_rows(groups, rows):
         left = []
         for key, calls in items:            # first the launches whose workgroup count is exactly what a row's shapes give
             hit = [r for r in cand if id(r) not in used and key[1] in expected_workgroups(r)[1]]
+            pair = carries_pair(key[0])
+            if pair is not None and any(("M2" in r) == pair for r in hit):     # a launch of two products has a second shape
+                hit = [r for r in hit if ("M2" in r) == pair]
             if len(hit) >= 1:
                 hit.sort(key=lambda r: abs(expected_workgroups(r)[0] - key[1]))
                 out[key] = hit[0]
