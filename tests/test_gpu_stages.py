@@ -47,9 +47,11 @@ def test_config5_forward_every_layer_full_size(k):
     (1024, 8, 16, 136, 3, "relu", "bf16", -1, "train"),        # ReLU, several bf16 layers, all ranks (sum-on-read reduce-scatter)
     (2048, 16, 32, 200, 4, "relu", "bf16", 0, "train"),        # ReLU, one rank
     (2048, 16, 8, 2100, 2, "relu", "bf16", -1, "train"),       # 272 output tiles: two-tile workgroups with the output error in the update
-    (4096, 16, 16, 4300, 2, "gelu", "bf16", 0, "train"),       # one rank, 34 x 2 tiles and a ragged batch; weight gradients cut in four along the batch
-    (2048, 8, 32, 2050, 3, "relu", "bf16", 0, "train"),        # ... cut in two, the second piece ragged
-    (1024, 4, 64, 3072, 2, "gelu", "bf16", 0, "no_update"),    # ... cut in three
+    (4096, 16, 16, 4300, 2, "gelu", "bf16", 0, "train"),       # one rank, 34 x 2 tiles and a ragged batch; compressor gradients cut in four along the batch
+    (2048, 8, 32, 2050, 3, "relu", "bf16", 0, "train"),        # one rank: all layers' weight gradients in one launch, compressor gradients cut in two
+    (1024, 4, 64, 3072, 2, "gelu", "bf16", 0, "no_update"),    # ... cut in three, no update
+    (512, 4, 8, 40, 17, "relu", "bf16", 0, "train"),           # one rank, more layers than the launch's table holds: a launch per layer
+    (16384, 8, 16, 200, 2, "gelu", "bf16", 0, "train"),        # one rank, 272 weight-gradient tiles per layer: a launch per layer
     (2048, 32, 4, 72, 2, "gelu", "bf16", -1, "no_update"),     # 32 ranks: the reduce-scatter kernel
     (520, 4, 3, 67, 3, "relu", "bf16", 1, "train"),            # k = 3: the shape-agnostic kernels in bf16
     (512, 1, 0, 300, 3, "relu", "bf16", 0, "train"),           # a dense stack
