@@ -1,9 +1,9 @@
 """Turns rocprofv3 output of a bench.py run into the short text summaries kept under profiles/.
 
-    python -m paper_2508_00960_amd.rocprof_summary trace   --workload c4 --dir gpurun_out/prof_c4 --bench gpurun_out/prof_c4.json
-    python -m paper_2508_00960_amd.rocprof_summary traffic --workload c4 --fetch gpurun_out/pmc_fetch_c4 --write gpurun_out/pmc_write_c4 \
-                                                           --bench gpurun_out/pmc_fetch_c4.json
-    python -m paper_2508_00960_amd.rocprof_summary mfma    --workload c4 --dir gpurun_out/pmc_mfma_c4 --bench gpurun_out/pmc_mfma_c4.json
+    python -m paper_2508_00960_amd.rocprof_summary trace   --workload c4 --dir out/prof_c4 --bench out/prof_c4.json
+    python -m paper_2508_00960_amd.rocprof_summary traffic --workload c4 --fetch out/pmc_fetch_c4 --write out/pmc_write_c4 \
+                                                           --bench out/pmc_fetch_c4.json
+    python -m paper_2508_00960_amd.rocprof_summary mfma    --workload c4 --dir out/pmc_mfma_c4 --bench out/pmc_mfma_c4.json
 
 Each mode prints the summary (redirect it into profiles/ffn_step_<workload>_<kind>.txt).  The directories are what
 `rocprofv3 --output-format csv -d <dir> -o <workload>` wrote; --bench is the JSON line bench.py printed in the same
