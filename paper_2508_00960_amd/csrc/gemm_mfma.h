@@ -80,6 +80,20 @@ __device__ __forceinline__ V load_global(const __bf16 *p)
     return *(const __attribute__((address_space(1))) V *)(uintptr_t)p;
 }
 
+// The epilogues' loads and stores, likewise: their pointers come out of parameter blocks, so the compiler would
+// take them for generic ones and use flat instructions (which also count as LDS operations: every wait for an LDS
+// read then waits for all of them).  _nt: streaming (read or written once).
+template <typename V> __device__ __forceinline__ V gload(const void *p) { return *(const __attribute__((address_space(1))) V *)(uintptr_t)p; }
+template <typename V> __device__ __forceinline__ V gload_nt(const void *p)
+{
+    return __builtin_nontemporal_load((const __attribute__((address_space(1))) V *)(uintptr_t)p);
+}
+template <typename V> __device__ __forceinline__ void gstore(void *p, const V &v) { *(__attribute__((address_space(1))) V *)(uintptr_t)p = v; }
+template <typename V> __device__ __forceinline__ void gstore_nt(void *p, const V &v)
+{
+    __builtin_nontemporal_store(v, (__attribute__((address_space(1))) V *)(uintptr_t)p);
+}
+
 // ---- staging one operand tile ---------------------------------------------------------
 // KIND == LD_KC: tile rows = free index r in [r0, r0+128), columns = reduction index c in [c0, c0+64).
 //                The reduction index may decide the region (head block / peer segments); r never does.
@@ -668,22 +682,34 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
     for (int u = 0; u < VEC; ++u) bias_v[u] = (__bf16)0.f;
     if (EPI == EPI_BIAS_ACT && ep.mode == EPI_BIAS_ACT) {
         const int n = n0 + (thread % PER_ROW) * VEC;   // a thread keeps its columns from pass to pass
-        if (n < P.N) bias_v = *(const BfV *)((const __bf16 *)ep.bias + g * ep.bias_g + n);
+        if (n < P.N) bias_v = gload<BfV>((const __bf16 *)ep.bias + g * ep.bias_g + n);
     }
     union AuxU { FlV f; BfV h; unsigned bits; __device__ AuxU() {} };
     constexpr int AUX_PASSES = EPI == EPI_DACT ? PASSES : 1;
     AuxU aux_v[AUX_PASSES];
     if (EPI == EPI_DACT && ep.mode == EPI_DACT && ep.aux) {
+        // One straight run of loads per kind of aux, addresses clamped into the tile's valid part instead of skipped:
+        // with the choice of kind and the bounds test inside the loop every pass was a basic block of its own and
+        // the compiler waited for each pass's load before it issued the next one's (eight memory latencies in a row).
+        int64_t at[AUX_PASSES];
 #pragma unroll
         for (int i = 0; i < AUX_PASSES; ++i) {
             const int v = thread + i * THREADS;
-            const int m = m0 + v / PER_ROW, n = n0 + (v % PER_ROW) * VEC;
-            if (m >= P.M || n >= P.N) continue;
-            const int64_t aux_at = g * ep.aux_g + (int64_t)m * ep.aux_ld + n;
-            if (ep.aux_bits) aux_v[i].bits = ((const uint8_t *)ep.aux)[aux_at >> 3];
-            else if (ep.aux_deriv) aux_v[i].f = __builtin_nontemporal_load((const FlV *)((const float *)ep.aux + aux_at));   // read once
-            else if (ep.aux_f32) aux_v[i].f = *(const FlV *)((const float *)ep.aux + aux_at);
-            else aux_v[i].h = *(const BfV *)((const __bf16 *)ep.aux + aux_at);
+            const int m = min(m0 + v / PER_ROW, P.M - 1), n = min(n0 + (v % PER_ROW) * VEC, P.N - VEC);
+            at[i] = g * ep.aux_g + (int64_t)m * ep.aux_ld + n;
+        }
+        if (ep.aux_bits) {                             // uniform
+#pragma unroll
+            for (int i = 0; i < AUX_PASSES; ++i) aux_v[i].bits = gload<uint8_t>((const uint8_t *)ep.aux + (at[i] >> 3));
+        } else if (ep.aux_deriv) {
+#pragma unroll
+            for (int i = 0; i < AUX_PASSES; ++i) aux_v[i].f = gload_nt<FlV>((const float *)ep.aux + at[i]);   // read once
+        } else if (ep.aux_f32) {
+#pragma unroll
+            for (int i = 0; i < AUX_PASSES; ++i) aux_v[i].f = gload<FlV>((const float *)ep.aux + at[i]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < AUX_PASSES; ++i) aux_v[i].h = gload<BfV>((const __bf16 *)ep.aux + at[i]);
         }
     }
     constexpr int EPI_UNROLL = EPI == EPI_DACT ? PASSES : 2;     // EPI_DACT: unrolled, the prefetched vectors stay in registers
@@ -724,17 +750,17 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
                         FlV a;
 #pragma unroll
                         for (int u = 0; u < VEC; ++u) a[u] = deriv[u];
-                        __builtin_nontemporal_store(a, (FlV *)((float *)ep.aux + aux_at));
+                        gstore_nt<FlV>((float *)ep.aux + aux_at, a);
                     } else if (ep.aux_f32) {
                         FlV a;
 #pragma unroll
                         for (int u = 0; u < VEC; ++u) a[u] = pre[u];
-                        *(FlV *)((float *)ep.aux + aux_at) = a;
+                        gstore<FlV>((float *)ep.aux + aux_at, a);
                     } else {
                         BfV a;
 #pragma unroll
                         for (int u = 0; u < VEC; ++u) a[u] = (__bf16)pre[u];
-                        *(BfV *)((__bf16 *)ep.aux + aux_at) = a;
+                        gstore<BfV>((__bf16 *)ep.aux + aux_at, a);
                     }
                 }
             } else {
@@ -743,17 +769,17 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
                         FlV a;
 #pragma unroll
                         for (int u = 0; u < VEC; ++u) a[u] = act_deriv(ep.act, x[u]);
-                        *(FlV *)((float *)ep.aux + aux_at) = a;
+                        gstore<FlV>((float *)ep.aux + aux_at, a);
                     } else if (ep.aux_f32) {
                         FlV a;
 #pragma unroll
                         for (int u = 0; u < VEC; ++u) a[u] = x[u];
-                        *(FlV *)((float *)ep.aux + aux_at) = a;
+                        gstore<FlV>((float *)ep.aux + aux_at, a);
                     } else {
                         BfV a;
 #pragma unroll
                         for (int u = 0; u < VEC; ++u) a[u] = (__bf16)x[u];
-                        *(BfV *)((__bf16 *)ep.aux + aux_at) = a;
+                        gstore<BfV>((__bf16 *)ep.aux + aux_at, a);
                     }
                 }
 #pragma unroll
@@ -791,7 +817,7 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
                 const int64_t at = dst - (region ? o1 : o0);
                 float *master = (region ? P.sgd.master1 : P.sgd.master0) + g * (region ? P.o.g1 : P.o.g0) + at;
                 __bf16 *w = (region ? P.sgd.w1 : P.sgd.w0) + g * (region ? P.o.g1 : P.o.g0) + at;
-                const FlV before = *(const FlV *)master;     // (requested ahead of the loop like sigma', the launch got 4 % slower)
+                const FlV before = gload<FlV>(master);     // (requested ahead of the loop like sigma', the launch got 4 % slower)
                 FlV after;
                 BfV rounded;
 #pragma unroll
@@ -801,25 +827,25 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
                 }
                 // (the master is next read a step later, by this epilogue; the bf16 copy by the next forward pass, which
                 // found it in the last-level cache before a streaming store put it out of there: 1.8 us per forward launch)
-                __builtin_nontemporal_store(after, (FlV *)master);
-                *(BfV *)w = rounded;
+                gstore_nt<FlV>(master, after);
+                gstore<BfV>(w, rounded);
                 if (!P.sgd.keep_grad) continue;
             }
         }
         // (outputs are written once and read by a later launch at the earliest: a streaming store leaves less for the
         // write-back at the end of the kernel; 0.4 % of configuration 4's step, 2-4 % of the forward-only and small ones)
-        __builtin_nontemporal_store(o, (OutV *)dst);
+        gstore_nt<OutV>(dst, o);
         if constexpr (EPI == EPI_BIAS_ACT && VEC == 8) {
             if (ep.mode == EPI_BIAS_ACT && ep.aux && ep.aux_bits) {     // uniform
                 unsigned bits = 0;
 #pragma unroll
                 for (int u = 0; u < VEC; ++u) bits |= ((float)o[u] > 0.f ? 1u : 0u) << u;
-                ((uint8_t *)ep.aux)[aux_at >> 3] = (uint8_t)bits;
+                gstore<uint8_t>((uint8_t *)ep.aux + (aux_at >> 3), (uint8_t)bits);
             }
         }
         if (EPI == EPI_BIAS_ACT && sizeof(TOut) == 2 && ep.mode == EPI_BIAS_ACT && ep.mse_target) {      // uniform
             // the MSE output error of Eq. (deltaL) from the output as stored, rounded once
-            const BfV t = *(const BfV *)((const __bf16 *)ep.mse_target + aux_at);
+            const BfV t = gload<BfV>((const __bf16 *)ep.mse_target + aux_at);
             BfV dl;
 #pragma unroll
             for (int u = 0; u < VEC; ++u) {
@@ -830,7 +856,7 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
                 dl[u] = (__bf16)e;
                 csum[u] += (float)dl[u];
             }
-            *(BfV *)((__bf16 *)ep.mse_delta + aux_at) = dl;
+            gstore<BfV>((__bf16 *)ep.mse_delta + aux_at, dl);
         } else {
 #pragma unroll
             for (int u = 0; u < VEC; ++u) csum[u] += (float)o[u];
@@ -839,9 +865,9 @@ __device__ __forceinline__ void epilogue_from_lds(const MfmaParams &P, int g, co
     if constexpr (EPI == EPI_STORE && sizeof(TOut) == 4 && VEC == 8) {
         if (P.sgd.bias_master && n0 == 0 && thread < MT && m0 + thread < P.M) {
             const int64_t at = g * (int64_t)P.M + m0 + thread;
-            const float nb = P.sgd.bias_master[at] - P.sgd.lr * P.sgd.bias_grad[at];
-            P.sgd.bias_master[at] = nb;
-            P.sgd.bias_w[at] = (__bf16)nb;
+            const float nb = gload<float>(P.sgd.bias_master + at) - P.sgd.lr * gload<float>(P.sgd.bias_grad + at);
+            gstore<float>(P.sgd.bias_master + at, nb);
+            gstore<__bf16>(P.sgd.bias_w + at, (__bf16)nb);
         }
     }
     if (EPI == EPI_BIAS_ACT && sizeof(TOut) == 2 && ep.mode == EPI_BIAS_ACT && ep.mse_target) {          // uniform
@@ -1022,7 +1048,7 @@ __device__ __forceinline__ void epilogue_pieces_from_lds(const MfmaParams &P, in
         if (P.sgd.master0) {                           // uniform: Section VI's plain SGD on the finished gradient
             float *master = (region ? P.sgd.master1 : P.sgd.master0) + at;
             __bf16 *w = (region ? P.sgd.w1 : P.sgd.w0) + at;
-            const f32x4 m_lo = *(const f32x4 *)master, m_hi = *(const f32x4 *)(master + 4);
+            const f32x4 m_lo = gload<f32x4>(master), m_hi = gload<f32x4>(master + 4);
             float nm[VEC];
             bf16x8 nw;
 #pragma unroll
@@ -1030,13 +1056,13 @@ __device__ __forceinline__ void epilogue_pieces_from_lds(const MfmaParams &P, in
                 nm[u] = (u < 4 ? m_lo[u] : m_hi[u - 4]) - P.sgd.lr * t[i][u];
                 nw[u] = (__bf16)nm[u];
             }
-            *(f32x4 *)master = f32x4{nm[0], nm[1], nm[2], nm[3]};
-            *(f32x4 *)(master + 4) = f32x4{nm[4], nm[5], nm[6], nm[7]};
-            *(bf16x8 *)w = nw;
+            gstore_nt<f32x4>(master, f32x4{nm[0], nm[1], nm[2], nm[3]});
+            gstore_nt<f32x4>(master + 4, f32x4{nm[4], nm[5], nm[6], nm[7]});
+            gstore<bf16x8>(w, nw);
             if (!P.sgd.keep_grad) continue;
         }
-        *(f32x4 *)dst = f32x4{t[i][0], t[i][1], t[i][2], t[i][3]};
-        *(f32x4 *)(dst + 4) = f32x4{t[i][4], t[i][5], t[i][6], t[i][7]};
+        gstore_nt<f32x4>(dst, f32x4{t[i][0], t[i][1], t[i][2], t[i][3]});
+        gstore_nt<f32x4>(dst + 4, f32x4{t[i][4], t[i][5], t[i][6], t[i][7]});
     }
     if (thread == 0) __hip_atomic_store(P.arrived + tile, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
